@@ -1,0 +1,198 @@
+/*
+ * forge.h -- C ABI of the fused transformer decoder-block forward for MI355X (gfx950).
+ *
+ * The library implements the *products* of the paper's two fusion passes as GPU kernels:
+ *   - the fused scaled-dot-product attention op that replaces the chain
+ *     Q.K^T -> scale -> [mask] -> softmax -> .V   (Sec. "Pass 4: Attention Fusion",
+ *     the attention-chain equation and the SDPA equation), taking the UN-transposed K;
+ *   - the fused linear op  matmul -> bias add -> activation  with the weight stored
+ *     [out_features, in_features], and the "matmul + residual add" pattern
+ *     (Sec. "Pass 5: Operator Fusion", the fused-op listing and its four patterns);
+ *   - a launcher that runs one decoder layer as a fixed list of launches with no
+ *     allocation and no host synchronisation, the three properties the paper states for
+ *     its compiled executor (Sec. "Code Generation: CompiledNPUExecutor").
+ *
+ * Conventions for EVERY entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library never
+ *     allocates, frees or synchronises.  Descriptor structs are HOST memory.
+ *   - Tensors are dense, row-major (innermost index last), base pointers 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued asynchronously on it; results are valid after the stream is synchronised.
+ *   - `dt` selects the storage type of all activations, weights, biases and gains of the
+ *     call: FORGE_F32 (fp32 storage, fp32 arithmetic) or FORGE_BF16 (bf16 storage, fp32
+ *     accumulation, one rounding to bf16 at each kernel's store).
+ *   - Return value: FORGE_OK, or an error.  Argument errors are detected on the host
+ *     BEFORE anything is enqueued.  FORGE_ERR_HIP reports a launch failure.
+ *   - `workspace` is caller-provided device scratch of `workspace_bytes` bytes (16-byte
+ *     aligned); the matching *_workspace_bytes() function gives the size needed (may be 0,
+ *     then NULL is accepted).  Too small -> FORGE_ERR_WORKSPACE.
+ *   - No global mutable state; calls on different streams with disjoint buffers are
+ *     independent.  Results are bitwise reproducible run to run (no atomics in reductions).
+ */
+#ifndef FORGE_H_
+#define FORGE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FORGE_OK = 0,
+  FORGE_ERR_INVALID_ARG = 1,   /* NULL / misaligned required pointer, non-positive size   */
+  FORGE_ERR_UNSUPPORTED = 2,   /* a shape or mode the kernels do not cover                */
+  FORGE_ERR_WORKSPACE = 3,     /* workspace missing or too small                          */
+  FORGE_ERR_HIP = 4            /* hipGetLastError() after a launch was not hipSuccess     */
+} forge_status;
+
+typedef enum { FORGE_F32 = 0, FORGE_BF16 = 1 } forge_dtype;
+
+typedef enum {
+  FORGE_ACT_NONE = 0,
+  FORGE_ACT_GELU_TANH = 1,     /* 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))         */
+  FORGE_ACT_RELU = 2,
+  FORGE_ACT_SILU = 3,          /* x / (1 + exp(-x))                                       */
+  FORGE_ACT_SWIGLU = 4         /* silu(gate) * up, gate and up from one [2N,K] weight     */
+} forge_act;
+
+typedef enum { FORGE_NORM_LAYERNORM = 0, FORGE_NORM_RMSNORM = 1 } forge_norm;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* forge_status_string(forge_status s);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int forge_version(void);
+
+/* ---------------------------------------------------------------------------------------
+ * Fused causal scaled-dot-product attention (Sec. "Pass 4: Attention Fusion", SDPA eq.).
+ *
+ *   out[b, i, h*dh : (h+1)*dh] = sum_j P[b,h,i,j] * v[b, g(h), j, :]
+ *   P[b,h,i,:] = softmax_j( mask( scale * q[b,h,i,:] . k[b,g(h),j,:] ) ),  g(h) = h / (Hq/Hkv)
+ *   mask (causal != 0): keys j > i + (kv_len - q_len) are excluded.
+ *
+ * S and P never reach memory (online softmax, fp32).  q: [B,Hq,q_len,dh] dense.
+ * k, v: [B,Hkv,*,dh] with row stride dh and explicit batch / head strides IN ELEMENTS, so the
+ * same call reads a packed prefill tensor or a KV cache with capacity > kv_len.
+ * out: [B,q_len,Hq*dh] dense (heads concatenated per token).  out must not alias q, k, v.
+ * Requirements: Hq % Hkv == 0; dh in {64,128}; q_len >= 1; kv_len >= q_len when causal;
+ * strides multiples of 8 elements.  q_len == 1 takes the split-KV (decode) path, which
+ * needs workspace.
+ * ------------------------------------------------------------------------------------ */
+size_t forge_attn_fused_workspace_bytes(int batch, int q_heads, int kv_heads, int q_len,
+                                        int kv_len, int head_dim, forge_dtype dt);
+
+forge_status forge_attn_fused(const void* q, const void* k, const void* v, void* out,
+                              int batch, int q_heads, int kv_heads, int q_len, int kv_len,
+                              int head_dim, int64_t kv_batch_stride, int64_t kv_head_stride,
+                              float scale, int causal, forge_dtype dt,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Fused linear: y = act(x . w^T + bias) (+ residual)   (Sec. "Pass 5: Operator Fusion").
+ *
+ * x: [M,K]; w: [N,K] ([out_features, in_features]); bias: [N] or NULL; residual: [M,N] or
+ * NULL (may alias y); y: [M,N].  Order on the fp32 accumulator: + bias, activation,
+ * + residual, one rounding to the storage type.
+ * act == FORGE_ACT_SWIGLU: w is [2N,K] (rows 0..N-1 gate, rows N..2N-1 up), bias [2N] or
+ * NULL, y[m,n] = silu(gate[m,n]) * up[m,n].
+ * The name is the paper's "linear+gelu" pattern; act = NONE with a residual is its
+ * "mm+add" pattern, act = RELU / SILU its other two.
+ * Requirements: M,N,K >= 1; K % 8 == 0 for bf16, K % 4 == 0 for fp32.
+ * ------------------------------------------------------------------------------------ */
+size_t forge_gemm_workspace_bytes(int M, int N, int K, forge_act act, forge_dtype dt);
+
+forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias,
+                                  const void* residual, void* y, int M, int N, int K,
+                                  forge_act act, forge_dtype dt,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Fused residual add + normalisation:  h = x (+ delta);  y = Norm(h).
+ *
+ * x, delta (may be NULL), h_out (may be NULL, may alias x), y: [rows,d].  gamma: [d];
+ * beta: [d] or NULL (ignored for RMSNorm).  LayerNorm: biased variance, eps inside the
+ * square root, y = (h-mean)/sqrt(var+eps)*gamma+beta.  RMSNorm: y = h/sqrt(mean(h^2)+eps)*gamma.
+ * The sum is normalised in fp32 BEFORE h_out is rounded to the storage type.
+ * Requirements: d % 8 == 0, 8 <= d <= 16384.
+ * ------------------------------------------------------------------------------------ */
+forge_status forge_residual_norm(const void* x, const void* delta, const void* gamma,
+                                 const void* beta, void* h_out, void* y, int rows, int d,
+                                 float eps, forge_norm kind, forge_dtype dt, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Rotary position embedding, in place, rotate-half pairing (i, i + dh/2):
+ *   theta_i = base^(-2i/dh);  position of row s is pos0 + s.
+ * x: [B,H,*,dh] with batch / head strides in elements and row stride dh; rows
+ * row0 .. row0+n_rows-1 of every (b,h) are rotated (a KV cache passes row0 = pos0).
+ * ------------------------------------------------------------------------------------ */
+forge_status forge_rope(void* x, int batch, int heads, int n_rows, int head_dim,
+                        int64_t batch_stride, int64_t head_stride, int row0, int pos0,
+                        float base, forge_dtype dt, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Token + learned-position embedding:  h[b,s,:] = wte[ids[b,s],:] + wpe[pos0+s,:].
+ * ids: int32 [B,S] (device).  Ids outside [0,vocab) are clamped into range.
+ * ------------------------------------------------------------------------------------ */
+forge_status forge_embed(const int32_t* ids, const void* wte, const void* wpe, void* h,
+                         int batch, int seq, int d, int vocab, int n_pos, int pos0,
+                         forge_dtype dt, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * One pre-norm decoder layer as a fixed launch list:
+ *   y = Norm1(x);  q,k,v = split_heads(y.Wqkv^T + b);  RoPE(q,k) if use_rope;
+ *   k,v -> cache rows pos0..pos0+q_len-1;  o = attention(q, cache[0..pos0+q_len));
+ *   h = x + o.Wo^T + b_o;  m = Norm2(h);  u = act(m.Wup^T + b_up);  x_out = h + u.Wdown^T + b_down
+ * w_qkv rows: Hq*dh query rows, then Hkv*dh key rows, then Hkv*dh value rows.
+ * mlp_act: FORGE_ACT_GELU_TANH (w_up [d_ff,d]) or FORGE_ACT_SWIGLU (w_up [2*d_ff,d]).
+ * Biases and norm shifts may be NULL.  All pointers in the descriptor are device pointers.
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+  int d_model, q_heads, kv_heads, head_dim, d_ff;
+  forge_norm norm;
+  float eps;
+  forge_act mlp_act;
+  int use_rope;
+  float rope_base;
+  forge_dtype dt;
+  const void *norm1_g, *norm1_b, *w_qkv, *b_qkv, *w_o, *b_o;
+  const void *norm2_g, *norm2_b, *w_up, *b_up, *w_down, *b_down;
+} forge_block_desc;
+
+size_t forge_decoder_block_workspace_bytes(const forge_block_desc* desc, int batch, int q_len,
+                                           int kv_cap);
+
+/* x_in, x_out: [B,q_len,d] residual stream (may alias).  k_cache, v_cache: [B,Hkv,kv_cap,dh];
+ * rows pos0..pos0+q_len-1 are written, rows < pos0 are read.  Prefill: pos0 = 0.
+ * Decode: q_len = 1, pos0 = number of cached positions.  pos0 + q_len <= kv_cap. */
+forge_status forge_decoder_block(const forge_block_desc* desc, const void* x_in, void* x_out,
+                                 void* k_cache, void* v_cache, int batch, int q_len, int pos0,
+                                 int kv_cap, void* workspace, size_t workspace_bytes,
+                                 void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Whole model: [embedding ->] L decoder layers -> final norm [-> tied LM head].
+ * The LM head multiplies by the token table itself: one physical tensor serves both uses
+ * (Sec. "Tied Weight Resolution").
+ * layers: HOST array of n_layers descriptors.  wte/wpe NULL: `input` is a hidden state
+ * [B,q_len,d] and `output` receives the final normed hidden state [B,q_len,d]; otherwise
+ * `input` is int32 ids [B,q_len] and `output` receives logits [B,q_len,vocab].
+ * k_cache, v_cache: [n_layers,B,Hkv,kv_cap,dh].
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+  int n_layers, vocab, n_pos;
+  const forge_block_desc* layers;
+  const void *wte, *wpe, *normf_g, *normf_b;
+} forge_model_desc;
+
+size_t forge_model_workspace_bytes(const forge_model_desc* model, int batch, int q_len, int kv_cap);
+
+forge_status forge_model_forward(const forge_model_desc* model, const void* input, void* output,
+                                 void* k_cache, void* v_cache, int batch, int q_len, int pos0,
+                                 int kv_cap, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FORGE_H_ */

@@ -1,0 +1,249 @@
+"""ctypes binding of the forge C ABI (include/forge.h).
+
+Argument marshalling only: every function here takes torch tensors that already
+live on the GPU, passes their device pointers, sizes and the current HIP stream
+to the entry point of the same name, and raises :class:`ForgeError` on a
+non-zero status.  No step of the computation runs in Python or in torch ops.
+The shared library must exist (``python -m paper_2604_16498_amd.build``); there
+is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libforge.so")
+
+FORGE_F32, FORGE_BF16 = 0, 1
+ACT = {"none": 0, "gelu_tanh": 1, "relu": 2, "silu": 3, "swiglu": 4}
+NORM = {"layernorm": 0, "rmsnorm": 1}
+
+
+class ForgeError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, status_string(status)))
+
+
+class BlockDesc(C.Structure):
+    _fields_ = [
+        ("d_model", C.c_int), ("q_heads", C.c_int), ("kv_heads", C.c_int), ("head_dim", C.c_int),
+        ("d_ff", C.c_int), ("norm", C.c_int), ("eps", C.c_float), ("mlp_act", C.c_int),
+        ("use_rope", C.c_int), ("rope_base", C.c_float), ("dt", C.c_int),
+        ("norm1_g", C.c_void_p), ("norm1_b", C.c_void_p), ("w_qkv", C.c_void_p), ("b_qkv", C.c_void_p),
+        ("w_o", C.c_void_p), ("b_o", C.c_void_p), ("norm2_g", C.c_void_p), ("norm2_b", C.c_void_p),
+        ("w_up", C.c_void_p), ("b_up", C.c_void_p), ("w_down", C.c_void_p), ("b_down", C.c_void_p),
+    ]
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int), ("vocab", C.c_int), ("n_pos", C.c_int),
+        ("layers", C.POINTER(BlockDesc)),
+        ("wte", C.c_void_p), ("wpe", C.c_void_p), ("normf_g", C.c_void_p), ("normf_b", C.c_void_p),
+    ]
+
+
+_lib = None
+
+_vp, _i, _f, _sz, _i64 = C.c_void_p, C.c_int, C.c_float, C.c_size_t, C.c_int64
+
+# name -> (restype, argtypes); the single list of what include/forge.h declares
+SIGNATURES = {
+    "forge_status_string": (C.c_char_p, [_i]),
+    "forge_version": (_i, []),
+    "forge_attn_fused_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i, _i]),
+    "forge_attn_fused": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _i, _vp, _sz, _vp]),
+    "forge_gemm_workspace_bytes": (_sz, [_i, _i, _i, _i, _i]),
+    "forge_gemm_bias_gelu": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
+    "forge_residual_norm": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _f, _i, _i, _vp]),
+    "forge_rope": (_i, [_vp, _i, _i, _i, _i, _i64, _i64, _i, _i, _f, _i, _vp]),
+    "forge_embed": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp]),
+    "forge_decoder_block_workspace_bytes": (_sz, [C.POINTER(BlockDesc), _i, _i, _i]),
+    "forge_decoder_block": (_i, [C.POINTER(BlockDesc), _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]),
+    "forge_model_workspace_bytes": (_sz, [C.POINTER(ModelDesc), _i, _i, _i]),
+    "forge_model_forward": (_i, [C.POINTER(ModelDesc), _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]),
+}
+
+
+def lib() -> C.CDLL:
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError("%s is missing: build it with `python -m paper_2604_16498_amd.build`"
+                              % _LIB_PATH)
+        l = C.CDLL(_LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = l
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().forge_status_string(status).decode()
+
+
+def _p(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("forge tensors must be contiguous GPU tensors")
+    return C.c_void_p(t.data_ptr())
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return FORGE_F32
+    if t.dtype == torch.bfloat16:
+        return FORGE_BF16
+    raise ValueError("unsupported dtype %s" % t.dtype)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(t: Optional[torch.Tensor]):
+    return (_p(t), 0 if t is None else t.numel() * t.element_size())
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise ForgeError(status, where)
+
+
+def workspace(nbytes: int, device="cuda") -> Optional[torch.Tensor]:
+    """Device scratch of at least nbytes (None when nothing is needed)."""
+    return None if nbytes == 0 else torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+# ---------------------------------------------------------------------------------------------
+
+
+def forge_attn_fused_workspace_bytes(batch, q_heads, kv_heads, q_len, kv_len, head_dim, dtype) -> int:
+    dt = FORGE_BF16 if dtype == torch.bfloat16 else FORGE_F32
+    return lib().forge_attn_fused_workspace_bytes(batch, q_heads, kv_heads, q_len, kv_len, head_dim, dt)
+
+
+def forge_attn_fused(q, k, v, out, kv_len=None, scale=None, causal=True, workspace=None,
+                     kv_batch_stride=None, kv_head_stride=None):
+    """q [B,Hq,Sq,dh]; k, v [B,Hkv,cap,dh] (cap >= kv_len); out [B,Sq,Hq*dh]."""
+    B, Hq, Sq, dh = q.shape
+    Hkv, cap = k.shape[1], k.shape[2]
+    kv_len = cap if kv_len is None else kv_len
+    scale = dh ** -0.5 if scale is None else scale
+    hs = cap * dh if kv_head_stride is None else kv_head_stride
+    bs = Hkv * hs if kv_batch_stride is None else kv_batch_stride
+    wp, wb = _ws(workspace)
+    _check(lib().forge_attn_fused(_p(q), _p(k), _p(v), _p(out), B, Hq, Hkv, Sq, kv_len, dh, bs, hs,
+                                  scale, int(causal), _dt(q), wp, wb, _stream()), "forge_attn_fused")
+    return out
+
+
+def forge_gemm_workspace_bytes(M, N, K, act, dtype) -> int:
+    dt = FORGE_BF16 if dtype == torch.bfloat16 else FORGE_F32
+    return lib().forge_gemm_workspace_bytes(M, N, K, ACT[act], dt)
+
+
+def forge_gemm_bias_gelu(x, w, bias, residual, y, act="gelu_tanh", workspace=None):
+    """y[M,N] = act(x[M,K] w[N,K]^T + bias) (+ residual); swiglu: w is [2N,K]."""
+    M, K = x.shape
+    N = y.shape[1]
+    wp, wb = _ws(workspace)
+    _check(lib().forge_gemm_bias_gelu(_p(x), _p(w), _p(bias), _p(residual), _p(y), M, N, K, ACT[act],
+                                      _dt(x), wp, wb, _stream()), "forge_gemm_bias_gelu")
+    return y
+
+
+def forge_residual_norm(x, delta, gamma, beta, h_out, y, eps=1e-5, kind="layernorm"):
+    rows, d = x.shape[0] if x.dim() == 2 else x.numel() // x.shape[-1], x.shape[-1]
+    _check(lib().forge_residual_norm(_p(x), _p(delta), _p(gamma), _p(beta), _p(h_out), _p(y), rows, d,
+                                     eps, NORM[kind], _dt(x), _stream()), "forge_residual_norm")
+    return h_out, y
+
+
+def forge_rope(x, n_rows=None, row0=0, pos0=0, base=10000.0):
+    """In place on x [B,H,rows_cap,dh]; rotates rows row0..row0+n_rows-1 at positions pos0.."""
+    B, H, cap, dh = x.shape
+    n_rows = cap - row0 if n_rows is None else n_rows
+    _check(lib().forge_rope(_p(x), B, H, n_rows, dh, H * cap * dh, cap * dh, row0, pos0, base, _dt(x),
+                            _stream()), "forge_rope")
+    return x
+
+
+def forge_embed(ids, wte, wpe, h, pos0=0):
+    B, S = ids.shape
+    _check(lib().forge_embed(_p(ids), _p(wte), _p(wpe), _p(h), B, S, wte.shape[1], wte.shape[0],
+                             wpe.shape[0], pos0, _dt(wte), _stream()), "forge_embed")
+    return h
+
+
+def make_block_desc(shape, w: Dict[str, Optional[torch.Tensor]]) -> BlockDesc:
+    """shape: object with the BlockShape attributes; w: name -> GPU tensor (or None).
+    The returned struct holds raw pointers: keep ``w`` alive while it is in use."""
+    d = BlockDesc()
+    d.d_model, d.q_heads, d.kv_heads, d.head_dim, d.d_ff = (shape.d_model, shape.q_heads,
+                                                            shape.kv_heads, shape.head_dim, shape.d_ff)
+    d.norm = NORM[shape.norm]
+    d.eps = shape.eps
+    d.mlp_act = ACT[shape.mlp_act]
+    d.use_rope = int(shape.use_rope)
+    d.rope_base = shape.rope_base
+    d.dt = _dt(w["w_qkv"])
+    for name in ("norm1_g", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o", "norm2_g", "norm2_b",
+                 "w_up", "b_up", "w_down", "b_down"):
+        t = w.get(name)
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("weight %s must be a contiguous GPU tensor" % name)
+        setattr(d, name, None if t is None else t.data_ptr())
+    return d
+
+
+def forge_decoder_block_workspace_bytes(desc: BlockDesc, batch, q_len, kv_cap) -> int:
+    return lib().forge_decoder_block_workspace_bytes(C.byref(desc), batch, q_len, kv_cap)
+
+
+def forge_decoder_block(desc: BlockDesc, x_in, x_out, k_cache, v_cache, pos0, workspace):
+    """x_in/x_out [B,q_len,d]; caches [B,Hkv,kv_cap,dh]."""
+    B, q_len, _ = x_in.shape
+    kv_cap = k_cache.shape[2]
+    wp, wb = _ws(workspace)
+    _check(lib().forge_decoder_block(C.byref(desc), _p(x_in), _p(x_out), _p(k_cache), _p(v_cache), B,
+                                     q_len, pos0, kv_cap, wp, wb, _stream()), "forge_decoder_block")
+    return x_out
+
+
+def make_model_desc(layer_descs: Sequence[BlockDesc], mw: Dict[str, Optional[torch.Tensor]]) -> ModelDesc:
+    """mw: wte, wpe (both or neither), normf_g, normf_b.  Keeps the layer array alive on the struct."""
+    m = ModelDesc()
+    arr = (BlockDesc * len(layer_descs))(*layer_descs)
+    m._layer_array = arr            # owner
+    m.n_layers = len(layer_descs)
+    m.layers = C.cast(arr, C.POINTER(BlockDesc))
+    wte, wpe = mw.get("wte"), mw.get("wpe")
+    m.vocab = 0 if wte is None else wte.shape[0]
+    m.n_pos = 0 if wpe is None else wpe.shape[0]
+    for name in ("wte", "wpe", "normf_g", "normf_b"):
+        t = mw.get(name)
+        setattr(m, name, None if t is None else t.data_ptr())
+    return m
+
+
+def forge_model_workspace_bytes(model: ModelDesc, batch, q_len, kv_cap) -> int:
+    return lib().forge_model_workspace_bytes(C.byref(model), batch, q_len, kv_cap)
+
+
+def forge_model_forward(model: ModelDesc, inp, out, k_cache, v_cache, pos0, workspace):
+    """inp: int32 ids [B,q_len] (token model) or hidden state [B,q_len,d]; caches [L,B,Hkv,cap,dh]."""
+    B, q_len = inp.shape[0], inp.shape[1]
+    kv_cap = k_cache.shape[3]
+    wp, wb = _ws(workspace)
+    _check(lib().forge_model_forward(C.byref(model), _p(inp), _p(out), _p(k_cache), _p(v_cache), B,
+                                     q_len, pos0, kv_cap, wp, wb, _stream()), "forge_model_forward")
+    return out

@@ -1,0 +1,358 @@
+// C ABI of the forge library: argument checks on the host, then a fixed list of launches on
+// the caller's stream.  Nothing here allocates, frees or synchronises.
+#include "common.hpp"
+
+using namespace forge;
+
+namespace {
+
+inline size_t esize(forge_dtype dt) { return dt == FORGE_BF16 ? 2 : 4; }
+inline bool dtype_ok(forge_dtype dt) { return dt == FORGE_F32 || dt == FORGE_BF16; }
+inline bool req(const void* p) { return p != nullptr && aligned16(p); }
+inline bool opt(const void* p) { return p == nullptr || aligned16(p); }
+
+// carve 256-byte aligned pieces out of one workspace
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base(static_cast<char*>(b)) {}
+  void* take(size_t bytes) {
+    void* p = base ? base + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  }
+};
+
+forge_status attn_dispatch(const AttnArgs& a, forge_dtype dt, hipStream_t s) {
+  if (dt == FORGE_F32) return launch_attn_f32(a, s);
+  if (a.q_len == 1) return launch_attn_decode_bf16(a, s);
+  return launch_attn_prefill_bf16(a, s);
+}
+
+size_t attn_ws(int batch, int q_heads, int kv_heads, int q_len, int kv_len, int head_dim,
+               forge_dtype dt) {
+  if (dt == FORGE_BF16 && q_len == 1)
+    return attn_decode_workspace_bytes(batch, q_heads, kv_heads, kv_len, head_dim);
+  return 0;
+}
+
+size_t gemm_ws(int M, int N, int K, forge_act act, forge_dtype dt) {
+  return dt == FORGE_BF16 ? gemm_bf16_workspace_bytes(M, N, K, act) : gemm_f32_workspace_bytes(M, N, K, act);
+}
+
+forge_status gemm_dispatch(const GemmArgs& a, forge_dtype dt, hipStream_t s) {
+  return dt == FORGE_BF16 ? launch_gemm_bf16(a, s) : launch_gemm_f32(a, s);
+}
+
+forge_status check_block_desc(const forge_block_desc* d) {
+  if (d == nullptr || !dtype_ok(d->dt)) return FORGE_ERR_INVALID_ARG;
+  if (d->d_model < 8 || d->q_heads < 1 || d->kv_heads < 1 || d->d_ff < 8) return FORGE_ERR_INVALID_ARG;
+  if (d->q_heads % d->kv_heads != 0) return FORGE_ERR_INVALID_ARG;
+  if (d->head_dim != 64 && d->head_dim != 128) return FORGE_ERR_UNSUPPORTED;
+  if (d->d_model % 8 != 0 || d->d_ff % 8 != 0 || d->d_model > 16384) return FORGE_ERR_UNSUPPORTED;
+  if (d->mlp_act != FORGE_ACT_GELU_TANH && d->mlp_act != FORGE_ACT_SWIGLU &&
+      d->mlp_act != FORGE_ACT_RELU && d->mlp_act != FORGE_ACT_SILU)
+    return FORGE_ERR_UNSUPPORTED;
+  if (d->norm != FORGE_NORM_LAYERNORM && d->norm != FORGE_NORM_RMSNORM) return FORGE_ERR_INVALID_ARG;
+  if (!req(d->norm1_g) || !req(d->w_qkv) || !req(d->w_o) || !req(d->norm2_g) || !req(d->w_up) ||
+      !req(d->w_down))
+    return FORGE_ERR_INVALID_ARG;
+  if (!opt(d->norm1_b) || !opt(d->b_qkv) || !opt(d->b_o) || !opt(d->norm2_b) || !opt(d->b_up) ||
+      !opt(d->b_down))
+    return FORGE_ERR_INVALID_ARG;
+  if (d->use_rope && !(d->rope_base > 1.0f)) return FORGE_ERR_INVALID_ARG;
+  return FORGE_OK;
+}
+
+struct BlockPlan {
+  size_t y, q, o, u, attn, gemm, total;
+};
+
+BlockPlan plan_block(const forge_block_desc* d, int batch, int q_len, int kv_cap) {
+  const size_t es = esize(d->dt);
+  const size_t T = (size_t)batch * q_len;
+  const int hd = d->q_heads * d->head_dim;
+  const int nqkv = (d->q_heads + 2 * d->kv_heads) * d->head_dim;
+  BlockPlan p;
+  p.y = align_up(T * d->d_model * es, 256);
+  p.q = align_up(T * hd * es, 256);
+  p.o = align_up(T * hd * es, 256);
+  p.u = align_up(T * d->d_ff * es, 256);
+  p.attn = align_up(attn_ws(batch, d->q_heads, d->kv_heads, q_len, kv_cap, d->head_dim, d->dt), 256);
+  size_t g = gemm_ws((int)T, nqkv, d->d_model, FORGE_ACT_NONE, d->dt);
+  g = g > gemm_ws((int)T, d->d_model, hd, FORGE_ACT_NONE, d->dt) ? g : gemm_ws((int)T, d->d_model, hd, FORGE_ACT_NONE, d->dt);
+  g = g > gemm_ws((int)T, d->d_ff, d->d_model, d->mlp_act, d->dt) ? g : gemm_ws((int)T, d->d_ff, d->d_model, d->mlp_act, d->dt);
+  g = g > gemm_ws((int)T, d->d_model, d->d_ff, FORGE_ACT_NONE, d->dt) ? g : gemm_ws((int)T, d->d_model, d->d_ff, FORGE_ACT_NONE, d->dt);
+  p.gemm = align_up(g, 256);
+  p.total = p.y + p.q + p.o + p.u + p.attn + p.gemm;
+  return p;
+}
+
+// the launch list of one layer; all arguments already validated
+forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out, void* k_cache,
+                       void* v_cache, int batch, int q_len, int pos0, int kv_cap, void* workspace,
+                       hipStream_t s) {
+  const BlockPlan pl = plan_block(d, batch, q_len, kv_cap);
+  Carver cv(workspace);
+  void* y = cv.take(pl.y);
+  void* q = cv.take(pl.q);
+  void* o = cv.take(pl.o);
+  void* u = cv.take(pl.u);
+  void* aws = cv.take(pl.attn);
+  void* gws = cv.take(pl.gemm);
+  const int T = batch * q_len;
+  const int dm = d->d_model, dh = d->head_dim, hd = d->q_heads * dh;
+  const int nqkv = (d->q_heads + 2 * d->kv_heads) * dh;
+  const int64_t kv_hs = (int64_t)kv_cap * dh, kv_bs = kv_hs * d->kv_heads;
+  forge_status st;
+
+  // 1. first norm
+  st = launch_residual_norm(x_in, nullptr, d->norm1_g, d->norm1_b, nullptr, y, T, dm, d->eps, d->norm, d->dt, s);
+  if (st != FORGE_OK) return st;
+  // 2. QKV projection, written head-major: q to the workspace, k and v into the cache rows
+  QkvSplit sp = {q, k_cache, v_cache, d->q_heads, d->kv_heads, dh, q_len, kv_cap, pos0};
+  GemmArgs g = {y, d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, FORGE_ACT_NONE, &sp, gws, pl.gemm};
+  st = gemm_dispatch(g, d->dt, s);
+  if (st != FORGE_OK) return st;
+  // 3. rotary embedding of the new q and k rows
+  if (d->use_rope) {
+    st = launch_rope(q, batch, d->q_heads, q_len, dh, (int64_t)d->q_heads * q_len * dh,
+                     (int64_t)q_len * dh, 0, pos0, d->rope_base, d->dt, s);
+    if (st != FORGE_OK) return st;
+    st = launch_rope(k_cache, batch, d->kv_heads, q_len, dh, kv_bs, kv_hs, pos0, pos0, d->rope_base, d->dt, s);
+    if (st != FORGE_OK) return st;
+  }
+  // 4. fused causal attention over cache rows [0, pos0 + q_len)
+  AttnArgs at = {q, k_cache, v_cache, o, batch, d->q_heads, d->kv_heads, q_len, pos0 + q_len, dh,
+                 kv_bs, kv_hs, 1.0f / sqrtf((float)dh), 1, aws, pl.attn};
+  st = attn_dispatch(at, d->dt, s);
+  if (st != FORGE_OK) return st;
+  // 5. output projection + bias + residual
+  g = GemmArgs{o, d->w_o, d->b_o, x_in, x_out, T, dm, hd, FORGE_ACT_NONE, nullptr, gws, pl.gemm};
+  st = gemm_dispatch(g, d->dt, s);
+  if (st != FORGE_OK) return st;
+  // 6. second norm
+  st = launch_residual_norm(x_out, nullptr, d->norm2_g, d->norm2_b, nullptr, y, T, dm, d->eps, d->norm, d->dt, s);
+  if (st != FORGE_OK) return st;
+  // 7. MLP up projection + bias + activation (SwiGLU: gate and up in one pass)
+  g = GemmArgs{y, d->w_up, d->b_up, nullptr, u, T, d->d_ff, dm, d->mlp_act, nullptr, gws, pl.gemm};
+  st = gemm_dispatch(g, d->dt, s);
+  if (st != FORGE_OK) return st;
+  // 8. MLP down projection + bias + residual
+  g = GemmArgs{u, d->w_down, d->b_down, x_out, x_out, T, dm, d->d_ff, FORGE_ACT_NONE, nullptr, gws, pl.gemm};
+  return gemm_dispatch(g, d->dt, s);
+}
+
+struct ModelPlan {
+  size_t h, yf, block, total;
+};
+
+ModelPlan plan_model(const forge_model_desc* m, int batch, int q_len, int kv_cap) {
+  const forge_block_desc* d0 = &m->layers[0];
+  const size_t es = esize(d0->dt);
+  const size_t T = (size_t)batch * q_len;
+  ModelPlan p;
+  p.h = align_up(T * d0->d_model * es, 256);
+  p.yf = m->wte != nullptr ? align_up(T * d0->d_model * es, 256) : 0;
+  p.block = 0;
+  for (int l = 0; l < m->n_layers; ++l) {
+    const size_t b = plan_block(&m->layers[l], batch, q_len, kv_cap).total;
+    p.block = b > p.block ? b : p.block;
+  }
+  const size_t head = m->wte != nullptr ? align_up(gemm_ws((int)T, m->vocab, d0->d_model, FORGE_ACT_NONE, d0->dt), 256) : 0;
+  p.block = head > p.block ? head : p.block;
+  p.total = p.h + p.yf + p.block;
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* forge_status_string(forge_status s) {
+  switch (s) {
+    case FORGE_OK: return "FORGE_OK";
+    case FORGE_ERR_INVALID_ARG: return "FORGE_ERR_INVALID_ARG";
+    case FORGE_ERR_UNSUPPORTED: return "FORGE_ERR_UNSUPPORTED";
+    case FORGE_ERR_WORKSPACE: return "FORGE_ERR_WORKSPACE";
+    case FORGE_ERR_HIP: return "FORGE_ERR_HIP";
+  }
+  return "FORGE_ERR_UNKNOWN";
+}
+
+int forge_version(void) { return 100; }
+
+size_t forge_attn_fused_workspace_bytes(int batch, int q_heads, int kv_heads, int q_len, int kv_len,
+                                        int head_dim, forge_dtype dt) {
+  if (batch < 1 || q_heads < 1 || kv_heads < 1 || q_len < 1 || kv_len < 1) return 0;
+  return attn_ws(batch, q_heads, kv_heads, q_len, kv_len, head_dim, dt);
+}
+
+forge_status forge_attn_fused(const void* q, const void* k, const void* v, void* out, int batch,
+                              int q_heads, int kv_heads, int q_len, int kv_len, int head_dim,
+                              int64_t kv_batch_stride, int64_t kv_head_stride, float scale,
+                              int causal, forge_dtype dt, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  if (!dtype_ok(dt) || !req(q) || !req(k) || !req(v) || !req(out) || !opt(workspace))
+    return FORGE_ERR_INVALID_ARG;
+  if (batch < 1 || q_heads < 1 || kv_heads < 1 || q_len < 1 || kv_len < 1) return FORGE_ERR_INVALID_ARG;
+  if (q_heads % kv_heads != 0) return FORGE_ERR_INVALID_ARG;
+  if (causal && kv_len < q_len) return FORGE_ERR_INVALID_ARG;
+  if (head_dim != 64 && head_dim != 128) return FORGE_ERR_UNSUPPORTED;
+  if (kv_head_stride < (int64_t)kv_len * head_dim || kv_batch_stride < kv_head_stride * kv_heads)
+    return FORGE_ERR_INVALID_ARG;
+  if (kv_head_stride % 8 != 0 || kv_batch_stride % 8 != 0) return FORGE_ERR_INVALID_ARG;
+  if (out == q || out == k || out == v) return FORGE_ERR_INVALID_ARG;
+  const size_t need = attn_ws(batch, q_heads, kv_heads, q_len, kv_len, head_dim, dt);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FORGE_ERR_WORKSPACE;
+  AttnArgs a = {q, k, v, out, batch, q_heads, kv_heads, q_len, kv_len, head_dim,
+                kv_batch_stride, kv_head_stride, scale, causal, workspace, workspace_bytes};
+  return attn_dispatch(a, dt, static_cast<hipStream_t>(stream));
+}
+
+size_t forge_gemm_workspace_bytes(int M, int N, int K, forge_act act, forge_dtype dt) {
+  if (M < 1 || N < 1 || K < 1) return 0;
+  return gemm_ws(M, N, K, act, dt);
+}
+
+forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias,
+                                  const void* residual, void* y, int M, int N, int K, forge_act act,
+                                  forge_dtype dt, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+  if (!dtype_ok(dt) || !req(x) || !req(w) || !req(y) || !opt(bias) || !opt(residual) || !opt(workspace))
+    return FORGE_ERR_INVALID_ARG;
+  if (M < 1 || N < 1 || K < 1) return FORGE_ERR_INVALID_ARG;
+  if (act < FORGE_ACT_NONE || act > FORGE_ACT_SWIGLU) return FORGE_ERR_INVALID_ARG;
+  if (K % (dt == FORGE_BF16 ? 8 : 4) != 0) return FORGE_ERR_UNSUPPORTED;
+  if (y == x || y == w) return FORGE_ERR_INVALID_ARG;
+  const size_t need = gemm_ws(M, N, K, act, dt);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FORGE_ERR_WORKSPACE;
+  GemmArgs a = {x, w, bias, residual, y, M, N, K, act, nullptr, workspace, workspace_bytes};
+  return gemm_dispatch(a, dt, static_cast<hipStream_t>(stream));
+}
+
+forge_status forge_residual_norm(const void* x, const void* delta, const void* gamma,
+                                 const void* beta, void* h_out, void* y, int rows, int d, float eps,
+                                 forge_norm kind, forge_dtype dt, void* stream) {
+  if (!dtype_ok(dt) || !req(x) || !req(gamma) || !req(y) || !opt(delta) || !opt(beta) || !opt(h_out))
+    return FORGE_ERR_INVALID_ARG;
+  if (rows < 1 || d < 1 || !(eps >= 0.f)) return FORGE_ERR_INVALID_ARG;
+  if (kind != FORGE_NORM_LAYERNORM && kind != FORGE_NORM_RMSNORM) return FORGE_ERR_INVALID_ARG;
+  if (d % 8 != 0 || d > 16384) return FORGE_ERR_UNSUPPORTED;
+  if (y == x || (h_out != nullptr && h_out == y)) return FORGE_ERR_INVALID_ARG;
+  return launch_residual_norm(x, delta, gamma, beta, h_out, y, rows, d, eps, kind, dt,
+                              static_cast<hipStream_t>(stream));
+}
+
+forge_status forge_rope(void* x, int batch, int heads, int n_rows, int head_dim,
+                        int64_t batch_stride, int64_t head_stride, int row0, int pos0, float base,
+                        forge_dtype dt, void* stream) {
+  if (!dtype_ok(dt) || !req(x)) return FORGE_ERR_INVALID_ARG;
+  if (batch < 1 || heads < 1 || n_rows < 1 || row0 < 0 || pos0 < 0 || !(base > 1.0f))
+    return FORGE_ERR_INVALID_ARG;
+  if (head_dim < 16 || head_dim % 16 != 0) return FORGE_ERR_UNSUPPORTED;
+  if (head_stride < (int64_t)(row0 + n_rows) * head_dim || batch_stride < head_stride * heads)
+    return FORGE_ERR_INVALID_ARG;
+  if (head_stride % 8 != 0 || batch_stride % 8 != 0) return FORGE_ERR_INVALID_ARG;
+  return launch_rope(x, batch, heads, n_rows, head_dim, batch_stride, head_stride, row0, pos0, base,
+                     dt, static_cast<hipStream_t>(stream));
+}
+
+forge_status forge_embed(const int32_t* ids, const void* wte, const void* wpe, void* h, int batch,
+                         int seq, int d, int vocab, int n_pos, int pos0, forge_dtype dt,
+                         void* stream) {
+  if (!dtype_ok(dt) || ids == nullptr || !req(wte) || !req(wpe) || !req(h)) return FORGE_ERR_INVALID_ARG;
+  if (batch < 1 || seq < 1 || d < 1 || vocab < 1 || pos0 < 0 || pos0 + seq > n_pos)
+    return FORGE_ERR_INVALID_ARG;
+  if (d % 8 != 0) return FORGE_ERR_UNSUPPORTED;
+  return launch_embed(ids, wte, wpe, h, batch, seq, d, vocab, n_pos, pos0, dt,
+                      static_cast<hipStream_t>(stream));
+}
+
+size_t forge_decoder_block_workspace_bytes(const forge_block_desc* desc, int batch, int q_len,
+                                           int kv_cap) {
+  if (check_block_desc(desc) != FORGE_OK || batch < 1 || q_len < 1 || kv_cap < q_len) return 0;
+  return plan_block(desc, batch, q_len, kv_cap).total;
+}
+
+forge_status forge_decoder_block(const forge_block_desc* desc, const void* x_in, void* x_out,
+                                 void* k_cache, void* v_cache, int batch, int q_len, int pos0,
+                                 int kv_cap, void* workspace, size_t workspace_bytes, void* stream) {
+  forge_status st = check_block_desc(desc);
+  if (st != FORGE_OK) return st;
+  if (!req(x_in) || !req(x_out) || !req(k_cache) || !req(v_cache) || !req(workspace))
+    return FORGE_ERR_INVALID_ARG;
+  if (batch < 1 || q_len < 1 || pos0 < 0 || pos0 + q_len > kv_cap) return FORGE_ERR_INVALID_ARG;
+  if (workspace_bytes < plan_block(desc, batch, q_len, kv_cap).total) return FORGE_ERR_WORKSPACE;
+  return run_block(desc, x_in, x_out, k_cache, v_cache, batch, q_len, pos0, kv_cap, workspace,
+                   static_cast<hipStream_t>(stream));
+}
+
+static forge_status check_model(const forge_model_desc* m) {
+  if (m == nullptr || m->n_layers < 1 || m->layers == nullptr) return FORGE_ERR_INVALID_ARG;
+  for (int l = 0; l < m->n_layers; ++l) {
+    forge_status st = check_block_desc(&m->layers[l]);
+    if (st != FORGE_OK) return st;
+    const forge_block_desc *a = &m->layers[l], *b = &m->layers[0];
+    if (a->d_model != b->d_model || a->dt != b->dt || a->kv_heads != b->kv_heads ||
+        a->head_dim != b->head_dim)
+      return FORGE_ERR_UNSUPPORTED;
+  }
+  if (!req(m->normf_g) || !opt(m->normf_b)) return FORGE_ERR_INVALID_ARG;
+  if ((m->wte == nullptr) != (m->wpe == nullptr)) return FORGE_ERR_INVALID_ARG;
+  if (m->wte != nullptr && (!req(m->wte) || !req(m->wpe) || m->vocab < 1 || m->n_pos < 1))
+    return FORGE_ERR_INVALID_ARG;
+  return FORGE_OK;
+}
+
+size_t forge_model_workspace_bytes(const forge_model_desc* model, int batch, int q_len, int kv_cap) {
+  if (check_model(model) != FORGE_OK || batch < 1 || q_len < 1 || kv_cap < q_len) return 0;
+  return plan_model(model, batch, q_len, kv_cap).total;
+}
+
+forge_status forge_model_forward(const forge_model_desc* model, const void* input, void* output,
+                                 void* k_cache, void* v_cache, int batch, int q_len, int pos0,
+                                 int kv_cap, void* workspace, size_t workspace_bytes, void* stream) {
+  forge_status st = check_model(model);
+  if (st != FORGE_OK) return st;
+  if (input == nullptr || !req(output) || !req(k_cache) || !req(v_cache) || !req(workspace))
+    return FORGE_ERR_INVALID_ARG;
+  if (batch < 1 || q_len < 1 || pos0 < 0 || pos0 + q_len > kv_cap) return FORGE_ERR_INVALID_ARG;
+  const bool tokens = model->wte != nullptr;
+  if (tokens && pos0 + q_len > model->n_pos) return FORGE_ERR_INVALID_ARG;
+  if (!tokens && !aligned16(input)) return FORGE_ERR_INVALID_ARG;
+  const ModelPlan pl = plan_model(model, batch, q_len, kv_cap);
+  if (workspace_bytes < pl.total) return FORGE_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const forge_block_desc* d0 = &model->layers[0];
+  const forge_dtype dt = d0->dt;
+  const int T = batch * q_len, dm = d0->d_model;
+  Carver cv(workspace);
+  void* h = cv.take(pl.h);
+  void* yf = tokens ? cv.take(pl.yf) : output;
+  void* bws = cv.take(pl.block);
+  const size_t layer_kv_bytes = (size_t)batch * d0->kv_heads * kv_cap * d0->head_dim * esize(dt);
+
+  const void* x = input;
+  if (tokens) {
+    st = launch_embed(static_cast<const int32_t*>(input), model->wte, model->wpe, h, batch, q_len,
+                      dm, model->vocab, model->n_pos, pos0, dt, s);
+    if (st != FORGE_OK) return st;
+    x = h;
+  }
+  for (int l = 0; l < model->n_layers; ++l) {
+    st = run_block(&model->layers[l], x, h, static_cast<char*>(k_cache) + l * layer_kv_bytes,
+                   static_cast<char*>(v_cache) + l * layer_kv_bytes, batch, q_len, pos0, kv_cap, bws, s);
+    if (st != FORGE_OK) return st;
+    x = h;
+  }
+  st = launch_residual_norm(h, nullptr, model->normf_g, model->normf_b, nullptr, yf, T, dm, d0->eps,
+                            d0->norm, dt, s);
+  if (st != FORGE_OK || !tokens) return st;
+  // tied LM head: the token table is the weight of the last projection
+  GemmArgs g = {yf, model->wte, nullptr, nullptr, output, T, model->vocab, dm, FORGE_ACT_NONE,
+                nullptr, bws, pl.block};
+  return gemm_dispatch(g, dt, s);
+}
+
+}  // extern "C"

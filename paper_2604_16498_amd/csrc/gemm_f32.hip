@@ -1,0 +1,146 @@
+// fp32 fused linear:  y = act(x . w^T + bias) (+ residual), true fp32 operands on the fp32
+// matrix cores (v_mfma_f32_32x32x2_f32), so the result stays within fp32 rounding of the
+// definition (no reduced-precision operand shortcut).
+//
+// Tiling: a 256-thread block (4 waves as 2 x 2) owns a 64 x 64 tile of y; each wave owns a
+// 32 x 32 accumulator.  K is walked in slabs of 32: the x slab [64,32] and the w slab [64,32]
+// (both K-contiguous in memory) are copied to LDS with 128-bit accesses, rows padded to 36
+// floats so that eight lanes reading the same column chunk of eight consecutive rows hit
+// disjoint banks.  The MFMA contracts two k per issue (lanes 0-31 supply one, lanes 32-63 the
+// other); lanes 0-31 walk k = 0..15 of the slab and lanes 32-63 walk k = 16..31, so every
+// lane reads four consecutive floats per 128-bit LDS read.
+#include "common.hpp"
+
+namespace forge {
+namespace {
+
+constexpr int BM = 64, BN = 64, BK = 32, LDK = BK + 4;
+
+__device__ inline void* split_dst(const QkvSplit& sp, int m, int n, size_t esz) {
+  const int dh = sp.head_dim;
+  const int b = m / sp.q_len, s = m % sp.q_len;
+  const int nq = sp.q_heads * dh, nk = sp.kv_heads * dh;
+  if (n < nq) {
+    const int h = n / dh;
+    return (char*)sp.q + ((((int64_t)b * sp.q_heads + h) * sp.q_len + s) * dh + n % dh) * esz;
+  }
+  const bool is_k = n < nq + nk;
+  const int nn = is_k ? n - nq : n - nq - nk;
+  const int h = nn / dh;
+  char* basep = (char*)(is_k ? sp.k_cache : sp.v_cache);
+  return basep + ((((int64_t)b * sp.kv_heads + h) * sp.kv_cap + sp.pos0 + s) * dh + nn % dh) * esz;
+}
+
+template <int ACT, bool SPLIT>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(
+    const float* __restrict__ x, const float* __restrict__ w, const float* __restrict__ bias,
+    const float* residual, float* y, int M, int N, int K, QkvSplit sp) {
+  constexpr bool SWIGLU = ACT == FORGE_ACT_SWIGLU;
+  constexpr int NB = SWIGLU ? 2 : 1;
+  __shared__ __attribute__((aligned(16))) float As[BM][LDK];
+  __shared__ __attribute__((aligned(16))) float Bs[NB][BN][LDK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+  floatx16 acc[NB];
+#pragma unroll
+  for (int t = 0; t < NB; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+
+  const int lrow = tid >> 3;        // 0..31
+  const int lcol = (tid & 7) * 4;   // 0,4,..,28
+
+  for (int k0 = 0; k0 < K; k0 += BK) {
+    // global -> LDS (zero fill outside the matrix)
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int row = lrow + 32 * r;
+      const int kk = k0 + lcol;
+      floatx4 va = {0.f, 0.f, 0.f, 0.f};
+      if (m0 + row < M && kk < K) va = *reinterpret_cast<const floatx4*>(x + (int64_t)(m0 + row) * K + kk);
+      *reinterpret_cast<floatx4*>(&As[row][lcol]) = va;
+#pragma unroll
+      for (int t = 0; t < NB; ++t) {
+        floatx4 vb = {0.f, 0.f, 0.f, 0.f};
+        if (n0 + row < N && kk < K)
+          vb = *reinterpret_cast<const floatx4*>(w + (int64_t)(n0 + row + t * N) * K + kk);
+        *reinterpret_cast<floatx4*>(&Bs[t][row][lcol]) = vb;
+      }
+    }
+    __syncthreads();
+    const int r = lane & 31, hk = (lane >> 5) * 16;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const floatx4 a = *reinterpret_cast<const floatx4*>(&As[wm * 32 + r][hk + 4 * j]);
+      floatx4 b[NB];
+#pragma unroll
+      for (int t = 0; t < NB; ++t) b[t] = *reinterpret_cast<const floatx4*>(&Bs[t][wn * 32 + r][hk + 4 * j]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int t = 0; t < NB; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], b[t][e], acc[t], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // epilogue on the accumulator: + bias, activation, + residual, store
+  const int n = n0 + wn * 32 + (lane & 31);
+  if (n >= N) return;
+  float bv = 0.f, bv2 = 0.f;
+  if (bias != nullptr) {
+    bv = bias[n];
+    if (SWIGLU) bv2 = bias[n + N];
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int m = m0 + wm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+    if (m >= M) continue;
+    float val = acc[0][v] + bv;
+    if (SWIGLU) val = silu_f(val) * (acc[NB - 1][v] + bv2);
+    else val = apply_act<ACT>(val);
+    if (SPLIT) {
+      *reinterpret_cast<float*>(split_dst(sp, m, n, sizeof(float))) = val;
+    } else {
+      if (residual != nullptr) val += residual[(int64_t)m * N + n];
+      y[(int64_t)m * N + n] = val;
+    }
+  }
+}
+
+}  // namespace
+
+size_t gemm_f32_workspace_bytes(int, int, int, forge_act) { return 0; }
+
+forge_status launch_gemm_f32(const GemmArgs& a, hipStream_t s) {
+  dim3 grid(ceil_div(a.N, BN), ceil_div(a.M, BM)), block(256);
+  const float* x = (const float*)a.x;
+  const float* w = (const float*)a.w;
+  const float* bias = (const float*)a.bias;
+  const float* res = (const float*)a.residual;
+  float* y = (float*)a.y;
+  QkvSplit sp = {};
+  if (a.split != nullptr) {
+    if (a.act != FORGE_ACT_NONE || a.residual != nullptr) return FORGE_ERR_UNSUPPORTED;
+    sp = *a.split;
+    gemm_f32_kernel<FORGE_ACT_NONE, true><<<grid, block, 0, s>>>(x, w, bias, res, y, a.M, a.N, a.K, sp);
+    return launch_status();
+  }
+  switch (a.act) {
+#define FORGE_CASE(ACT) \
+  case ACT: gemm_f32_kernel<ACT, false><<<grid, block, 0, s>>>(x, w, bias, res, y, a.M, a.N, a.K, sp); break
+    FORGE_CASE(FORGE_ACT_NONE);
+    FORGE_CASE(FORGE_ACT_GELU_TANH);
+    FORGE_CASE(FORGE_ACT_RELU);
+    FORGE_CASE(FORGE_ACT_SILU);
+    FORGE_CASE(FORGE_ACT_SWIGLU);
+#undef FORGE_CASE
+    default: return FORGE_ERR_INVALID_ARG;
+  }
+  return launch_status();
+}
+
+}  // namespace forge

@@ -1,0 +1,143 @@
+// Fused residual add + LayerNorm / RMSNorm.
+//
+// HBM-bound: every element of x (and delta) is read once and h, y are written once.  A row is
+// held in registers as fp32 between the read and the two writes, so the mean, the centred
+// variance and the normalisation all run without a second pass over memory.
+//
+// Two launch shapes:
+//   - d <= 1024: one 64-lane wave per row (4 rows per 256-thread block), reductions by
+//     cross-lane shuffles only;
+//   - d  > 1024: one 256-thread block per row, wave shuffles then a 4-entry LDS exchange.
+// Each lane owns CH chunks of 8 consecutive elements (one 128-bit access for bf16, two for
+// fp32), chunk c of lane l covers elements 8*(l + c*G) .. +8 with G lanes per row, so that
+// consecutive lanes touch consecutive 16 B.
+#include "common.hpp"
+
+namespace forge {
+namespace {
+
+template <typename T, int CH, int G, bool RMS>
+__global__ __launch_bounds__(256) void residual_norm_kernel(
+    const T* __restrict__ x, const T* __restrict__ delta, const T* __restrict__ gamma,
+    const T* __restrict__ beta, T* __restrict__ h_out, T* __restrict__ y, int rows, int d,
+    float eps) {
+  constexpr int ROWS_PER_BLOCK = 256 / G;
+  const int tid = threadIdx.x;
+  const int lane_in_row = tid % G;
+  const int row = blockIdx.x * ROWS_PER_BLOCK + tid / G;
+  const bool row_ok = row < rows;   // G == 256: uniform per block; G == 64: uniform per wave
+  __shared__ float red[4];
+
+  float v[CH][8];
+  const int64_t base = (int64_t)row * d;
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < CH; ++c) {
+    const int e = 8 * (lane_in_row + c * G);
+    if (row_ok && e < d) {
+      Vec8<T>::load(x + base + e, v[c]);
+      if (delta != nullptr) {
+        float t[8];
+        Vec8<T>::load(delta + base + e, t);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[c][i] += t[i];
+      }
+      if (h_out != nullptr) Vec8<T>::store(h_out + base + e, v[c]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sum += RMS ? v[c][i] * v[c][i] : v[c][i];
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[c][i] = 0.f;
+    }
+  }
+
+  auto row_sum = [&](float s) -> float {
+    s = wave_sum(s);
+    if (G == 256) {
+      __syncthreads();            // protects red[] between the two uses
+      if ((tid & 63) == 0) red[tid >> 6] = s;
+      __syncthreads();
+      s = red[0] + red[1] + red[2] + red[3];
+    }
+    return s;
+  };
+
+  const float inv_d = 1.0f / (float)d;
+  float mean = 0.f, rstd;
+  if (RMS) {
+    rstd = rsqrtf(row_sum(sum) * inv_d + eps);
+  } else {
+    mean = row_sum(sum) * inv_d;
+    float sq = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int e = 8 * (lane_in_row + c * G);
+      if (e < d) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { float t = v[c][i] - mean; sq += t * t; }
+      }
+    }
+    rstd = rsqrtf(row_sum(sq) * inv_d + eps);
+  }
+
+#pragma unroll
+  for (int c = 0; c < CH; ++c) {
+    const int e = 8 * (lane_in_row + c * G);
+    if (row_ok && e < d) {
+      float g[8], o[8];
+      Vec8<T>::load(gamma + e, g);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = (v[c][i] - mean) * rstd * g[i];
+      if (!RMS && beta != nullptr) {
+        float b[8];
+        Vec8<T>::load(beta + e, b);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] += b[i];
+      }
+      Vec8<T>::store(y + base + e, o);
+    }
+  }
+}
+
+template <typename T, int CH, int G>
+forge_status launch_g(const void* x, const void* delta, const void* gamma, const void* beta,
+                      void* h_out, void* y, int rows, int d, float eps, forge_norm kind,
+                      hipStream_t s) {
+  const int rows_per_block = 256 / G;
+  dim3 grid(ceil_div(rows, rows_per_block)), block(256);
+  if (kind == FORGE_NORM_RMSNORM)
+    residual_norm_kernel<T, CH, G, true><<<grid, block, 0, s>>>(
+        (const T*)x, (const T*)delta, (const T*)gamma, (const T*)beta, (T*)h_out, (T*)y, rows, d, eps);
+  else
+    residual_norm_kernel<T, CH, G, false><<<grid, block, 0, s>>>(
+        (const T*)x, (const T*)delta, (const T*)gamma, (const T*)beta, (T*)h_out, (T*)y, rows, d, eps);
+  return launch_status();
+}
+
+template <typename T>
+forge_status launch_t(const void* x, const void* delta, const void* gamma, const void* beta,
+                      void* h_out, void* y, int rows, int d, float eps, forge_norm kind,
+                      hipStream_t s) {
+  const int chunks = d / 8;
+#define FORGE_NORM_CASE(CH, G) \
+  return launch_g<T, CH, G>(x, delta, gamma, beta, h_out, y, rows, d, eps, kind, s)
+  if (chunks <= 64) FORGE_NORM_CASE(1, 64);
+  if (chunks <= 128) FORGE_NORM_CASE(2, 64);
+  if (chunks <= 256) FORGE_NORM_CASE(1, 256);
+  if (chunks <= 512) FORGE_NORM_CASE(2, 256);
+  if (chunks <= 1024) FORGE_NORM_CASE(4, 256);
+  if (chunks <= 2048) FORGE_NORM_CASE(8, 256);
+#undef FORGE_NORM_CASE
+  return FORGE_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+forge_status launch_residual_norm(const void* x, const void* delta, const void* gamma,
+                                  const void* beta, void* h_out, void* y, int rows, int d,
+                                  float eps, forge_norm kind, forge_dtype dt, hipStream_t s) {
+  if (dt == FORGE_BF16) return launch_t<bf16>(x, delta, gamma, beta, h_out, y, rows, d, eps, kind, s);
+  return launch_t<float>(x, delta, gamma, beta, h_out, y, rows, d, eps, kind, s);
+}
+
+}  // namespace forge

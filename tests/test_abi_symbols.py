@@ -1,0 +1,75 @@
+"""The C-ABI library loads, exports every function include/forge.h declares, and rejects bad
+arguments on the host before any launch (so these calls are safe without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "forge.h")
+LIB = os.path.join(ROOT, "paper_2604_16498_amd", "libforge.so")
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(forge_[a-z_0-9]+)\s*\(", src)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2604_16498_amd import build
+        build.build(verbose=False)
+    return C.CDLL(LIB)
+
+
+def test_header_declares_the_four_named_calls():
+    names = declared_functions()
+    for n in ("forge_attn_fused", "forge_gemm_bias_gelu", "forge_residual_norm", "forge_decoder_block"):
+        assert n in names
+
+
+def test_every_declared_symbol_is_exported_and_bound(lib):
+    from paper_2604_16498_amd import binding
+    names = declared_functions()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), "library does not export %s" % n
+        assert n in binding.SIGNATURES, "binding has no signature for %s" % n
+    assert sorted(binding.SIGNATURES) == names
+
+
+def test_status_strings(lib):
+    lib.forge_status_string.restype = C.c_char_p
+    got = [lib.forge_status_string(i).decode() for i in range(5)]
+    assert got == ["FORGE_OK", "FORGE_ERR_INVALID_ARG", "FORGE_ERR_UNSUPPORTED",
+                   "FORGE_ERR_WORKSPACE", "FORGE_ERR_HIP"]
+
+
+def test_argument_errors_are_caught_on_the_host():
+    from paper_2604_16498_amd import binding as B
+    l = B.lib()
+    vp = C.c_void_p
+    good = vp(0x1000)            # aligned, never dereferenced: every call below fails its checks first
+    odd = vp(0x1004)
+    # NULL / misaligned pointers
+    assert l.forge_residual_norm(None, None, good, None, None, good, 4, 64, 1e-5, 0, 0, None) == 1
+    assert l.forge_residual_norm(odd, None, good, None, None, good, 4, 64, 1e-5, 0, 0, None) == 1
+    # unsupported width, bad sizes
+    assert l.forge_residual_norm(good, None, good, None, None, vp(0x2000), 4, 60, 1e-5, 0, 0, None) == 2
+    assert l.forge_residual_norm(good, None, good, None, None, vp(0x2000), 0, 64, 1e-5, 0, 0, None) == 1
+    # gemm: K not a multiple of 8 for bf16; y aliasing x
+    assert l.forge_gemm_bias_gelu(good, vp(0x2000), None, None, vp(0x3000), 4, 4, 12, 0, 1, None, 0, None) == 2
+    assert l.forge_gemm_bias_gelu(good, vp(0x2000), None, None, good, 4, 4, 16, 0, 1, None, 0, None) == 1
+    assert l.forge_gemm_bias_gelu(good, vp(0x2000), None, None, vp(0x3000), 4, 4, 16, 9, 1, None, 0, None) == 1
+    # attention: head dim, head ratio, causal with kv_len < q_len
+    a = (good, vp(0x2000), vp(0x3000), vp(0x4000))
+    assert l.forge_attn_fused(*a, 1, 4, 4, 8, 8, 32, 4 * 8 * 32, 8 * 32, 0.1, 1, 1, None, 0, None) == 2
+    assert l.forge_attn_fused(*a, 1, 4, 3, 8, 8, 64, 3 * 8 * 64, 8 * 64, 0.1, 1, 1, None, 0, None) == 1
+    assert l.forge_attn_fused(*a, 1, 4, 4, 8, 4, 64, 4 * 4 * 64, 4 * 64, 0.1, 1, 1, None, 0, None) == 1
+    # block: NULL descriptor; workspace size of an invalid descriptor is 0
+    assert l.forge_decoder_block(None, good, good, good, good, 1, 1, 0, 1, good, 0, None) == 1
+    d = B.BlockDesc()
+    assert l.forge_decoder_block_workspace_bytes(C.byref(d), 1, 1, 1) == 0

@@ -1,0 +1,154 @@
+"""GPU parity: each C-ABI operator against the fp64 oracle on the same seeded inputs.
+Sizes span several tiles and a ragged tail; the tolerance is the one stated for the path
+(fp32: max-abs 1e-4; bf16: 2e-2 relative to max(|ref|, rms(ref)))."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import forge_oracle as O
+from paper_2604_16498_amd import inputs as I
+from util import check, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def F():
+    from paper_2604_16498_amd import binding
+    binding.lib()
+    return binding
+
+
+def tdtype(bf16):
+    return torch.bfloat16 if bf16 else torch.float32
+
+
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("kind", ["layernorm", "rmsnorm"])
+@pytest.mark.parametrize("rows,d", [(128, 768), (64, 4096), (37, 2048), (5, 8), (3, 16384),
+                                    (1000, 1032), (9, 520), (8192, 768)])
+def test_residual_norm(F, bf16, kind, rows, d):
+    x = I.normal(60, 0, "x", (rows, d), 1.5, mean=0.3, bf16=bf16)
+    dl = I.normal(60, 0, "delta", (rows, d), 0.7, bf16=bf16)
+    g = I.normal(60, 0, "norm1_g", (d,), 0.2, mean=1.0, bf16=bf16)
+    b = I.normal(60, 0, "norm1_b", (d,), 0.2, bf16=bf16)
+    for use_delta in (True, False):
+        h_ref, y_ref = O.residual_norm(x, dl if use_delta else None, g, b, 1e-5, kind)
+        tx, tg, tb = dev(x, bf16), dev(g, bf16), dev(b, bf16)
+        td = dev(dl, bf16) if use_delta else None
+        th = torch.empty_like(tx) if use_delta else None
+        ty = torch.empty_like(tx)
+        F.forge_residual_norm(tx, td, tg, tb, th, ty, 1e-5, kind)
+        torch.cuda.synchronize()
+        check(ty, y_ref, bf16, "y")
+        if use_delta:
+            check(th, h_ref, bf16, "h")
+
+
+# ---------------------------------------------------------------------------------------------
+GEMM_SHAPES = [(128, 2304, 768), (100, 200, 72), (1, 8, 8), (300, 515, 264), (257, 1001, 64),
+               (64, 768, 3072), (513, 384, 136)]
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("act", ["none", "gelu_tanh", "relu", "silu", "swiglu"])
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_bias_act(F, bf16, act, M, N, K):
+    wn = 2 * N if act == "swiglu" else N
+    x = I.normal(61, 0, "x", (M, K), 1.0, bf16=bf16)
+    w = I.normal(61, 0, "w_up", (wn, K), 1.0 / math.sqrt(K), bf16=bf16)
+    b = I.normal(61, 0, "b_up", (wn,), 0.5, bf16=bf16)
+    r = I.normal(61, 0, "residual", (M, N), 1.0, bf16=bf16)
+    tx, tw, tb, tr = (dev(a, bf16) for a in (x, w, b, r))
+    for use_b, use_r in ((True, True), (False, False)):
+        ref = O.gemm_bias_act(x, w, b if use_b else None, r if use_r else None, act)
+        ty = torch.empty(M, N, dtype=tdtype(bf16), device="cuda")
+        ws = F.workspace(F.forge_gemm_workspace_bytes(M, N, K, act, tdtype(bf16)))
+        F.forge_gemm_bias_gelu(tx, tw, tb if use_b else None, tr if use_r else None, ty, act, ws)
+        torch.cuda.synchronize()
+        check(ty, ref, bf16, "gemm %s" % act)
+
+
+def test_gemm_residual_in_place(F):
+    M, N, K = 200, 256, 128
+    x = I.normal(62, 0, "x", (M, K), 1.0, bf16=True)
+    w = I.normal(62, 0, "w_o", (N, K), 0.1, bf16=True)
+    r = I.normal(62, 0, "residual", (M, N), 1.0, bf16=True)
+    ref = O.gemm_bias_act(x, w, None, r, "none")
+    ty = dev(r, True)
+    F.forge_gemm_bias_gelu(dev(x, True), dev(w, True), None, ty, ty, "none")
+    torch.cuda.synchronize()
+    check(ty, ref, True, "in-place residual")
+
+
+# ---------------------------------------------------------------------------------------------
+ATTN_SHAPES = [  # B, Hq, Hkv, Sq, Skv, cap, dh
+    (1, 12, 12, 128, 128, 128, 64),
+    (2, 8, 2, 100, 100, 100, 128),
+    (2, 4, 4, 1, 300, 320, 64),
+    (1, 4, 2, 70, 200, 256, 128),
+    (1, 2, 1, 333, 333, 333, 64),
+    (3, 8, 2, 1, 1, 8, 128),
+    (1, 2, 2, 257, 257, 257, 128),
+]
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Skv,cap,dh", ATTN_SHAPES)
+def test_attn_fused(F, bf16, causal, B, Hq, Hkv, Sq, Skv, cap, dh):
+    q = I.normal(63, 0, "q", (B, Hq, Sq, dh), 1.0, bf16=bf16)
+    k = I.normal(63, 0, "k", (B, Hkv, cap, dh), 1.0, bf16=bf16)
+    v = I.normal(63, 0, "v", (B, Hkv, cap, dh), 1.0, bf16=bf16)
+    scale = 1.0 / math.sqrt(dh)
+    ref = O.attention(q, k[:, :, :Skv], v[:, :, :Skv], scale, causal)
+    tq, tk, tv = dev(q, bf16), dev(k, bf16), dev(v, bf16)
+    out = torch.empty(B, Sq, Hq * dh, dtype=tdtype(bf16), device="cuda")
+    ws = F.workspace(F.forge_attn_fused_workspace_bytes(B, Hq, Hkv, Sq, Skv, dh, tdtype(bf16)))
+    F.forge_attn_fused(tq, tk, tv, out, kv_len=Skv, scale=scale, causal=causal, workspace=ws)
+    torch.cuda.synchronize()
+    check(out, ref, bf16, "attention")
+
+
+def test_attn_sharp_softmax(F):
+    """Large score spread: one key dominates each row, the online rescaling must not lose it."""
+    B, H, S, dh = 1, 2, 200, 64
+    q = I.normal(64, 0, "q", (B, H, S, dh), 6.0, bf16=True)
+    k = I.normal(64, 0, "k", (B, H, S, dh), 6.0, bf16=True)
+    v = I.normal(64, 0, "v", (B, H, S, dh), 1.0, bf16=True)
+    ref = O.attention(q, k, v, 0.125, True)
+    out = torch.empty(B, S, H * dh, dtype=torch.bfloat16, device="cuda")
+    F.forge_attn_fused(dev(q, True), dev(k, True), dev(v, True), out, scale=0.125)
+    torch.cuda.synchronize()
+    check(out, ref, True, "sharp attention")
+
+
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("dh", [64, 128])
+def test_rope(F, bf16, dh):
+    B, H, cap, row0, n_rows, pos0 = 2, 3, 50, 7, 40, 2040
+    x = I.normal(65, 0, "q", (B, H, cap, dh), 1.0, bf16=bf16)
+    ref = x.astype(np.float64).copy()
+    ref[:, :, row0:row0 + n_rows] = O.rope(x[:, :, row0:row0 + n_rows], np.arange(pos0, pos0 + n_rows), 500000.0)
+    tx = dev(x, bf16)
+    F.forge_rope(tx, n_rows=n_rows, row0=row0, pos0=pos0, base=500000.0)
+    torch.cuda.synchronize()
+    check(tx, ref, bf16, "rope")
+    assert np.array_equal(host(tx)[:, :, :row0], x[:, :, :row0].astype(np.float64))
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+def test_embed(F, bf16):
+    B, S, d, V, P = 3, 17, 264, 1001, 40
+    wte = I.normal(66, 0, "wte", (V, d), 0.02, bf16=bf16)
+    wpe = I.normal(66, 0, "wpe", (P, d), 0.02, bf16=bf16)
+    ids = I.token_ids(66, B, S, V)
+    ref = O.embed(ids, wte, wpe, pos0=5)
+    h = torch.empty(B, S, d, dtype=tdtype(bf16), device="cuda")
+    F.forge_embed(torch.from_numpy(ids).cuda(), dev(wte, bf16), dev(wpe, bf16), h, pos0=5)
+    torch.cuda.synchronize()
+    check(h, ref, bf16, "embed")
