@@ -103,6 +103,11 @@ forge_status forge_attn_fused(const void* q, const void* k, const void* v, void*
  * ------------------------------------------------------------------------------------ */
 size_t forge_gemm_workspace_bytes(int M, int N, int K, forge_act act, forge_dtype dt);
 
+/* Diagnostic: the name of the kernel variant (tile shape and wave layout) that
+ * forge_gemm_bias_gelu launches for this problem, e.g. "gemm_bf16<256,256,2,4>"; static
+ * storage, never NULL.  Lets a profiler trace be matched to the calls that produced it. */
+const char* forge_gemm_variant(int M, int N, int K, forge_act act, forge_dtype dt);
+
 forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias,
                                   const void* residual, void* y, int M, int N, int K,
                                   forge_act act, forge_dtype dt,

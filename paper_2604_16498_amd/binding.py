@@ -58,6 +58,7 @@ SIGNATURES = {
     "forge_attn_fused_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i, _i]),
     "forge_attn_fused": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _i, _vp, _sz, _vp]),
     "forge_gemm_workspace_bytes": (_sz, [_i, _i, _i, _i, _i]),
+    "forge_gemm_variant": (C.c_char_p, [_i, _i, _i, _i, _i]),
     "forge_gemm_bias_gelu": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
     "forge_residual_norm": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _f, _i, _i, _vp]),
     "forge_rope": (_i, [_vp, _i, _i, _i, _i, _i64, _i64, _i, _i, _f, _i, _vp]),
@@ -149,6 +150,11 @@ def forge_attn_fused(q, k, v, out, kv_len=None, scale=None, causal=True, workspa
 def forge_gemm_workspace_bytes(M, N, K, act, dtype) -> int:
     dt = FORGE_BF16 if dtype == torch.bfloat16 else FORGE_F32
     return lib().forge_gemm_workspace_bytes(M, N, K, ACT[act], dt)
+
+
+def forge_gemm_variant(M, N, K, act, dtype) -> str:
+    dt = FORGE_BF16 if dtype == torch.bfloat16 else FORGE_F32
+    return lib().forge_gemm_variant(M, N, K, ACT[act], dt).decode()
 
 
 def forge_gemm_bias_gelu(x, w, bias, residual, y, act="gelu_tanh", workspace=None):

@@ -215,6 +215,11 @@ size_t forge_gemm_workspace_bytes(int M, int N, int K, forge_act act, forge_dtyp
   return gemm_ws(M, N, K, act, dt);
 }
 
+const char* forge_gemm_variant(int M, int N, int K, forge_act act, forge_dtype dt) {
+  if (M < 1 || N < 1 || K < 1) return "none";
+  return dt == FORGE_BF16 ? gemm_bf16_variant(M, N, K, act) : "gemm_f32<64,64,2,2>";
+}
+
 forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias,
                                   const void* residual, void* y, int M, int N, int K, forge_act act,
                                   forge_dtype dt, void* workspace, size_t workspace_bytes,

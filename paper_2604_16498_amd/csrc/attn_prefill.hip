@@ -1,0 +1,276 @@
+// bf16 fused causal attention for prefill on the gfx950 matrix cores: scores, scale, mask,
+// softmax and the product with V in one kernel; S and P live only in registers.
+//
+// Work split: a 256-thread block (4 waves) owns 128 consecutive queries of one (batch, head);
+// each wave owns 32 of them and walks the keys in tiles of 64 up to its diagonal.
+//
+// Both contractions are computed TRANSPOSED so that the two MFMAs chain without any data
+// movement:
+//   S^T[key, query] = K . Q^T   : A operand = K rows (LDS, 128-bit reads along dh),
+//                                 B operand = Q^T, i.e. each lane's own query row (registers).
+//   O^T[d, query]   = V^T . P^T : B operand = P^T, which is exactly the accumulator layout of
+//                                 S^T (lane = query, registers = keys) rounded to bf16;
+//                                 A operand = V^T, read from the row-major V tile in LDS with
+//                                 the transposing LDS read (ds_read_b64_tr_b16: within 16 lanes,
+//                                 lane 4q+r receives element r of the 8-byte rows addressed by
+//                                 lanes q, q+4, q+8, q+12).
+// A lane therefore owns ONE query throughout: its 32 scores per tile sit in its own registers,
+// the row maximum needs a single exchange with lane^32 (the other half of the keys), the row
+// sum is kept as a per-lane partial and combined once at the end, and the rescale factor of
+// the online softmax is a per-lane scalar.
+//
+// The contraction order over keys inside a 16-key MFMA step is permuted (the same permutation
+// on both operands, so the sum is unchanged): element e of lane-half h is key
+// 16 s + 8 (e / 4) + 4 h + e % 4, which is what the S^T accumulator registers 8 (s % 2) + e hold.
+//
+// LDS: K tile rows padded by 16 B and V tile rows by 64 B so that the row reads (K) and the
+// 4-rows-by-64-B transposing reads (V) of a half wave fall on disjoint banks.  K and V tiles
+// are double buffered: the global loads of tile t+1 are issued before the MFMAs of tile t.
+#include "common.hpp"
+
+namespace forge {
+namespace {
+
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
+
+struct AttnParams {
+  const bf16* q;
+  const bf16* k;
+  const bf16* v;
+  bf16* out;
+  int q_heads, kv_heads, q_len, kv_len;
+  int64_t kv_bs, kv_hs;
+  float scale_log2e;
+  int causal;
+  int n_qblocks;
+};
+
+__device__ inline float xchg32_max(float x) {
+  // max over the lane pair (l, l^32)
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float xchg32_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+template <int DH>
+__global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnParams p) {
+  constexpr int BQ = 128, BKV = 64;
+  constexpr int CPR = DH / 8;                 // 16-byte chunks per row
+  constexpr int KS = DH * 2 + 16;             // K row stride in LDS (bytes)
+  constexpr int VS = DH * 2 + 64;             // V row stride in LDS (bytes)
+  constexpr int K_BYTES = BKV * KS, V_BYTES = BKV * VS;
+  constexpr int LPT = BKV * CPR / 256;        // chunks per thread per tensor per tile
+  constexpr int NKS = DH / 16;                // MFMA k-steps over dh
+  constexpr int NDT = DH / 32;                // 32-row tiles of O^T
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // [K0 | V0 | K1 | V1]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int fr = lane & 31, fh = lane >> 5;
+  // late (long) query blocks first: they carry the most key tiles under the causal mask
+  const int qb = p.n_qblocks - 1 - blockIdx.x;
+  const int h = blockIdx.y, b = blockIdx.z;
+  const int g = h / (p.q_heads / p.kv_heads);
+  const int q0 = qb * BQ, q0w = q0 + wave * 32;
+  const int off = p.kv_len - p.q_len;
+
+  const bf16* kbase = p.k + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
+  const bf16* vbase = p.v + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
+
+  // ---- this lane's query row as the B operand of S^T (registers for the whole kernel) ------
+  const int my_q = q0w + fr;
+  bf16x8 qf[NKS];
+  {
+    const int qr = min(my_q, p.q_len - 1);
+    const bf16* qrow = p.q + (((int64_t)b * p.q_heads + h) * p.q_len + qr) * DH;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks)
+      qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + (2 * ks + fh) * 8);
+  }
+
+  // keys a query may see: [0, limit]
+  const int last_q_blk = min(q0 + BQ, p.q_len) - 1;
+  const int n_tiles = ceil_div((p.causal ? last_q_blk + off : p.kv_len - 1) + 1, BKV);
+  const int my_limit = p.causal ? my_q + off : p.kv_len - 1;
+  const int wave_max_limit = p.causal ? min(q0w + 31, p.q_len - 1) + off : p.kv_len - 1;
+  const int wave_min_limit = p.causal ? q0w + off : p.kv_len - 1;
+
+  // ---- global -> LDS copy plan ---------------------------------------------------------------
+  int ld_row[LPT], ld_c[LPT];
+#pragma unroll
+  for (int i = 0; i < LPT; ++i) {
+    const int idx = tid + i * 256;
+    ld_row[i] = idx / CPR;
+    ld_c[i] = idx % CPR;
+  }
+  u32x4 rk[LPT], rv[LPT];
+  auto load_tile = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      const int key = min(t * BKV + ld_row[i], p.kv_len - 1);   // rows past the end re-read the last key
+      rk[i] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)key * DH + ld_c[i] * 8);
+      rv[i] = *reinterpret_cast<const u32x4*>(vbase + (int64_t)key * DH + ld_c[i] * 8);
+    }
+  };
+  auto store_tile = [&](int buf) {
+    char* sk = smem + buf * (K_BYTES + V_BYTES);
+    char* sv = sk + K_BYTES;
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      *reinterpret_cast<u32x4*>(sk + ld_row[i] * KS + ld_c[i] * 16) = rk[i];
+      *reinterpret_cast<u32x4*>(sv + ld_row[i] * VS + ld_c[i] * 16) = rv[i];
+    }
+  };
+
+  floatx16 o_acc[NDT];
+#pragma unroll
+  for (int i = 0; i < NDT; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o_acc[i][e] = 0.f;
+  float m_run = -1e30f, l_run = 0.f;   // finite start: no inf - inf anywhere
+  const float c = p.scale_log2e;
+
+  // per-lane byte offset of the transposing V read inside a tile (without key step / d tile)
+  const int vt_lane = (((lane & 15) >> 2) + 4 * fh) * VS + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const bool more = t + 1 < n_tiles;
+    if (more) load_tile(t + 1);
+    const int kv0 = t * BKV;
+    if (kv0 <= wave_max_limit) {   // wave-uniform: tiles wholly above this wave's diagonal are skipped
+      const char* sk = smem + (t & 1) * (K_BYTES + V_BYTES);
+      const char* sv = sk + K_BYTES;
+
+      // ---- S^T = K . Q^T --------------------------------------------------------------------
+      floatx16 s_acc[2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s_acc[kb][e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + fr) * KS + (2 * ks + fh) * 16);
+          s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s_acc[kb], 0, 0, 0);
+        }
+      }
+      // ---- mask (diagonal / tail tiles only) ---------------------------------------------------
+      if (kv0 + BKV - 1 > wave_min_limit) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int key = kv0 + kb * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
+            if (key > my_limit) s_acc[kb][v] = -INFINITY;
+          }
+      }
+      // ---- online softmax ----------------------------------------------------------------------
+      float mx = s_acc[0][0];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s_acc[kb][v]);
+      mx = xchg32_max(mx);
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+      const float mc = m_new * c;
+      float psum = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float pv = __builtin_amdgcn_exp2f(s_acc[kb][v] * c - mc);
+          s_acc[kb][v] = pv;
+          psum += pv;
+        }
+      l_run = l_run * alpha + psum;
+      m_run = m_new;
+#pragma unroll
+      for (int i = 0; i < NDT; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
+
+      // ---- O^T += V^T . P^T ---------------------------------------------------------------------
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        bf16x8 pf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[e] = (bf16)s_acc[s >> 1][8 * (s & 1) + e];
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) {
+          const char* va = sv + vt_lane + (16 * s) * VS + dt * 64;
+          const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(va));
+          const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(va + 8 * VS));
+          typedef short v8i16 __attribute__((ext_vector_type(8)));
+          v8i16 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
+          o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o_acc[dt], 0, 0, 0);
+        }
+      }
+    }
+    if (more) store_tile((t + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- normalise and store: lane owns query my_q; registers 4g..4g+3 are 4 consecutive d -----
+  const float l_tot = xchg32_sum(l_run);
+  if (my_q < p.q_len) {
+    const float inv = 1.0f / l_tot;
+    bf16* orow = p.out + ((int64_t)b * p.q_len + my_q) * ((int64_t)p.q_heads * DH) + (int64_t)h * DH;
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+      for (int gg = 0; gg < 4; ++gg) {
+        u32x2 pk;
+        pk[0] = pack_bf2(o_acc[dt][4 * gg] * inv, o_acc[dt][4 * gg + 1] * inv);
+        pk[1] = pack_bf2(o_acc[dt][4 * gg + 2] * inv, o_acc[dt][4 * gg + 3] * inv);
+        *reinterpret_cast<u32x2*>(orow + dt * 32 + 8 * gg + 4 * fh) = pk;
+      }
+  }
+}
+
+template <int DH>
+forge_status launch_dh(const AttnArgs& a, hipStream_t s) {
+  AttnParams p;
+  p.q = (const bf16*)a.q;
+  p.k = (const bf16*)a.k;
+  p.v = (const bf16*)a.v;
+  p.out = (bf16*)a.out;
+  p.q_heads = a.q_heads;
+  p.kv_heads = a.kv_heads;
+  p.q_len = a.q_len;
+  p.kv_len = a.kv_len;
+  p.kv_bs = a.kv_batch_stride;
+  p.kv_hs = a.kv_head_stride;
+  p.scale_log2e = a.scale * 1.4426950408889634f;
+  p.causal = a.causal;
+  p.n_qblocks = ceil_div(a.q_len, 128);
+  constexpr int smem = 2 * 64 * ((DH * 2 + 16) + (DH * 2 + 64));
+  auto kern = attn_prefill_kernel<DH>;
+  static bool configured = false;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+      return FORGE_ERR_HIP;
+    configured = true;
+  }
+  dim3 grid(p.n_qblocks, a.q_heads, a.batch), block(256);
+  kern<<<grid, block, smem, s>>>(p);
+  return launch_status();
+}
+
+}  // namespace
+
+forge_status launch_attn_prefill_bf16(const AttnArgs& a, hipStream_t s) {
+  if (a.head_dim == 64) return launch_dh<64>(a, s);
+  if (a.head_dim == 128) return launch_dh<128>(a, s);
+  return FORGE_ERR_UNSUPPORTED;
+}
+
+}  // namespace forge

@@ -142,6 +142,7 @@ struct GemmArgs {
 forge_status launch_gemm_f32(const GemmArgs& a, hipStream_t s);
 forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
 size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act);
+const char* gemm_bf16_variant(int M, int N, int K, forge_act act);
 size_t gemm_f32_workspace_bytes(int M, int N, int K, forge_act act);
 
 struct AttnArgs {

@@ -235,17 +235,32 @@ forge_status launch_cfg(const GemmParams& p0, hipStream_t s) {
   return launch_status();
 }
 
+// tile choice: big tiles when they still give every CU work, smaller ones otherwise
+enum Variant { V_256x256 = 0, V_128x128 = 1 };
+inline Variant choose_variant(int M, int N, int K, forge_act act) {
+  (void)K;
+  const int64_t big = (int64_t)ceil_div(M, 256) * ceil_div(N, act == FORGE_ACT_SWIGLU ? 128 : 256);
+  return big >= 512 ? V_256x256 : V_128x128;
+}
+
 template <int ACT, bool SPLIT>
 forge_status launch_act(const GemmParams& p, hipStream_t s) {
-  // tile choice: big tiles when they still give every CU work, smaller ones otherwise
-  const int64_t big = (int64_t)ceil_div(p.M, 256) * ceil_div(p.N, ACT == FORGE_ACT_SWIGLU ? 128 : 256);
-  if (big >= 512) return launch_cfg<256, 256, 2, 4, ACT, SPLIT>(p, s);
-  return launch_cfg<128, 128, 2, 2, ACT, SPLIT>(p, s);
+  switch (choose_variant(p.M, p.N, p.K, (forge_act)ACT)) {
+    case V_256x256: return launch_cfg<256, 256, 2, 4, ACT, SPLIT>(p, s);
+    default: return launch_cfg<128, 128, 2, 2, ACT, SPLIT>(p, s);
+  }
 }
 
 }  // namespace
 
 size_t gemm_bf16_workspace_bytes(int, int, int, forge_act) { return 0; }
+
+const char* gemm_bf16_variant(int M, int N, int K, forge_act act) {
+  switch (choose_variant(M, N, K, act)) {
+    case V_256x256: return "gemm_bf16<256,256,2,4>";
+    default: return "gemm_bf16<128,128,2,2>";
+  }
+}
 
 forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   GemmParams p = {};

@@ -93,6 +93,9 @@ ATTN_SHAPES = [  # B, Hq, Hkv, Sq, Skv, cap, dh
     (1, 2, 1, 333, 333, 333, 64),
     (3, 8, 2, 1, 1, 8, 128),
     (1, 2, 2, 257, 257, 257, 128),
+    (1, 4, 2, 1000, 1000, 1000, 128),
+    (2, 3, 3, 700, 700, 704, 64),
+    (1, 2, 1, 130, 900, 900, 128),
 ]
 
 
