@@ -1,0 +1,304 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused decoder-block forward on one MI355X.
+
+One "step" is one whole forward of the workload: embedding -> L fused decoder
+layers (norm, QKV GEMM, fused causal attention, out GEMM + residual, norm, MLP
+GEMMs with fused activation / residual) -> final norm -> tied LM head, on
+synthetic seeded inputs that are resident in HBM before the timed region.
+
+Default workload: the 12-layer GPT-2-small-shaped model, bf16, batch 8 x 1024
+tokens.  Prints ONE JSON line with the whole-job throughput in tokens/s, the
+roofline of the dominant kernel (measured with HIP events on the launch stream)
+and the fp64 CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0,
+                    help="stop adding oracle samples once this much CPU time is spent")
+    return ap.parse_args()
+
+
+# ---------------------------------------------------------------------------------------------
+# model construction (device memory plumbing only)
+# ---------------------------------------------------------------------------------------------
+
+def build_model(wl, F, torch, I):
+    """Weights, descriptors, caches, workspace and the input of one workload on the GPU."""
+    sh = wl.block
+    dt = torch.bfloat16 if wl.bf16 else torch.float32
+    big = sh.d_model >= 4096          # 8B-shaped: draw on the device (host generation takes minutes)
+    g = torch.Generator(device="cuda").manual_seed(I.BASE_SEED * 1000 + wl.cid)
+
+    def dev(a):
+        if a is None:
+            return None
+        t = torch.from_numpy(a)
+        return (t.to(torch.bfloat16) if wl.bf16 else t).cuda()
+
+    def dev_normal(shape, std):
+        return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(dt)
+
+    layers = []
+    for l in range(wl.layers):
+        if not big:
+            w = {k: dev(v) for k, v in I.block_weights(sh, wl.cid, l, wl.bf16, wl.bias_std).items()}
+        else:
+            d = sh.d_model
+            w = {
+                "norm1_g": torch.ones(d, device="cuda", dtype=dt), "norm1_b": None,
+                "w_qkv": dev_normal((sh.qkv_out, d), 0.02), "b_qkv": None,
+                "w_o": dev_normal((d, sh.q_heads * sh.head_dim), 0.02), "b_o": None,
+                "norm2_g": torch.ones(d, device="cuda", dtype=dt), "norm2_b": None,
+                "w_up": dev_normal((sh.up_out, d), 0.02), "b_up": None,
+                "w_down": dev_normal((d, sh.d_ff), 0.02), "b_down": None,
+            }
+        layers.append(w)
+    mw = {k: dev(v) for k, v in I.model_weights(wl).items()}
+    descs = [F.make_block_desc(sh, w) for w in layers]
+    model = F.make_model_desc(descs, mw)
+
+    B, S = wl.batch, wl.seq
+    cap = wl.pos0 + S
+    cap = (cap + 63) // 64 * 64
+    kshape = (wl.layers, B, sh.kv_heads, cap, sh.head_dim)
+    if wl.pos0:
+        kc = torch.randn(kshape, generator=g, device="cuda", dtype=torch.float32).to(dt)
+        vc = torch.randn(kshape, generator=g, device="cuda", dtype=torch.float32).to(dt)
+    else:
+        kc = torch.zeros(kshape, device="cuda", dtype=dt)
+        vc = torch.zeros_like(kc)
+    if wl.vocab:
+        ids_host = I.token_ids(wl.cid, B, S, wl.vocab)
+        inp = torch.from_numpy(ids_host).cuda()
+        out = torch.empty(B, S, wl.vocab, device="cuda", dtype=dt)
+    else:
+        ids_host = None
+        inp = dev(I.hidden_states(wl))
+        out = torch.empty(B, S, sh.d_model, device="cuda", dtype=dt)
+    ws = F.workspace(F.forge_model_workspace_bytes(model, B, S, cap))
+    keep = (layers, mw, descs)
+    return dict(model=model, inp=inp, out=out, kc=kc, vc=vc, ws=ws, keep=keep, ids_host=ids_host,
+                layers=layers, mw=mw, cap=cap)
+
+
+# ---------------------------------------------------------------------------------------------
+# algorithmic work
+# ---------------------------------------------------------------------------------------------
+
+def gemm_launches(wl):
+    """The plain (non head-split) GEMM launches of one step: (name, M, N_out, K, act, count)."""
+    sh = wl.block
+    T = wl.batch * wl.seq
+    hd = sh.q_heads * sh.head_dim
+    out = [
+        ("out", T, sh.d_model, hd, "none", wl.layers),
+        ("mlp_up", T, sh.d_ff, sh.d_model, sh.mlp_act, wl.layers),
+        ("mlp_down", T, sh.d_model, sh.d_ff, "none", wl.layers),
+    ]
+    if wl.vocab:
+        out.append(("lm_head", T, wl.vocab, sh.d_model, "none", 1))
+    return out
+
+
+def step_flops(wl):
+    sh = wl.block
+    T = wl.batch * wl.seq
+    hd = sh.q_heads * sh.head_dim
+    kv = wl.pos0 + wl.seq
+    gemm = 2.0 * T * (sh.qkv_out * sh.d_model + sh.d_model * hd + sh.up_out * sh.d_model
+                      + sh.d_model * sh.d_ff) * wl.layers
+    if wl.vocab:
+        gemm += 2.0 * T * wl.vocab * sh.d_model
+    # causal attention: only the keys a query may see (lower triangle incl. diagonal)
+    pairs = wl.batch * sum(wl.pos0 + s + 1 for s in range(wl.seq)) if wl.seq <= 8192 else 0
+    attn = 4.0 * sh.q_heads * sh.head_dim * pairs * wl.layers
+    return gemm, attn
+
+
+def step_bytes(wl):
+    """Algorithmic HBM bytes of one step for the bandwidth-bound (decode) workload: every weight
+    and every cached K/V row is read once."""
+    sh = wl.block
+    es = 2 if wl.bf16 else 4
+    hd = sh.q_heads * sh.head_dim
+    wbytes = (sh.qkv_out * sh.d_model + sh.d_model * hd + sh.up_out * sh.d_model + sh.d_model * sh.d_ff) * es
+    kvbytes = 2 * wl.batch * sh.kv_heads * (wl.pos0 + wl.seq) * sh.head_dim * es
+    return (wbytes + kvbytes) * wl.layers
+
+
+# ---------------------------------------------------------------------------------------------
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2604_16498_amd import binding as F
+    from paper_2604_16498_amd import inputs as I
+    F.lib()                                    # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+
+    wl = I.WORKLOADS[int(args.workload[1])]
+    m = build_model(wl, F, torch, I)
+    pos0 = wl.pos0
+
+    def step():
+        F.forge_model_forward(m["model"], m["inp"], m["out"], m["kc"], m["vc"], pos0, m["ws"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens = wl.batch * wl.seq
+    value = tokens / (ms_per_step * 1e-3)
+    gemm_fl, attn_fl = step_flops(wl)
+
+    # ---- roofline of the dominant kernel: HIP events on the launch stream around every launch
+    # of each plain GEMM of one step (same shapes, same weights), repeated; the group with the
+    # largest total time is reported.
+    dt = torch.bfloat16 if wl.bf16 else torch.float32
+    sh = wl.block
+    groups = {}
+    reps = max(3, min(args.steps, 10))
+    for name, M, N, K, act, count in gemm_launches(wl):
+        if name == "lm_head":
+            w, b = m["mw"]["wte"], None
+        else:
+            key = {"out": ("w_o", "b_o"), "mlp_up": ("w_up", "b_up"), "mlp_down": ("w_down", "b_down")}[name]
+        x = torch.randn(M, K, device="cuda", dtype=torch.float32).to(dt)
+        y = torch.empty(M, N, device="cuda", dtype=dt)
+        res = torch.randn(M, N, device="cuda", dtype=torch.float32).to(dt) if name in ("out", "mlp_down") else None
+        gws = F.workspace(F.forge_gemm_workspace_bytes(M, N, K, act, dt))
+        times = []
+        for r in range(reps):
+            for l in range(count):
+                if name != "lm_head":
+                    w, b = m["layers"][l][key[0]], m["layers"][l][key[1]]
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                F.forge_gemm_bias_gelu(x, w, b, res, y, act, gws)
+                e1.record()
+                times.append((e0, e1))
+        torch.cuda.synchronize()
+        durs = [a.elapsed_time(b_) * 1e-3 for a, b_ in times]
+        nw = 2 * N if act == "swiglu" else N
+        sym = "%s act=%s" % (F.forge_gemm_variant(M, N, K, act, dt), act)
+        gkey = sym
+        gr = groups.setdefault(gkey, {"time": 0.0, "flops": 0.0, "launches": 0, "bytes": 0.0})
+        gr["time"] += sum(durs)
+        gr["flops"] += 2.0 * M * nw * K * len(durs)
+        gr["launches"] += len(durs)
+        del x, y, res
+    dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["time"])
+    avg_dur = dom["time"] / dom["launches"]
+    flops_per_launch = dom["flops"] / dom["launches"]
+    if args.workload == "c5":
+        # decode: every kernel streams weights / cache; report bytes per step over step time
+        achieved = step_bytes(wl) / (ms_per_step * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                    "kernel": "whole decode step (weights + KV cache read once)"}
+    else:
+        achieved = flops_per_launch / avg_dur / 1e12
+        roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS if wl.bf16 else 157.3,
+                    "unit": "TFLOP/s", "frac": round(achieved / (PEAK_BF16_TFLOPS if wl.bf16 else 157.3), 4),
+                    "traffic": None, "kernel": dom_name, "avg_launch_us": round(avg_dur * 1e6, 2),
+                    "launches_timed": dom["launches"],
+                    "groups": {k: {"tflops": round(v["flops"] / v["time"] / 1e12, 1),
+                                   "avg_us": round(v["time"] / v["launches"] * 1e6, 2)} for k, v in groups.items()}}
+
+    # ---- the fp64 oracle on the host cores, on a bounded sample of the same workload -------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(wl, m, args.cpu_seconds)
+
+    line = {
+        "metric": "decoder-block tokens/s; fused attention+GEMM TFLOP/s as % of MI355X peak",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if wl.bf16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.layers, "batch": wl.batch, "seq_len": wl.seq,
+                   "kv_pos0": wl.pos0, "d_model": sh.d_model, "parallelism": "single-gpu"},
+        "step_tflops": round((gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12, 1),
+        "step_frac_of_bf16_peak": round((gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+def cpu_baseline(wl, m, budget_s):
+    """Time the oracle as it stands on whole sequences of the workload until ~budget_s is spent."""
+    import numpy as np
+    from oracle import forge_oracle as O
+    from paper_2604_16498_amd import inputs as I
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    sh = wl.block
+    if sh.d_model >= 4096:
+        # 8B-shaped: one layer of one sequence, scaled by the layer count
+        w = {k: (None if v is None else v.float().cpu().numpy()) for k, v in m["layers"][0].items()}
+        x = I.hidden_states(wl, batch=1)
+        t0 = time.perf_counter()
+        if wl.pos0:
+            kc = m["kc"][0, :1].float().cpu().numpy().astype(np.float64)
+            vc = m["vc"][0, :1].float().cpu().numpy().astype(np.float64)
+            t0 = time.perf_counter()
+            O.decoder_block(sh, w, x, kc, vc, pos0=wl.pos0)
+        else:
+            O.decoder_block(sh, w, x)
+        dt_ = (time.perf_counter() - t0) * wl.layers
+        return {"value": round(wl.seq / dt_, 3), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                "sample": "1 layer x 1 sequence timed, multiplied by %d layers (extrapolated)" % wl.layers}
+    layers = [I.block_weights(sh, wl.cid, l, wl.bf16, wl.bias_std) for l in range(wl.layers)]
+    mw = I.model_weights(wl)
+    done, t_used = 0, 0.0
+    while done < wl.batch and t_used < budget_s:
+        t0 = time.perf_counter()
+        if wl.vocab:
+            O.gpt_forward(sh, layers, mw, ids=m["ids_host"][done:done + 1])
+        else:
+            O.gpt_forward(sh, layers, mw, x=I.hidden_states(wl)[done:done + 1])
+        t_used += time.perf_counter() - t0
+        done += 1
+    return {"value": round(done * wl.seq / t_used, 2), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "%d of %d sequences of %d tokens, all %d layers%s, %.1f s" % (
+                done, wl.batch, wl.seq, wl.layers, " + LM head" if wl.vocab else "", t_used)}
+
+
+if __name__ == "__main__":
+    main()
