@@ -57,10 +57,14 @@ struct GemmParams {
   bf16* y;
   int M, N, K;        // N: output columns
   int tiles_m, tiles_n;
+  int k_per_split;    // split-K: k range of one block (multiple of 64); otherwise >= K
+  float* part;        // split-K: fp32 partial sums [splits, M, N]
   QkvSplit sp;
 };
 
-template <int BM, int BN, int WM, int WN, int ACT, bool SPLIT>
+enum Mode { MODE_PLAIN = 0, MODE_QKV = 1, MODE_SPLITK = 2 };
+
+template <int BM, int BN, int WM, int WN, int ACT, int MODE>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmParams p) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -79,7 +83,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmParams p) {
   // ---- tile of this block: XCD-contiguous runs, grouped tile order --------------------------
   int tile;
   {
-    const int pid = blockIdx.x, nwg = gridDim.x;
+    const int pid = blockIdx.x, nwg = gridDim.x;   // grid.y indexes the k split
     const int xcd = pid & 7, idx = pid >> 3;
     const int per = nwg >> 3, rem = nwg & 7;
     tile = xcd * per + min(xcd, rem) + idx;
@@ -171,13 +175,15 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmParams p) {
     }
   };
 
-  const int nk = ceil_div(K, BK);
-  load_slab(0);
+  const int k_begin = MODE == MODE_SPLITK ? blockIdx.y * p.k_per_split : 0;
+  const int k_end = MODE == MODE_SPLITK ? min(K, k_begin + p.k_per_split) : K;
+  const int nk = ceil_div(k_end - k_begin, BK);
+  load_slab(k_begin);
   store_slab(0);
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const bool more = kt + 1 < nk;
-    if (more) load_slab((kt + 1) * BK);
+    if (more) load_slab(k_begin + (kt + 1) * BK);
     compute_slab(kt & 1);
     if (more) store_slab((kt + 1) & 1);
     __syncthreads();
@@ -201,10 +207,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmParams p) {
       for (int v = 0; v < 16; ++v) {
         const int m = m0 + (wm * TM + i) * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
         if (m >= M) continue;
+        if (MODE == MODE_SPLITK) {   // raw partial sum; bias / activation happen in the reduce
+          p.part[((int64_t)blockIdx.y * M + m) * N + n] = acc[i][j][v];
+          continue;
+        }
         float val = acc[i][j][v] + bv;
         if (SWIGLU) val = silu_f(val) * (acc[i][SWIGLU ? j + TN / 2 : j][v] + bv2);
         else val = apply_act<ACT>(val);
-        if (SPLIT) {
+        if (MODE == MODE_QKV) {
           *split_dst_bf16(p.sp, m, n) = (bf16)val;
         } else {
           if (p.residual != nullptr) val += (float)p.residual[(int64_t)m * N + n];
@@ -215,14 +225,49 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmParams p) {
   }
 }
 
-template <int BM, int BN, int WM, int WN, int ACT, bool SPLIT>
-forge_status launch_cfg(const GemmParams& p0, hipStream_t s) {
+// Split-K second stage: sums the fp32 partials of one output element in split order (fixed
+// order, no atomics), then applies the same epilogue as the single-pass kernel.  One thread
+// owns 4 consecutive columns.  For SwiGLU the partials hold 2N columns: gate n and up n + N.
+template <int ACT, bool QKV>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p, int splits, int ncols) {
+  constexpr bool SWIGLU = ACT == FORGE_ACT_SWIGLU;
+  const int N = p.N;                        // output columns
+  const int groups = ceil_div(N, 4);
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (int64_t)p.M * groups) return;
+  const int m = (int)(gid / groups), n0 = (int)(gid % groups) * 4;
+  const int64_t plane = (int64_t)p.M * ncols;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int n = n0 + e;
+    if (n >= N) break;
+    float a = 0.f, u = 0.f;
+    for (int z = 0; z < splits; ++z) {
+      a += p.part[z * plane + (int64_t)m * ncols + n];
+      if (SWIGLU) u += p.part[z * plane + (int64_t)m * ncols + n + N];
+    }
+    if (p.bias != nullptr) {
+      a += (float)p.bias[n];
+      if (SWIGLU) u += (float)p.bias[n + N];
+    }
+    float val = SWIGLU ? silu_f(a) * u : apply_act<ACT>(a);
+    if (QKV) {
+      *split_dst_bf16(p.sp, m, n) = (bf16)val;
+    } else {
+      if (p.residual != nullptr) val += (float)p.residual[(int64_t)m * N + n];
+      p.y[(int64_t)m * N + n] = (bf16)val;
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int ACT, int MODE>
+forge_status launch_cfg(const GemmParams& p0, int splits, hipStream_t s) {
   GemmParams p = p0;
   constexpr int BN_OUT = ACT == FORGE_ACT_SWIGLU ? BN / 2 : BN;
   p.tiles_m = ceil_div(p.M, BM);
   p.tiles_n = ceil_div(p.N, BN_OUT);
   constexpr int smem = 2 * (BM + BN) * BK * 2;
-  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, ACT, SPLIT>;
+  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, ACT, MODE>;
   static bool configured = false;   // idempotent attribute, set once per instantiation
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -230,35 +275,72 @@ forge_status launch_cfg(const GemmParams& p0, hipStream_t s) {
       return FORGE_ERR_HIP;
     configured = true;
   }
-  dim3 grid(p.tiles_m * p.tiles_n), block(WM * WN * 64);
+  dim3 grid(p.tiles_m * p.tiles_n, splits), block(WM * WN * 64);
   kern<<<grid, block, smem, s>>>(p);
   return launch_status();
 }
 
-// tile choice: big tiles when they still give every CU work, smaller ones otherwise
-enum Variant { V_256x256 = 0, V_128x128 = 1 };
+// tile choice: big tiles when they still give every CU work, smaller ones otherwise; problems
+// with at most 64 rows (decode) stream the weight once and are split over K to fill the chip
+enum Variant { V_256x256 = 0, V_128x128 = 1, V_SKINNY = 2 };
 inline Variant choose_variant(int M, int N, int K, forge_act act) {
   (void)K;
+  if (M <= 64) return V_SKINNY;
   const int64_t big = (int64_t)ceil_div(M, 256) * ceil_div(N, act == FORGE_ACT_SWIGLU ? 128 : 256);
   return big >= 512 ? V_256x256 : V_128x128;
 }
 
-template <int ACT, bool SPLIT>
+struct SkinnyPlan {
+  int ncols;        // columns of the partial planes (2N for SwiGLU)
+  int splits;
+  int k_per_split;
+};
+inline SkinnyPlan plan_skinny(int N, int K, forge_act act) {
+  SkinnyPlan sp;
+  sp.ncols = act == FORGE_ACT_SWIGLU ? 2 * N : N;
+  const int tiles = ceil_div(sp.ncols, 64);
+  const int slabs = ceil_div(K, BK);
+  int want = ceil_div(512, tiles);                 // aim at >= 512 blocks
+  want = max(1, min(want, slabs / 4));             // but at least 4 slabs of work per block
+  const int per = ceil_div(slabs, want);
+  sp.splits = ceil_div(slabs, per);
+  sp.k_per_split = per * BK;
+  return sp;
+}
+
+template <int ACT, int MODE>
 forge_status launch_act(const GemmParams& p, hipStream_t s) {
   switch (choose_variant(p.M, p.N, p.K, (forge_act)ACT)) {
-    case V_256x256: return launch_cfg<256, 256, 2, 4, ACT, SPLIT>(p, s);
-    default: return launch_cfg<128, 128, 2, 2, ACT, SPLIT>(p, s);
+    case V_256x256: return launch_cfg<256, 256, 2, 4, ACT, MODE>(p, 1, s);
+    case V_128x128: return launch_cfg<128, 128, 2, 2, ACT, MODE>(p, 1, s);
+    default: break;
   }
+  // skinny: raw split-K GEMM over all weight rows into fp32 partials, then reduce + epilogue
+  const SkinnyPlan sk = plan_skinny(p.N, p.K, (forge_act)ACT);
+  GemmParams q = p;
+  q.N = sk.ncols;
+  q.k_per_split = sk.k_per_split;
+  forge_status st = launch_cfg<64, 64, 2, 2, FORGE_ACT_NONE, MODE_SPLITK>(q, sk.splits, s);
+  if (st != FORGE_OK) return st;
+  GemmParams r = p;
+  const int64_t threads = (int64_t)p.M * ceil_div(p.N, 4);
+  splitk_reduce_kernel<ACT, MODE == MODE_QKV><<<(unsigned)ceil_div64(threads, 256), 256, 0, s>>>(r, sk.splits, sk.ncols);
+  return launch_status();
 }
 
 }  // namespace
 
-size_t gemm_bf16_workspace_bytes(int, int, int, forge_act) { return 0; }
+size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act) {
+  if (choose_variant(M, N, K, act) != V_SKINNY) return 0;
+  const SkinnyPlan sk = plan_skinny(N, K, act);
+  return (size_t)sk.splits * M * sk.ncols * sizeof(float);
+}
 
 const char* gemm_bf16_variant(int M, int N, int K, forge_act act) {
   switch (choose_variant(M, N, K, act)) {
     case V_256x256: return "gemm_bf16<256,256,2,4>";
-    default: return "gemm_bf16<128,128,2,2>";
+    case V_128x128: return "gemm_bf16<128,128,2,2>";
+    default: return "gemm_bf16<64,64,2,2>+splitk";
   }
 }
 
@@ -272,17 +354,22 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   p.M = a.M;
   p.N = a.N;
   p.K = a.K;
+  p.k_per_split = a.K;
+  p.part = (float*)a.workspace;
+  if (gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act) > a.workspace_bytes ||
+      (gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act) > 0 && a.workspace == nullptr))
+    return FORGE_ERR_WORKSPACE;
   if (a.split != nullptr) {
     if (a.act != FORGE_ACT_NONE || a.residual != nullptr) return FORGE_ERR_UNSUPPORTED;
     p.sp = *a.split;
-    return launch_act<FORGE_ACT_NONE, true>(p, s);
+    return launch_act<FORGE_ACT_NONE, MODE_QKV>(p, s);
   }
   switch (a.act) {
-    case FORGE_ACT_NONE: return launch_act<FORGE_ACT_NONE, false>(p, s);
-    case FORGE_ACT_GELU_TANH: return launch_act<FORGE_ACT_GELU_TANH, false>(p, s);
-    case FORGE_ACT_RELU: return launch_act<FORGE_ACT_RELU, false>(p, s);
-    case FORGE_ACT_SILU: return launch_act<FORGE_ACT_SILU, false>(p, s);
-    case FORGE_ACT_SWIGLU: return launch_act<FORGE_ACT_SWIGLU, false>(p, s);
+    case FORGE_ACT_NONE: return launch_act<FORGE_ACT_NONE, MODE_PLAIN>(p, s);
+    case FORGE_ACT_GELU_TANH: return launch_act<FORGE_ACT_GELU_TANH, MODE_PLAIN>(p, s);
+    case FORGE_ACT_RELU: return launch_act<FORGE_ACT_RELU, MODE_PLAIN>(p, s);
+    case FORGE_ACT_SILU: return launch_act<FORGE_ACT_SILU, MODE_PLAIN>(p, s);
+    case FORGE_ACT_SWIGLU: return launch_act<FORGE_ACT_SWIGLU, MODE_PLAIN>(p, s);
     default: return FORGE_ERR_INVALID_ARG;
   }
 }

@@ -50,7 +50,7 @@ def test_residual_norm(F, bf16, kind, rows, d):
 
 # ---------------------------------------------------------------------------------------------
 GEMM_SHAPES = [(128, 2304, 768), (100, 200, 72), (1, 8, 8), (300, 515, 264), (257, 1001, 64),
-               (64, 768, 3072), (513, 384, 136)]
+               (64, 768, 3072), (513, 384, 136), (64, 4096, 512), (33, 130, 1032), (2, 1536, 4096)]
 
 
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
@@ -96,6 +96,10 @@ ATTN_SHAPES = [  # B, Hq, Hkv, Sq, Skv, cap, dh
     (1, 4, 2, 1000, 1000, 1000, 128),
     (2, 3, 3, 700, 700, 704, 64),
     (1, 2, 1, 130, 900, 900, 128),
+    (2, 8, 2, 1, 2049, 2112, 128),
+    (1, 8, 4, 1, 700, 704, 64),
+    (1, 6, 2, 1, 300, 300, 128),
+    (2, 4, 4, 1, 257, 257, 128),
 ]
 
 
