@@ -64,12 +64,12 @@ def test_block_prefill_then_decode(F, sh, bf16):
     kc = np.zeros((B, sh.kv_heads, cap, sh.head_dim)); vc = np.zeros_like(kc)
     ref = O.decoder_block(sh, w, x[:, :S], kc, vc, pos0=0)
     out, tk, tv = run_block(F, sh, w, x[:, :S], bf16, cap)
-    check(out, ref, bf16, "prefill block")
+    check(out, ref, bf16, "prefill block", chain=True)
     check(tk, kc, bf16, "k cache"); check(tv, vc, bf16, "v cache")
     # decode step on the GPU's own cache; the oracle continues from its own
     ref1 = O.decoder_block(sh, w, x[:, S:], kc, vc, pos0=S)
     out1, tk, tv = run_block(F, sh, w, x[:, S:], bf16, cap, pos0=S, kc=tk, vc=tv)
-    check(out1, ref1, bf16, "decode block")
+    check(out1, ref1, bf16, "decode block", chain=True)
     check(tk, kc, bf16, "k cache after decode")
 
 
@@ -86,7 +86,7 @@ def test_block_in_place(F, bf16):
     ws = F.workspace(F.forge_decoder_block_workspace_bytes(desc, 1, 70, 70))
     F.forge_decoder_block(desc, tx, tx, tk, tv, 0, ws)
     torch.cuda.synchronize()
-    check(tx, ref, bf16, "in-place block")
+    check(tx, ref, bf16, "in-place block", chain=True)
 
 
 def test_block_rejects_small_workspace(F):
