@@ -75,7 +75,10 @@ def build_model(wl, F, torch, I):
         layers.append(w)
     mw = {k: dev(v) for k, v in I.model_weights(wl).items()}
     descs = [F.make_block_desc(sh, w) for w in layers]
-    model = F.make_model_desc(descs, mw)
+    # logits rows padded to a multiple of 8 elements (16-byte aligned rows, the usual vocabulary
+    # padding); the padding columns are never written or read
+    logits_ld = (wl.vocab + 7) // 8 * 8
+    model = F.make_model_desc(descs, mw, logits_ld=logits_ld)
 
     B, S = wl.batch, wl.seq
     cap = wl.pos0 + S
@@ -90,7 +93,7 @@ def build_model(wl, F, torch, I):
     if wl.vocab:
         ids_host = I.token_ids(wl.cid, B, S, wl.vocab)
         inp = torch.from_numpy(ids_host).cuda()
-        out = torch.empty(B, S, wl.vocab, device="cuda", dtype=dt)
+        out = torch.empty(B, S, logits_ld, device="cuda", dtype=dt)
     else:
         ids_host = None
         inp = dev(I.hidden_states(wl))
@@ -98,7 +101,7 @@ def build_model(wl, F, torch, I):
     ws = F.workspace(F.forge_model_workspace_bytes(model, B, S, cap))
     keep = (layers, mw, descs)
     return dict(model=model, inp=inp, out=out, kc=kc, vc=vc, ws=ws, keep=keep, ids_host=ids_host,
-                layers=layers, mw=mw, cap=cap)
+                layers=layers, mw=mw, cap=cap, logits_ld=logits_ld)
 
 
 # ---------------------------------------------------------------------------------------------
@@ -196,7 +199,8 @@ def main():
         else:
             key = {"out": ("w_o", "b_o"), "mlp_up": ("w_up", "b_up"), "mlp_down": ("w_down", "b_down")}[name]
         x = torch.randn(M, K, device="cuda", dtype=torch.float32).to(dt)
-        y = torch.empty(M, N, device="cuda", dtype=dt)
+        ld = m["logits_ld"] if name == "lm_head" else N
+        y = torch.empty(M, ld, device="cuda", dtype=dt)
         res = torch.randn(M, N, device="cuda", dtype=torch.float32).to(dt) if name in ("out", "mlp_down") else None
         gws = F.workspace(F.forge_gemm_workspace_bytes(M, N, K, act, dt))
         times = []
@@ -206,13 +210,13 @@ def main():
                     w, b = m["layers"][l][key[0]], m["layers"][l][key[1]]
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
-                F.forge_gemm_bias_gelu(x, w, b, res, y, act, gws)
+                F.forge_gemm_bias_gelu(x, w, b, res, y, act, gws, n=N)
                 e1.record()
                 times.append((e0, e1))
         torch.cuda.synchronize()
         durs = [a.elapsed_time(b_) * 1e-3 for a, b_ in times]
         nw = 2 * N if act == "swiglu" else N
-        sym = "%s act=%s" % (F.forge_gemm_variant(M, N, K, act, dt), act)
+        sym = "%s act=%s" % (F.forge_gemm_variant(M, N, K, act, dt, ldy=ld), act)
         gkey = sym
         gr = groups.setdefault(gkey, {"time": 0.0, "flops": 0.0, "launches": 0, "bytes": 0.0})
         gr["time"] += sum(durs)

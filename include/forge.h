@@ -99,17 +99,20 @@ forge_status forge_attn_fused(const void* q, const void* k, const void* v, void*
  * NULL, y[m,n] = silu(gate[m,n]) * up[m,n].
  * The name is the paper's "linear+gelu" pattern; act = NONE with a residual is its
  * "mm+add" pattern, act = RELU / SILU its other two.
- * Requirements: M,N,K >= 1; K % 8 == 0 for bf16, K % 4 == 0 for fp32.
+ * ldy: row stride of y and residual in elements (0 = dense, N).  A stride that is a multiple of
+ * 8 elements keeps every output row 16-byte aligned, which the fast store path needs; a
+ * vocabulary-sized N such as 50257 is best given a padded stride (50264).
+ * Requirements: M,N,K >= 1; K % 8 == 0 for bf16, K % 4 == 0 for fp32; ldy == 0 or ldy >= N.
  * ------------------------------------------------------------------------------------ */
 size_t forge_gemm_workspace_bytes(int M, int N, int K, forge_act act, forge_dtype dt);
 
 /* Diagnostic: the name of the kernel variant (tile shape and wave layout) that
  * forge_gemm_bias_gelu launches for this problem, e.g. "gemm_bf16<256,256,2,4>"; static
  * storage, never NULL.  Lets a profiler trace be matched to the calls that produced it. */
-const char* forge_gemm_variant(int M, int N, int K, forge_act act, forge_dtype dt);
+const char* forge_gemm_variant(int M, int N, int K, int ldy, forge_act act, forge_dtype dt);
 
 forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias,
-                                  const void* residual, void* y, int M, int N, int K,
+                                  const void* residual, void* y, int M, int N, int K, int ldy,
                                   forge_act act, forge_dtype dt,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
@@ -182,11 +185,13 @@ forge_status forge_decoder_block(const forge_block_desc* desc, const void* x_in,
  * (Sec. "Tied Weight Resolution").
  * layers: HOST array of n_layers descriptors.  wte/wpe NULL: `input` is a hidden state
  * [B,q_len,d] and `output` receives the final normed hidden state [B,q_len,d]; otherwise
- * `input` is int32 ids [B,q_len] and `output` receives logits [B,q_len,vocab].
+ * `input` is int32 ids [B,q_len] and `output` receives logits [B,q_len,vocab] with row stride
+ * logits_ld (padding columns, if any, are left untouched).
  * k_cache, v_cache: [n_layers,B,Hkv,kv_cap,dh].
  * ------------------------------------------------------------------------------------ */
 typedef struct {
   int n_layers, vocab, n_pos;
+  int logits_ld;   /* row stride of the logits in elements; 0 = vocab (dense) */
   const forge_block_desc* layers;
   const void *wte, *wpe, *normf_g, *normf_b;
 } forge_model_desc;

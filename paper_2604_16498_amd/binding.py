@@ -41,7 +41,7 @@ class BlockDesc(C.Structure):
 
 class ModelDesc(C.Structure):
     _fields_ = [
-        ("n_layers", C.c_int), ("vocab", C.c_int), ("n_pos", C.c_int),
+        ("n_layers", C.c_int), ("vocab", C.c_int), ("n_pos", C.c_int), ("logits_ld", C.c_int),
         ("layers", C.POINTER(BlockDesc)),
         ("wte", C.c_void_p), ("wpe", C.c_void_p), ("normf_g", C.c_void_p), ("normf_b", C.c_void_p),
     ]
@@ -58,8 +58,8 @@ SIGNATURES = {
     "forge_attn_fused_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i, _i]),
     "forge_attn_fused": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _i, _vp, _sz, _vp]),
     "forge_gemm_workspace_bytes": (_sz, [_i, _i, _i, _i, _i]),
-    "forge_gemm_variant": (C.c_char_p, [_i, _i, _i, _i, _i]),
-    "forge_gemm_bias_gelu": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
+    "forge_gemm_variant": (C.c_char_p, [_i, _i, _i, _i, _i, _i]),
+    "forge_gemm_bias_gelu": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
     "forge_residual_norm": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _f, _i, _i, _vp]),
     "forge_rope": (_i, [_vp, _i, _i, _i, _i, _i64, _i64, _i, _i, _f, _i, _vp]),
     "forge_embed": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp]),
@@ -152,18 +152,20 @@ def forge_gemm_workspace_bytes(M, N, K, act, dtype) -> int:
     return lib().forge_gemm_workspace_bytes(M, N, K, ACT[act], dt)
 
 
-def forge_gemm_variant(M, N, K, act, dtype) -> str:
+def forge_gemm_variant(M, N, K, act, dtype, ldy=0) -> str:
     dt = FORGE_BF16 if dtype == torch.bfloat16 else FORGE_F32
-    return lib().forge_gemm_variant(M, N, K, ACT[act], dt).decode()
+    return lib().forge_gemm_variant(M, N, K, ldy, ACT[act], dt).decode()
 
 
-def forge_gemm_bias_gelu(x, w, bias, residual, y, act="gelu_tanh", workspace=None):
-    """y[M,N] = act(x[M,K] w[N,K]^T + bias) (+ residual); swiglu: w is [2N,K]."""
+def forge_gemm_bias_gelu(x, w, bias, residual, y, act="gelu_tanh", workspace=None, n=None):
+    """y[M,:N] = act(x[M,K] w[N,K]^T + bias) (+ residual); swiglu: w is [2N,K].
+    y (and residual) may be wider than N (row stride y.shape[1]); pass n=N then."""
     M, K = x.shape
-    N = y.shape[1]
+    ldy = y.shape[1]
+    N = ldy if n is None else n
     wp, wb = _ws(workspace)
-    _check(lib().forge_gemm_bias_gelu(_p(x), _p(w), _p(bias), _p(residual), _p(y), M, N, K, ACT[act],
-                                      _dt(x), wp, wb, _stream()), "forge_gemm_bias_gelu")
+    _check(lib().forge_gemm_bias_gelu(_p(x), _p(w), _p(bias), _p(residual), _p(y), M, N, K, ldy,
+                                      ACT[act], _dt(x), wp, wb, _stream()), "forge_gemm_bias_gelu")
     return y
 
 
@@ -225,7 +227,8 @@ def forge_decoder_block(desc: BlockDesc, x_in, x_out, k_cache, v_cache, pos0, wo
     return x_out
 
 
-def make_model_desc(layer_descs: Sequence[BlockDesc], mw: Dict[str, Optional[torch.Tensor]]) -> ModelDesc:
+def make_model_desc(layer_descs: Sequence[BlockDesc], mw: Dict[str, Optional[torch.Tensor]],
+                    logits_ld: int = 0) -> ModelDesc:
     """mw: wte, wpe (both or neither), normf_g, normf_b.  Keeps the layer array alive on the struct."""
     m = ModelDesc()
     arr = (BlockDesc * len(layer_descs))(*layer_descs)
@@ -235,6 +238,7 @@ def make_model_desc(layer_descs: Sequence[BlockDesc], mw: Dict[str, Optional[tor
     wte, wpe = mw.get("wte"), mw.get("wpe")
     m.vocab = 0 if wte is None else wte.shape[0]
     m.n_pos = 0 if wpe is None else wpe.shape[0]
+    m.logits_ld = logits_ld
     for name in ("wte", "wpe", "normf_g", "normf_b"):
         t = mw.get(name)
         setattr(m, name, None if t is None else t.data_ptr())

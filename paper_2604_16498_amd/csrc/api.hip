@@ -111,7 +111,7 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
   if (st != FORGE_OK) return st;
   // 2. QKV projection, written head-major: q to the workspace, k and v into the cache rows
   QkvSplit sp = {q, k_cache, v_cache, d->q_heads, d->kv_heads, dh, q_len, kv_cap, pos0};
-  GemmArgs g = {y, d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, FORGE_ACT_NONE, &sp, gws, pl.gemm};
+  GemmArgs g = {y, d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, 0, FORGE_ACT_NONE, &sp, gws, pl.gemm};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
   // 3. rotary embedding of the new q and k rows
@@ -128,18 +128,18 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
   st = attn_dispatch(at, d->dt, s);
   if (st != FORGE_OK) return st;
   // 5. output projection + bias + residual
-  g = GemmArgs{o, d->w_o, d->b_o, x_in, x_out, T, dm, hd, FORGE_ACT_NONE, nullptr, gws, pl.gemm};
+  g = GemmArgs{o, d->w_o, d->b_o, x_in, x_out, T, dm, hd, 0, FORGE_ACT_NONE, nullptr, gws, pl.gemm};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
   // 6. second norm
   st = launch_residual_norm(x_out, nullptr, d->norm2_g, d->norm2_b, nullptr, y, T, dm, d->eps, d->norm, d->dt, s);
   if (st != FORGE_OK) return st;
   // 7. MLP up projection + bias + activation (SwiGLU: gate and up in one pass)
-  g = GemmArgs{y, d->w_up, d->b_up, nullptr, u, T, d->d_ff, dm, d->mlp_act, nullptr, gws, pl.gemm};
+  g = GemmArgs{y, d->w_up, d->b_up, nullptr, u, T, d->d_ff, dm, 0, d->mlp_act, nullptr, gws, pl.gemm};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
   // 8. MLP down projection + bias + residual
-  g = GemmArgs{u, d->w_down, d->b_down, x_out, x_out, T, dm, d->d_ff, FORGE_ACT_NONE, nullptr, gws, pl.gemm};
+  g = GemmArgs{u, d->w_down, d->b_down, x_out, x_out, T, dm, d->d_ff, 0, FORGE_ACT_NONE, nullptr, gws, pl.gemm};
   return gemm_dispatch(g, d->dt, s);
 }
 
@@ -215,24 +215,24 @@ size_t forge_gemm_workspace_bytes(int M, int N, int K, forge_act act, forge_dtyp
   return gemm_ws(M, N, K, act, dt);
 }
 
-const char* forge_gemm_variant(int M, int N, int K, forge_act act, forge_dtype dt) {
+const char* forge_gemm_variant(int M, int N, int K, int ldy, forge_act act, forge_dtype dt) {
   if (M < 1 || N < 1 || K < 1) return "none";
-  return dt == FORGE_BF16 ? gemm_bf16_variant(M, N, K, act) : "gemm_f32<64,64,2,2>";
+  return dt == FORGE_BF16 ? gemm_bf16_variant(M, N, K, ldy > 0 ? ldy : N, act) : "gemm_f32<64,64,2,2>";
 }
 
 forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias,
-                                  const void* residual, void* y, int M, int N, int K, forge_act act,
-                                  forge_dtype dt, void* workspace, size_t workspace_bytes,
-                                  void* stream) {
+                                  const void* residual, void* y, int M, int N, int K, int ldy,
+                                  forge_act act, forge_dtype dt, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
   if (!dtype_ok(dt) || !req(x) || !req(w) || !req(y) || !opt(bias) || !opt(residual) || !opt(workspace))
     return FORGE_ERR_INVALID_ARG;
-  if (M < 1 || N < 1 || K < 1) return FORGE_ERR_INVALID_ARG;
+  if (M < 1 || N < 1 || K < 1 || ldy < 0 || (ldy > 0 && ldy < N)) return FORGE_ERR_INVALID_ARG;
   if (act < FORGE_ACT_NONE || act > FORGE_ACT_SWIGLU) return FORGE_ERR_INVALID_ARG;
   if (K % (dt == FORGE_BF16 ? 8 : 4) != 0) return FORGE_ERR_UNSUPPORTED;
   if (y == x || y == w) return FORGE_ERR_INVALID_ARG;
   const size_t need = gemm_ws(M, N, K, act, dt);
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FORGE_ERR_WORKSPACE;
-  GemmArgs a = {x, w, bias, residual, y, M, N, K, act, nullptr, workspace, workspace_bytes};
+  GemmArgs a = {x, w, bias, residual, y, M, N, K, ldy, act, nullptr, workspace, workspace_bytes};
   return gemm_dispatch(a, dt, static_cast<hipStream_t>(stream));
 }
 
@@ -307,6 +307,7 @@ static forge_status check_model(const forge_model_desc* m) {
   if ((m->wte == nullptr) != (m->wpe == nullptr)) return FORGE_ERR_INVALID_ARG;
   if (m->wte != nullptr && (!req(m->wte) || !req(m->wpe) || m->vocab < 1 || m->n_pos < 1))
     return FORGE_ERR_INVALID_ARG;
+  if (m->logits_ld != 0 && m->logits_ld < m->vocab) return FORGE_ERR_INVALID_ARG;
   return FORGE_OK;
 }
 
@@ -355,7 +356,7 @@ forge_status forge_model_forward(const forge_model_desc* model, const void* inpu
                             d0->norm, dt, s);
   if (st != FORGE_OK || !tokens) return st;
   // tied LM head: the token table is the weight of the last projection
-  GemmArgs g = {yf, model->wte, nullptr, nullptr, output, T, model->vocab, dm, FORGE_ACT_NONE,
+  GemmArgs g = {yf, model->wte, nullptr, nullptr, output, T, model->vocab, dm, model->logits_ld, FORGE_ACT_NONE,
                 nullptr, bws, pl.block};
   return gemm_dispatch(g, dt, s);
 }

@@ -133,6 +133,7 @@ struct GemmArgs {
   const void* residual;
   void* y;
   int M, N, K;            // N = number of OUTPUT columns (SWIGLU: w has 2N rows)
+  int ldy;                // row stride of y and residual in elements (0: N)
   forge_act act;
   const QkvSplit* split;  // NULL: plain row-major output
   void* workspace;
@@ -142,7 +143,7 @@ struct GemmArgs {
 forge_status launch_gemm_f32(const GemmArgs& a, hipStream_t s);
 forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
 size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act);
-const char* gemm_bf16_variant(int M, int N, int K, forge_act act);
+const char* gemm_bf16_variant(int M, int N, int K, int ldy, forge_act act);
 size_t gemm_f32_workspace_bytes(int M, int N, int K, forge_act act);
 
 struct AttnArgs {

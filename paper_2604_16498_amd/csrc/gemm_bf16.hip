@@ -5,25 +5,37 @@
 // operand is ever transposed.  Accumulation is fp32; bias, activation and the residual are
 // applied to the accumulator and the result is rounded to bf16 once, at the store.
 //
-// Tiling (template parameters): a block of WM x WN waves owns a BM x BN tile of y; each wave
-// owns (BM/WM) x (BN/WN) as TM x TN accumulators of 32 x 32.  K is walked in slabs of 64.  The
-// x and w slabs go HBM -> registers -> LDS with 128-bit accesses, double buffered: the loads of
-// slab k+1 are issued before the MFMAs of slab k and stored to the other LDS buffer after them
-// (one barrier per slab).
+// Two kernels share the tiling (a block of WM x WN waves owns a BM x BN tile of y, each wave
+// (BM/WM) x (BN/WN) as TM x TN accumulators of 32 x 32, K walked in slabs of 64):
 //
-// LDS layout: a slab row is 64 bf16 = 8 chunks of 16 B; chunk c of row r is stored at chunk
+//  * gemm_bf16_dlds_kernel -- the fast path (K % 64 == 0, output rows 16-byte aligned).
+//    Slabs go HBM -> LDS directly (global_load_lds_dwordx4: each wave-wide load drops 1 KB into
+//    LDS at lane*16, no staging registers, no LDS store instructions) into a 2-stage ring: the
+//    loads of slab k+1 are in flight while slab k is multiplied; one barrier per slab.
+//    w is the MFMA A operand and x the B operand, so an accumulator holds D[n, m]: a lane owns
+//    ONE output row m and, after a permlane32 swap of register groups, two runs of 8 consecutive
+//    columns -- bias, residual and y move as 128-bit accesses, and the QKV head split needs one
+//    (batch, position) division per lane instead of one per element.
+//  * gemm_bf16_generic_kernel -- any K % 8 == 0 and any row stride: HBM -> registers -> LDS
+//    double buffering with zero fill of the K tail, x as the A operand, element stores.
+//
+// LDS layout (both): a slab row is 64 bf16 = 8 chunks of 16 B; chunk c of row r sits at chunk
 // position c ^ ((r >> 1) & 7).  A fragment read has lanes 0-31 on 32 consecutive rows at one
-// logical chunk; with the swizzle any 16 consecutive rows hit 16 distinct 16-byte bank groups
-// (two rows fill the 64 x 4 B banks), so 128-bit reads are conflict free.
+// logical chunk; with the swizzle any 16 consecutive rows hit 16 distinct 16-byte bank groups,
+// so the 128-bit reads are conflict free.  The direct loads apply the inverse mapping on the
+// global side: the lane that lands on (row, position p) fetches logical chunk p ^ f(row).
 //
 // SwiGLU: the w slab of a block is half gate rows and half up rows of the SAME output columns,
-// arranged so that accumulator (tm, t) is the gate and (tm, t + TN/2) the up projection of one
+// arranged so that accumulator (., t) is the gate and (., t + TN/2) the up projection of one
 // column block; the epilogue writes silu(gate) * up and no extra accumulators are needed.
 //
 // Work-group order: blocks are dealt round-robin over the 8 XCDs (each with its own L2), so the
 // block id is first remapped to give every XCD one contiguous run of tiles, and tiles are
-// numbered in groups of GROUP_M tile rows, column-major inside a group, so that the tiles
-// resident in one XCD at a time share x and w panels in that L2.
+// numbered in groups of 8 tile rows, column-major inside a group, so that the tiles resident in
+// one XCD at a time share x and w panels in that L2.
+//
+// M <= 64 (decode): the weight is streamed once; 64 x 64 tiles, K split over grid.y so that at
+// least 512 blocks run, fp32 partials, and a fixed-order reduce kernel that carries the epilogue.
 #include "common.hpp"
 
 namespace forge {
@@ -56,6 +68,7 @@ struct GemmParams {
   const bf16* residual;
   bf16* y;
   int M, N, K;        // N: output columns
+  int ldy;            // row stride of y and residual (elements)
   int tiles_m, tiles_n;
   int k_per_split;    // split-K: k range of one block (multiple of 64); otherwise >= K
   float* part;        // split-K: fp32 partial sums [splits, M, N]
@@ -65,7 +78,7 @@ struct GemmParams {
 enum Mode { MODE_PLAIN = 0, MODE_QKV = 1, MODE_SPLITK = 2 };
 
 template <int BM, int BN, int WM, int WN, int ACT, int MODE>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmParams p) {
+__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_generic_kernel(GemmParams p) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr bool SWIGLU = ACT == FORGE_ACT_SWIGLU;
@@ -217,8 +230,221 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(GemmParams p) {
         if (MODE == MODE_QKV) {
           *split_dst_bf16(p.sp, m, n) = (bf16)val;
         } else {
-          if (p.residual != nullptr) val += (float)p.residual[(int64_t)m * N + n];
-          p.y[(int64_t)m * N + n] = (bf16)val;
+          if (p.residual != nullptr) val += (float)p.residual[(int64_t)m * p.ldy + n];
+          p.y[(int64_t)m * p.ldy + n] = (bf16)val;
+        }
+      }
+    }
+  }
+}
+
+typedef __attribute__((address_space(3))) void lds_void;
+
+// Fast path, see the file header.  STAGES = 2.
+template <int BM, int BN, int WM, int WN, int ACT, int MODE>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dlds_kernel(GemmParams p) {
+  constexpr int NW = WM * WN;
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr bool SWIGLU = ACT == FORGE_ACT_SWIGLU;
+  constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+  constexpr int TN_OUT = SWIGLU ? TN / 2 : TN;
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+  constexpr int IA = BM / 8 / NW, IB = BN / 8 / NW;   // wave-wide 1 KB loads per wave per slab
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile / wave mismatch");
+  static_assert(!SWIGLU || TN % 2 == 0, "SwiGLU pairs accumulators");
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // [A0 | B0 | A1 | B1]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  int tile;
+  {
+    const int pid = blockIdx.x, nwg = gridDim.x;   // grid.y indexes the k split
+    const int xcd = pid & 7, idx = pid >> 3;
+    const int per = nwg >> 3, rem = nwg & 7;
+    tile = xcd * per + min(xcd, rem) + idx;
+  }
+  constexpr int GROUP_M = 8;
+  const int in_group = GROUP_M * p.tiles_n;
+  const int group = tile / in_group;
+  const int first_m = group * GROUP_M;
+  const int gsz = min(p.tiles_m - first_m, GROUP_M);
+  const int tile_m = first_m + (tile % in_group) % gsz;
+  const int tile_n = (tile % in_group) / gsz;
+  const int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
+  const int M = p.M, N = p.N, K = p.K;
+
+  // ---- direct-to-LDS copy plan ---------------------------------------------------------------
+  // wave-wide load i of this wave fills LDS rows (i*NW + wave)*8 .. +8 of a slab (1 KB at
+  // lane*16): lane -> (row = base + lane/8, position = lane%8) -> logical chunk = position ^ f(row)
+  const bf16* a_src[IA];
+  const bf16* b_src[IB];
+#pragma unroll
+  for (int i = 0; i < IA; ++i) {
+    const int r = (i * NW + wave) * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    a_src[i] = p.x + (int64_t)min(m0 + r, M - 1) * K + c * 8;   // rows past the end re-read the last row
+  }
+#pragma unroll
+  for (int i = 0; i < IB; ++i) {
+    const int r = (i * NW + wave) * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    int gn;
+    if (SWIGLU) {
+      const int wcol = r / (32 * TN), t = (r / 32) % TN, rr = r % 32;
+      const int col = n0 + (wcol * (TN / 2) + t % (TN / 2)) * 32 + rr;
+      gn = min(col, N - 1) + (t >= TN / 2 ? N : 0);
+    } else {
+      gn = min(n0 + r, N - 1);
+    }
+    b_src[i] = p.w + (int64_t)gn * K + c * 8;
+  }
+  auto issue = [&](int k0, int buf) {
+    char* sa = smem + buf * STAGE;
+    char* sb = sa + A_BYTES;
+#pragma unroll
+    for (int i = 0; i < IA; ++i)
+      __builtin_amdgcn_global_load_lds((const void*)(a_src[i] + k0), (lds_void*)(sa + (i * NW + wave) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < IB; ++i)
+      __builtin_amdgcn_global_load_lds((const void*)(b_src[i] + k0), (lds_void*)(sb + (i * NW + wave) * 1024), 16, 0, 0);
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int fr = lane & 31, fh = lane >> 5;
+  auto compute = [&](int buf) {
+    const char* sa = smem + buf * STAGE;
+    const char* sb = sa + A_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        fa[i] = *reinterpret_cast<const bf16x8*>(sa + lds_chunk_off((wm * TM + i) * 32 + fr, 2 * ks + fh));
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        fb[j] = *reinterpret_cast<const bf16x8*>(sb + lds_chunk_off((wn * TN + j) * 32 + fr, 2 * ks + fh));
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)   // D[n, m]: w fragment is the A operand
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  const int k_begin = MODE == MODE_SPLITK ? blockIdx.y * p.k_per_split : 0;
+  const int k_end = MODE == MODE_SPLITK ? min(K, k_begin + p.k_per_split) : K;
+  const int nk = (k_end - k_begin) / BK;
+  issue(k_begin, 0);
+  for (int kt = 0; kt < nk; ++kt) {
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this thread's loads of slab kt are in LDS
+    __syncthreads();                      // everyone's are; everyone is done reading the other buffer
+    if (kt + 1 < nk) issue(k_begin + (kt + 1) * BK, (kt + 1) & 1);
+    compute(kt & 1);
+  }
+
+  // ---- epilogue: lane = output row m; registers = columns ---------------------------------------
+  // register v of accumulator (i, j) is column 8(v/4) + 4 fh + v%4 of its 32-column block.  Swapping
+  // register groups (0,2) and (1,3) between lanes l and l^32 leaves lanes 0-31 with columns 0..15 and
+  // lanes 32-63 with columns 16..31, each as two runs of 8 consecutive columns.
+  auto runs_of = [&](const floatx16& a, float (&run)[2][8]) {
+#pragma unroll
+    for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(a[4 * gp + r]),
+                                                   __float_as_uint(a[4 * (gp + 2) + r]), false, false);
+        run[gp][r] = __uint_as_float(sw[0]);
+        run[gp][4 + r] = __uint_as_float(sw[1]);
+      }
+  };
+  const bool vec_y = (p.ldy & 7) == 0;          // plain mode: rows of y / residual 16-byte aligned
+  const bool vec_part = (N & 3) == 0;           // split-K mode: rows of the fp32 partials aligned
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = m0 + (wm * TM + i) * 32 + fr;
+    const bool row_ok = m < M;
+    int sb_ = 0, ss_ = 0;
+    if (MODE == MODE_QKV) { sb_ = m / p.sp.q_len; ss_ = m - sb_ * p.sp.q_len; }
+#pragma unroll
+    for (int j = 0; j < TN_OUT; ++j) {
+      float run[2][8], run2[2][8];
+      runs_of(acc[i][j], run);
+      if (SWIGLU) runs_of(acc[i][SWIGLU ? j + TN / 2 : j], run2);
+      const int nb = n0 + (wn * TN_OUT + j) * 32 + 16 * fh;
+#pragma unroll
+      for (int gp = 0; gp < 2; ++gp) {
+        const int n = nb + 8 * gp;
+        if (!row_ok || n >= N) continue;
+        const bool full = n + 8 <= N;
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = run[gp][e];
+        if (MODE == MODE_SPLITK) {     // raw partial sums; the reduce kernel carries the epilogue
+          float* dst = p.part + ((int64_t)blockIdx.y * M + m) * N + n;
+          if (full && vec_part) {
+            Vec8<float>::store(dst, o);
+          } else {
+            for (int e = 0; e < 8 && n + e < N; ++e) dst[e] = o[e];
+          }
+          continue;
+        }
+        if (p.bias != nullptr) {
+          if (full) {
+            float bb[8];
+            Vec8<bf16>::load(p.bias + n, bb);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] += bb[e];
+            if (SWIGLU) {
+              Vec8<bf16>::load(p.bias + N + n, bb);     // N % 8 == 0 is checked by the host for SwiGLU
+#pragma unroll
+              for (int e = 0; e < 8; ++e) run2[gp][e] += bb[e];
+            }
+          } else {
+            for (int e = 0; e < 8 && n + e < N; ++e) {
+              o[e] += (float)p.bias[n + e];
+              if (SWIGLU) run2[gp][e] += (float)p.bias[N + n + e];
+            }
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = SWIGLU ? silu_f(o[e]) * run2[gp][e] : apply_act<ACT>(o[e]);
+        if (MODE == MODE_QKV) {
+          // 8 consecutive columns never straddle a head (head_dim % 8 == 0, n % 8 == 0)
+          const int dh = p.sp.head_dim, nq = p.sp.q_heads * dh, nkv = p.sp.kv_heads * dh;
+          bf16* dst;
+          if (n < nq) {
+            dst = (bf16*)p.sp.q + (((int64_t)sb_ * p.sp.q_heads + n / dh) * p.sp.q_len + ss_) * dh + n % dh;
+          } else {
+            const bool is_k = n < nq + nkv;
+            const int nn = is_k ? n - nq : n - nq - nkv;
+            dst = (bf16*)(is_k ? p.sp.k_cache : p.sp.v_cache) +
+                  (((int64_t)sb_ * p.sp.kv_heads + nn / dh) * p.sp.kv_cap + p.sp.pos0 + ss_) * dh + nn % dh;
+          }
+          Vec8<bf16>::store(dst, o);     // the host checks N % 8 == 0 for the split
+          continue;
+        }
+        const int64_t at = (int64_t)m * p.ldy + n;
+        if (full && vec_y) {
+          if (p.residual != nullptr) {
+            float rr[8];
+            Vec8<bf16>::load(p.residual + at, rr);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] += rr[e];
+          }
+          Vec8<bf16>::store(p.y + at, o);
+        } else {
+          for (int e = 0; e < 8 && n + e < N; ++e) {
+            float val = o[e];
+            if (p.residual != nullptr) val += (float)p.residual[at + e];
+            p.y[at + e] = (bf16)val;
+          }
         }
       }
     }
@@ -254,20 +480,21 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p, int sp
     if (QKV) {
       *split_dst_bf16(p.sp, m, n) = (bf16)val;
     } else {
-      if (p.residual != nullptr) val += (float)p.residual[(int64_t)m * N + n];
-      p.y[(int64_t)m * N + n] = (bf16)val;
+      if (p.residual != nullptr) val += (float)p.residual[(int64_t)m * p.ldy + n];
+      p.y[(int64_t)m * p.ldy + n] = (bf16)val;
     }
   }
 }
 
-template <int BM, int BN, int WM, int WN, int ACT, int MODE>
+template <bool FAST, int BM, int BN, int WM, int WN, int ACT, int MODE>
 forge_status launch_cfg(const GemmParams& p0, int splits, hipStream_t s) {
   GemmParams p = p0;
   constexpr int BN_OUT = ACT == FORGE_ACT_SWIGLU ? BN / 2 : BN;
   p.tiles_m = ceil_div(p.M, BM);
   p.tiles_n = ceil_div(p.N, BN_OUT);
   constexpr int smem = 2 * (BM + BN) * BK * 2;
-  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, ACT, MODE>;
+  auto kern = FAST ? gemm_bf16_dlds_kernel<BM, BN, WM, WN, ACT, MODE>
+                   : gemm_bf16_generic_kernel<BM, BN, WM, WN, ACT, MODE>;
   static bool configured = false;   // idempotent attribute, set once per instantiation
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -280,14 +507,17 @@ forge_status launch_cfg(const GemmParams& p0, int splits, hipStream_t s) {
   return launch_status();
 }
 
-// tile choice: big tiles when they still give every CU work, smaller ones otherwise; problems
-// with at most 64 rows (decode) stream the weight once and are split over K to fill the chip
-enum Variant { V_256x256 = 0, V_128x128 = 1, V_SKINNY = 2 };
-inline Variant choose_variant(int M, int N, int K, forge_act act) {
-  (void)K;
-  if (M <= 64) return V_SKINNY;
+// Which kernel and tile a problem gets.  Fast path: K a multiple of the slab and 16-byte aligned
+// output rows (the head split and the fp32 partials have their own alignment rules).
+enum Variant { V_FAST_256 = 0, V_FAST_128 = 1, V_GEN_256 = 2, V_GEN_128 = 3, V_SKINNY_FAST = 4, V_SKINNY_GEN = 5 };
+inline Variant choose_variant(int M, int N, int K, int ldy, forge_act act, bool qkv) {
+  const bool k_ok = K % BK == 0;
+  if (M <= 64) return k_ok ? V_SKINNY_FAST : V_SKINNY_GEN;
+  const bool rows_ok = qkv ? N % 8 == 0 : (ldy % 8 == 0 && (act != FORGE_ACT_SWIGLU || N % 8 == 0));
+  const bool fast = k_ok && rows_ok;
   const int64_t big = (int64_t)ceil_div(M, 256) * ceil_div(N, act == FORGE_ACT_SWIGLU ? 128 : 256);
-  return big >= 512 ? V_256x256 : V_128x128;
+  if (big >= 512) return fast ? V_FAST_256 : V_GEN_256;
+  return fast ? V_FAST_128 : V_GEN_128;
 }
 
 struct SkinnyPlan {
@@ -310,9 +540,12 @@ inline SkinnyPlan plan_skinny(int N, int K, forge_act act) {
 
 template <int ACT, int MODE>
 forge_status launch_act(const GemmParams& p, hipStream_t s) {
-  switch (choose_variant(p.M, p.N, p.K, (forge_act)ACT)) {
-    case V_256x256: return launch_cfg<256, 256, 2, 4, ACT, MODE>(p, 1, s);
-    case V_128x128: return launch_cfg<128, 128, 2, 2, ACT, MODE>(p, 1, s);
+  const Variant v = choose_variant(p.M, p.N, p.K, p.ldy, (forge_act)ACT, MODE == MODE_QKV);
+  switch (v) {
+    case V_FAST_256: return launch_cfg<true, 256, 256, 2, 4, ACT, MODE>(p, 1, s);
+    case V_FAST_128: return launch_cfg<true, 128, 128, 2, 2, ACT, MODE>(p, 1, s);
+    case V_GEN_256: return launch_cfg<false, 256, 256, 2, 4, ACT, MODE>(p, 1, s);
+    case V_GEN_128: return launch_cfg<false, 128, 128, 2, 2, ACT, MODE>(p, 1, s);
     default: break;
   }
   // skinny: raw split-K GEMM over all weight rows into fp32 partials, then reduce + epilogue
@@ -320,27 +553,31 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
   GemmParams q = p;
   q.N = sk.ncols;
   q.k_per_split = sk.k_per_split;
-  forge_status st = launch_cfg<64, 64, 2, 2, FORGE_ACT_NONE, MODE_SPLITK>(q, sk.splits, s);
+  forge_status st = v == V_SKINNY_FAST
+      ? launch_cfg<true, 64, 64, 2, 2, FORGE_ACT_NONE, MODE_SPLITK>(q, sk.splits, s)
+      : launch_cfg<false, 64, 64, 2, 2, FORGE_ACT_NONE, MODE_SPLITK>(q, sk.splits, s);
   if (st != FORGE_OK) return st;
-  GemmParams r = p;
   const int64_t threads = (int64_t)p.M * ceil_div(p.N, 4);
-  splitk_reduce_kernel<ACT, MODE == MODE_QKV><<<(unsigned)ceil_div64(threads, 256), 256, 0, s>>>(r, sk.splits, sk.ncols);
+  splitk_reduce_kernel<ACT, MODE == MODE_QKV><<<(unsigned)ceil_div64(threads, 256), 256, 0, s>>>(p, sk.splits, sk.ncols);
   return launch_status();
 }
 
 }  // namespace
 
 size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act) {
-  if (choose_variant(M, N, K, act) != V_SKINNY) return 0;
+  if (M > 64) return 0;
   const SkinnyPlan sk = plan_skinny(N, K, act);
   return (size_t)sk.splits * M * sk.ncols * sizeof(float);
 }
 
-const char* gemm_bf16_variant(int M, int N, int K, forge_act act) {
-  switch (choose_variant(M, N, K, act)) {
-    case V_256x256: return "gemm_bf16<256,256,2,4>";
-    case V_128x128: return "gemm_bf16<128,128,2,2>";
-    default: return "gemm_bf16<64,64,2,2>+splitk";
+const char* gemm_bf16_variant(int M, int N, int K, int ldy, forge_act act) {
+  switch (choose_variant(M, N, K, ldy, act, false)) {
+    case V_FAST_256: return "gemm_bf16_dlds<256,256,2,4>";
+    case V_FAST_128: return "gemm_bf16_dlds<128,128,2,2>";
+    case V_GEN_256: return "gemm_bf16_generic<256,256,2,4>";
+    case V_GEN_128: return "gemm_bf16_generic<128,128,2,2>";
+    case V_SKINNY_FAST: return "gemm_bf16_dlds<64,64,2,2>+splitk";
+    default: return "gemm_bf16_generic<64,64,2,2>+splitk";
   }
 }
 
@@ -354,11 +591,11 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   p.M = a.M;
   p.N = a.N;
   p.K = a.K;
+  p.ldy = a.ldy > 0 ? a.ldy : a.N;
   p.k_per_split = a.K;
   p.part = (float*)a.workspace;
-  if (gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act) > a.workspace_bytes ||
-      (gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act) > 0 && a.workspace == nullptr))
-    return FORGE_ERR_WORKSPACE;
+  const size_t need = gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act);
+  if (need > a.workspace_bytes || (need > 0 && a.workspace == nullptr)) return FORGE_ERR_WORKSPACE;
   if (a.split != nullptr) {
     if (a.act != FORGE_ACT_NONE || a.residual != nullptr) return FORGE_ERR_UNSUPPORTED;
     p.sp = *a.split;

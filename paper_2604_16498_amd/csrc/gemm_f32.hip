@@ -34,7 +34,7 @@ __device__ inline void* split_dst(const QkvSplit& sp, int m, int n, size_t esz) 
 template <int ACT, bool SPLIT>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const float* __restrict__ x, const float* __restrict__ w, const float* __restrict__ bias,
-    const float* residual, float* y, int M, int N, int K, QkvSplit sp) {
+    const float* residual, float* y, int M, int N, int K, int ldy, QkvSplit sp) {
   constexpr bool SWIGLU = ACT == FORGE_ACT_SWIGLU;
   constexpr int NB = SWIGLU ? 2 : 1;
   __shared__ __attribute__((aligned(16))) float As[BM][LDK];
@@ -105,8 +105,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     if (SPLIT) {
       *reinterpret_cast<float*>(split_dst(sp, m, n, sizeof(float))) = val;
     } else {
-      if (residual != nullptr) val += residual[(int64_t)m * N + n];
-      y[(int64_t)m * N + n] = val;
+      if (residual != nullptr) val += residual[(int64_t)m * ldy + n];
+      y[(int64_t)m * ldy + n] = val;
     }
   }
 }
@@ -123,15 +123,16 @@ forge_status launch_gemm_f32(const GemmArgs& a, hipStream_t s) {
   const float* res = (const float*)a.residual;
   float* y = (float*)a.y;
   QkvSplit sp = {};
+  const int ldy = a.ldy > 0 ? a.ldy : a.N;
   if (a.split != nullptr) {
     if (a.act != FORGE_ACT_NONE || a.residual != nullptr) return FORGE_ERR_UNSUPPORTED;
     sp = *a.split;
-    gemm_f32_kernel<FORGE_ACT_NONE, true><<<grid, block, 0, s>>>(x, w, bias, res, y, a.M, a.N, a.K, sp);
+    gemm_f32_kernel<FORGE_ACT_NONE, true><<<grid, block, 0, s>>>(x, w, bias, res, y, a.M, a.N, a.K, ldy, sp);
     return launch_status();
   }
   switch (a.act) {
 #define FORGE_CASE(ACT) \
-  case ACT: gemm_f32_kernel<ACT, false><<<grid, block, 0, s>>>(x, w, bias, res, y, a.M, a.N, a.K, sp); break
+  case ACT: gemm_f32_kernel<ACT, false><<<grid, block, 0, s>>>(x, w, bias, res, y, a.M, a.N, a.K, ldy, sp); break
     FORGE_CASE(FORGE_ACT_NONE);
     FORGE_CASE(FORGE_ACT_GELU_TANH);
     FORGE_CASE(FORGE_ACT_RELU);

@@ -61,9 +61,10 @@ def test_argument_errors_are_caught_on_the_host():
     assert l.forge_residual_norm(good, None, good, None, None, vp(0x2000), 4, 60, 1e-5, 0, 0, None) == 2
     assert l.forge_residual_norm(good, None, good, None, None, vp(0x2000), 0, 64, 1e-5, 0, 0, None) == 1
     # gemm: K not a multiple of 8 for bf16; y aliasing x
-    assert l.forge_gemm_bias_gelu(good, vp(0x2000), None, None, vp(0x3000), 4, 4, 12, 0, 1, None, 0, None) == 2
-    assert l.forge_gemm_bias_gelu(good, vp(0x2000), None, None, good, 4, 4, 16, 0, 1, None, 0, None) == 1
-    assert l.forge_gemm_bias_gelu(good, vp(0x2000), None, None, vp(0x3000), 4, 4, 16, 9, 1, None, 0, None) == 1
+    assert l.forge_gemm_bias_gelu(good, vp(0x2000), None, None, vp(0x3000), 4, 4, 12, 0, 0, 1, None, 0, None) == 2
+    assert l.forge_gemm_bias_gelu(good, vp(0x2000), None, None, good, 4, 4, 16, 0, 0, 1, None, 0, None) == 1
+    assert l.forge_gemm_bias_gelu(good, vp(0x2000), None, None, vp(0x3000), 4, 4, 16, 0, 9, 1, None, 0, None) == 1
+    assert l.forge_gemm_bias_gelu(good, vp(0x2000), None, None, vp(0x3000), 4, 4, 16, 3, 0, 1, None, 0, None) == 1   # ldy < N
     # attention: head dim, head ratio, causal with kv_len < q_len
     a = (good, vp(0x2000), vp(0x3000), vp(0x4000))
     assert l.forge_attn_fused(*a, 1, 4, 4, 8, 8, 32, 4 * 8 * 32, 8 * 32, 0.1, 1, 1, None, 0, None) == 2

@@ -100,9 +100,11 @@ def test_block_rejects_small_workspace(F):
     assert e.value.status == 3
 
 
+@pytest.mark.parametrize("ld", [0, 1008], ids=["dense", "padded"])
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
-def test_model_forward_tokens(F, bf16):
-    """Small GPT-shaped model with embedding and tied head, odd vocabulary size."""
+def test_model_forward_tokens(F, bf16, ld):
+    """Small GPT-shaped model with embedding and tied head, odd vocabulary size; logits rows
+    dense or padded to a 16-byte aligned stride."""
     sh = SMALL_GPT
     L, B, S, V = 3, 2, 90, 1001
     wl = I.scaled(I.WORKLOADS[2], block=sh, layers=L, vocab=V, n_pos=128, batch=B, seq=S, bf16=bf16)
@@ -113,22 +115,24 @@ def test_model_forward_tokens(F, bf16):
     dt = torch.bfloat16 if bf16 else torch.float32
     tl = [dev_dict(w, bf16) for w in layers]
     tm = dev_dict(mw, bf16)
-    model = F.make_model_desc([F.make_block_desc(sh, w) for w in tl], tm)
-    logits = torch.empty(B, S, V, dtype=dt, device="cuda")
+    model = F.make_model_desc([F.make_block_desc(sh, w) for w in tl], tm, logits_ld=ld)
+    full = torch.zeros(B, S, ld if ld else V, dtype=dt, device="cuda")
+    logits = full[..., :V]
     kc = torch.zeros(L, B, sh.kv_heads, S, sh.head_dim, dtype=dt, device="cuda"); vc = torch.zeros_like(kc)
     ws = F.workspace(F.forge_model_workspace_bytes(model, B, S, S))
-    F.forge_model_forward(model, torch.from_numpy(ids).cuda(), logits, kc, vc, 0, ws)
+    F.forge_model_forward(model, torch.from_numpy(ids).cuda(), full, kc, vc, 0, ws)
     torch.cuda.synchronize()
+    assert torch.all(full[..., V:] == 0)
     if bf16:
         mx, l2 = rel_err(host(logits), ref)
         print("model bf16: max rel %.3e l2 %.3e" % (mx, l2))
         assert l2 < 2e-2 and mx < 6e-2      # end-to-end drift through L layers: reported, loosely gated
     else:
         check(logits, ref, False, "model logits")
-    a = logits.clone()
-    F.forge_model_forward(model, torch.from_numpy(ids).cuda(), logits, kc, vc, 0, ws)
+    a = full.clone()
+    F.forge_model_forward(model, torch.from_numpy(ids).cuda(), full, kc, vc, 0, ws)
     torch.cuda.synchronize()
-    assert torch.equal(a, logits)
+    assert torch.equal(a, full)
 
 
 def test_model_forward_hidden_llama(F):

@@ -72,6 +72,22 @@ def test_gemm_bias_act(F, bf16, act, M, N, K):
         check(ty, ref, bf16, "gemm %s" % act)
 
 
+@pytest.mark.parametrize("M,N,K,ld", [(300, 1001, 128, 1008), (257, 515, 64, 520), (130, 50257, 64, 50264)])
+def test_gemm_padded_row_stride(F, M, N, K, ld):
+    """Odd N with a padded, 16-byte aligned row stride: fast store path; the padding stays untouched."""
+    x = I.normal(67, 0, "x", (M, K), 1.0, bf16=True)
+    w = I.normal(67, 0, "w_up", (N, K), 0.1, bf16=True)
+    b = I.normal(67, 0, "b_up", (N,), 0.5, bf16=True)
+    r = I.normal(67, 0, "residual", (M, ld), 1.0, bf16=True)
+    ref = O.gemm_bias_act(x, w, b, r[:, :N], "gelu_tanh")
+    ty = torch.full((M, ld), 7.0, dtype=torch.bfloat16, device="cuda")
+    assert "dlds" in F.forge_gemm_variant(M, N, K, "gelu_tanh", torch.bfloat16, ldy=ld)
+    F.forge_gemm_bias_gelu(dev(x, True), dev(w, True), dev(b, True), dev(r, True), ty, "gelu_tanh", n=N)
+    torch.cuda.synchronize()
+    check(ty[:, :N], ref, True, "padded-stride gemm")
+    assert torch.all(ty[:, N:] == 7.0)
+
+
 def test_gemm_residual_in_place(F):
     M, N, K = 200, 256, 128
     x = I.normal(62, 0, "x", (M, K), 1.0, bf16=True)
