@@ -2,27 +2,36 @@
 // every cached K and V row is read exactly once, with 128-bit loads, and nothing else of
 // comparable size moves.
 //
-// Split-KV: block (split, kv head, batch) streams CHUNK consecutive cache rows of ONE kv head
-// for all G = Hq/Hkv query heads that share it (grouped-query attention reads the cache once
-// per group, not once per query head).  Each of the 4 waves owns 64 rows.  A cache row of dh
-// elements is spread over dh/8 lanes (16 B each), so one wave-wide load covers 64/(dh/8) rows;
-// a wave issues ALL its K and V loads first (the whole 64-row slice sits in registers) and then
-// computes, so a CU always has tens of KB in flight.
+// Split-KV: block (split, kv head, batch) streams CHUNK = 256 consecutive cache rows of ONE kv
+// head for all G = Hq/Hkv query heads that share it (grouped-query attention reads the cache
+// once per group, not once per query head).  Each of the 4 waves owns 64 rows as 4 tiles of 16
+// and keeps two tiles of K and V loads in flight ahead of the one it is working on.
 //
-// Per row group: partial dot products with packed bf16 dot2 (fp32 accumulate), a DPP butterfly
-// over the lanes of a row, online softmax in the exp2 domain with LAZY rescaling (the running
-// maximum only moves when some row beats it, which becomes rare after the first rows), and the
-// P.V accumulation in fp32 with each lane owning 8 output columns for every query head.
-// Lane-group, wave and block partials are merged with a fixed-order log-sum-exp combine; the
-// block writes (m, l, o) per query head to the workspace and a second kernel merges the splits
-// in split order -- no atomics, so the result is bitwise reproducible.
+// Per tile of 16 rows:
+//   scores   S[row, head] = K . q^T on the matrix cores (v_mfma_f32_16x16x32_bf16, heads padded
+//            to 16).  K is loaded straight from HBM in the MFMA A layout: lane = (row l%16, 16-byte
+//            chunk), the contraction order over dh is permuted so that one wave-wide load reads 64
+//            contiguous bytes of each row.  No LDS, no transposition.
+//   softmax  in the accumulator layout (lane = head, 4 rows per lane): running maximum per head
+//            with LAZY rescaling (the accumulators are only rescaled when some row beats the
+//            maximum, which becomes rare after the first tiles), exp2 domain.
+//   P . V    each lane owns 8 output columns for every head.  P goes through a 16 x G float
+//            patch of LDS (the only cross-lane traffic), is packed with its neighbour row to
+//            bf16 pairs, V rows of two steps are interleaved with byte permutes, and the
+//            accumulation runs on v_dot2_f32_bf16: two rows per instruction, fp32 accumulate.
+// Wave and block partials are merged in a fixed order; the block writes (m, l, o) per query head
+// to the workspace and a second kernel merges the splits in split order -- no atomics, so the
+// result is bitwise reproducible.
 #include "common.hpp"
 
 namespace forge {
 namespace {
 
-constexpr int CHUNK = 256;   // cache rows per block
-constexpr int WROWS = 64;    // cache rows per wave
+constexpr int NWAVES = 4;                 // waves per block
+constexpr int TILE = 16;                  // cache rows per MFMA tile
+constexpr int WTILES = 4;                 // tiles per wave
+constexpr int WROWS = TILE * WTILES;      // cache rows per wave
+constexpr int CHUNK = NWAVES * WROWS;     // cache rows per block
 
 struct DecParams {
   const bf16* q;
@@ -34,134 +43,169 @@ struct DecParams {
   float scale_log2e;
 };
 
-template <int CTRL> __device__ inline float dpp_add(float x) {
-  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
-  return x + __int_as_float(t);
+// Lanes of one wave exchange data through LDS: the hardware runs a wave's LDS instructions in
+// order, but the compiler must be told that other lanes wrote between this lane's accesses.
+__device__ inline void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
-// sum over the LPR (8 or 16) consecutive lanes that hold one cache row; all of them get it
-template <int LPR> __device__ inline float row_sum(float x) {
-  x = dpp_add<0xB1>(x);    // quad_perm [1,0,3,2]
-  x = dpp_add<0x4E>(x);    // quad_perm [2,3,0,1]
-  x = dpp_add<0x141>(x);   // row_half_mirror
-  if (LPR == 16) x = dpp_add<0x140>(x);   // row_mirror
-  return x;
-}
+
+__device__ inline float xor16_max(float x) { return fmaxf(x, __shfl_xor(x, 16, 64)); }
+__device__ inline float xor32_max(float x) { return fmaxf(x, __shfl_xor(x, 32, 64)); }
 
 template <int DH, int G>
-__global__ __launch_bounds__(256) void attn_decode_kernel(DecParams p) {
-  constexpr int LPR = DH / 8;          // lanes per cache row
-  constexpr int RPI = 64 / LPR;        // rows per wave-wide load
-  constexpr int STEPS = WROWS / RPI;
+__global__ __launch_bounds__(NWAVES * 64, 3) void attn_decode_kernel(DecParams p) {
+  constexpr int NJ = DH / 32;          // MFMAs (and K loads) per tile
+  constexpr int LPR = DH / 8;          // lanes per V row
+  constexpr int KPS = 64 / LPR;        // rows per wave-wide V load
+  constexpr int VSTEPS = TILE / KPS;   // V loads per tile
+  constexpr int NPAIR = VSTEPS / 2;    // row pairs per lane per tile
+  __shared__ __attribute__((aligned(16))) float pbuf[NWAVES][TILE][G];
+  __shared__ __attribute__((aligned(16))) float abuf[NWAVES][G];
+  __shared__ float sm[NWAVES][G][DH + 2];
+
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int slot = lane / LPR, c = lane % LPR;
   const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  const int krow = lane & 15, kg = lane >> 4;          // MFMA layout: row in tile / lane group
+  const int head = lane & 15;                          // ... and the accumulator's column
+  const int slot = lane / LPR, c = lane % LPR;         // V layout: row in step / 16-byte chunk
 
-  const bf16* kb = p.k + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs + c * 8;
-  const bf16* vb = p.v + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs + c * 8;
-  const int row0 = split * CHUNK + wave * WROWS + slot;
+  const bf16* kb = p.k + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
+  const bf16* vb = p.v + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
+  const int row0 = split * CHUNK + wave * WROWS;
   const int row_end = min(p.kv_len, (split + 1) * CHUNK);
+  const int last = p.kv_len - 1;
 
-  // ---- issue every load of this wave's slice -------------------------------------------------
-  u32x4 kr[STEPS], vr[STEPS];
+  // q as the MFMA B operand: lane = (head, chunk 4j + kg); heads >= G are zero columns
+  bf16x8 qf[NJ];
 #pragma unroll
-  for (int s = 0; s < STEPS; ++s) {
-    const int row = min(row0 + s * RPI, p.kv_len - 1);   // rows past the end re-read the last row
-    kr[s] = *reinterpret_cast<const u32x4*>(kb + (int64_t)row * DH);
-    vr[s] = *reinterpret_cast<const u32x4*>(vb + (int64_t)row * DH);
+  for (int j = 0; j < NJ; ++j) {
+    u32x4 t = {0, 0, 0, 0};
+    if (head < G) t = *reinterpret_cast<const u32x4*>(p.q + ((int64_t)b * p.q_heads + g * G + head) * DH + (4 * j + kg) * 8);
+    qf[j] = __builtin_bit_cast(bf16x8, t);
   }
-  // the G query rows, 8 elements per lane, kept packed for dot2
-  u32x4 qr[G];
+
+  u32x4 kr[2][NJ], vr[2][VSTEPS];
+  auto load_tile = [&](int t, u32x4 (&kk)[NJ], u32x4 (&vv)[VSTEPS]) {
+    const int base = row0 + t * TILE;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)   // rows past the end re-read the last row (masked below)
+      kk[j] = *reinterpret_cast<const u32x4*>(kb + (int64_t)min(base + krow, last) * DH + (4 * j + kg) * 8);
+#pragma unroll
+    for (int s = 0; s < VSTEPS; ++s)
+      vv[s] = *reinterpret_cast<const u32x4*>(vb + (int64_t)min(base + s * KPS + slot, last) * DH + c * 8);
+  };
+  load_tile(0, kr[0], vr[0]);
+  load_tile(1, kr[1], vr[1]);
+
+  float m_run = -1e30f, l_part = 0.f;      // accumulator layout: this lane's head
+  float acc[G][8];                         // V layout: this lane's 8 columns, all heads
 #pragma unroll
   for (int h = 0; h < G; ++h)
-    qr[h] = *reinterpret_cast<const u32x4*>(p.q + ((int64_t)b * p.q_heads + g * G + h) * DH + c * 8);
-
-  float m[G], l[G], acc[G][8];
-#pragma unroll
-  for (int h = 0; h < G; ++h) {
-    m[h] = -1e30f;
-    l[h] = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
-  }
   const float cl = p.scale_log2e;
 
 #pragma unroll
-  for (int s = 0; s < STEPS; ++s) {
-    const bool valid = row0 + s * RPI < row_end;
-    float sc[G];
+  for (int t = 0; t < WTILES; ++t) {
+    u32x4 (&kk)[NJ] = kr[t & 1];
+    u32x4 (&vv)[VSTEPS] = vr[t & 1];
+    const int base = row0 + t * TILE;
+    if (base < row_end) {     // wave-uniform: tiles wholly past the end contribute nothing
+      // ---- scores ------------------------------------------------------------------------------
+      floatx4 sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      // whole-vector casts, then element pairs by shuffle (never a cast of a single element)
-      const bf16x8 k8 = __builtin_bit_cast(bf16x8, kr[s]);
-      const bf16x8 q8 = __builtin_bit_cast(bf16x8, qr[h]);
-      float d = 0.f;
-      d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(k8, k8, 0, 1), __builtin_shufflevector(q8, q8, 0, 1), d, false);
-      d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(k8, k8, 2, 3), __builtin_shufflevector(q8, q8, 2, 3), d, false);
-      d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(k8, k8, 4, 5), __builtin_shufflevector(q8, q8, 4, 5), d, false);
-      d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(k8, k8, 6, 7), __builtin_shufflevector(q8, q8, 6, 7), d, false);
-      d = row_sum<LPR>(d) * cl;
-      sc[h] = valid ? d : -INFINITY;
-    }
-    bool grow = false;
+      for (int j = 0; j < NJ; ++j)
+        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kk[j]), qf[j], sacc, 0, 0, 0);
+      float sc[4];
+      float mx = -INFINITY;
 #pragma unroll
-    for (int h = 0; h < G; ++h) grow |= sc[h] > m[h];
-    if (__any(grow)) {   // wave-uniform: some row raised a running maximum
+      for (int v = 0; v < 4; ++v) {     // accumulator register v is row 4 kg + v
+        sc[v] = base + 4 * kg + v < row_end ? sacc[v] * cl : -INFINITY;
+        mx = fmaxf(mx, sc[v]);
+      }
+      mx = xor32_max(xor16_max(mx));
+      // ---- lazy rescale --------------------------------------------------------------------------
+      if (__any(mx > m_run)) {
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        l_part *= alpha;
+        if (lane < G) abuf[wave][lane] = alpha;      // lane = head (kg == 0)
+        wave_lds_sync();
+        float al[G];
 #pragma unroll
-      for (int h = 0; h < G; ++h) {
-        const float mn = fmaxf(m[h], sc[h]);
-        const float alpha = __builtin_amdgcn_exp2f(m[h] - mn);
-        m[h] = mn;
-        l[h] *= alpha;
+        for (int h = 0; h < G; ++h) al[h] = abuf[wave][h];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[h][e] *= alpha;
+        for (int h = 0; h < G; ++h)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[h][e] *= al[h];
+      }
+      // ---- probabilities, through LDS to the V layout ---------------------------------------------
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const float pr = __builtin_amdgcn_exp2f(sc[v] - m_run);   // exp2(-inf) = 0 past the end
+        l_part += pr;
+        if (head < G) pbuf[wave][4 * kg + v][head] = pr;
+      }
+      wave_lds_sync();
+      // ---- P . V on dot2: rows (s, s+1) of this lane's slot packed as bf16 pairs ---------------------
+#pragma unroll
+      for (int pi = 0; pi < NPAIR; ++pi) {
+        const int ra = (2 * pi) * KPS + slot, rb = (2 * pi + 1) * KPS + slot;
+        bf16x2 pp[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          pp[h][0] = (bf16)pbuf[wave][ra][h];
+          pp[h][1] = (bf16)pbuf[wave][rb][h];
+        }
+        const u32x4 va = vv[2 * pi], vb2 = vv[2 * pi + 1];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          // (va.lo, vb.lo) and (va.hi, vb.hi): element 2d and 2d+1 of both rows
+          const uint32_t lo = __builtin_amdgcn_perm(vb2[d], va[d], 0x05040100);
+          const uint32_t hi = __builtin_amdgcn_perm(vb2[d], va[d], 0x07060302);
+          const bf16x2 vlo = __builtin_bit_cast(bf16x2, lo), vhi = __builtin_bit_cast(bf16x2, hi);
+#pragma unroll
+          for (int h = 0; h < G; ++h) {
+            acc[h][2 * d] = __builtin_amdgcn_fdot2_f32_bf16(vlo, pp[h], acc[h][2 * d], false);
+            acc[h][2 * d + 1] = __builtin_amdgcn_fdot2_f32_bf16(vhi, pp[h], acc[h][2 * d + 1], false);
+          }
+        }
       }
     }
-    float vf[8];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { vf[2 * e] = bf_lo(vr[s][e]); vf[2 * e + 1] = bf_hi(vr[s][e]); }
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const float pr = __builtin_amdgcn_exp2f(sc[h] - m[h]);   // exp2(-inf) = 0 for rows past the end
-      l[h] += pr;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[h][e] += pr * vf[e];
-    }
+    wave_lds_sync();   // this tile's LDS reads are done before the next tile's writes
+    if (t + 2 < WTILES) load_tile(t + 2, kr[t & 1], vr[t & 1]);   // refill the registers just consumed
   }
 
-  // ---- merge the RPI lane groups of the wave (xor over the lane bits above the row bits) ------
+  // ---- merge inside the wave: plain sums (one running maximum per head for the whole wave) -------
 #pragma unroll
-  for (int o = LPR; o < 64; o <<= 1) {
+  for (int o = LPR; o < 64; o <<= 1)
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const float m2 = __shfl_xor(m[h], o, 64), l2 = __shfl_xor(l[h], o, 64);
-      const float mn = fmaxf(m[h], m2);
-      const float a1 = __builtin_amdgcn_exp2f(m[h] - mn), a2 = __builtin_amdgcn_exp2f(m2 - mn);
-      l[h] = l[h] * a1 + l2 * a2;
+    for (int h = 0; h < G; ++h)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[h][e] = acc[h][e] * a1 + __shfl_xor(acc[h][e], o, 64) * a2;
-      m[h] = mn;
-    }
-  }
-  // ---- merge the 4 waves through LDS, fixed order ------------------------------------------------
-  __shared__ float sm[4][G][DH + 2];
+      for (int e = 0; e < 8; ++e) acc[h][e] += __shfl_xor(acc[h][e], o, 64);
+  l_part += __shfl_xor(l_part, 16, 64);
+  l_part += __shfl_xor(l_part, 32, 64);
   if (slot == 0) {
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
+    for (int h = 0; h < G; ++h)
 #pragma unroll
       for (int e = 0; e < 8; ++e) sm[wave][h][c * 8 + e] = acc[h][e];
-      if (c == 0) { sm[wave][h][DH] = m[h]; sm[wave][h][DH + 1] = l[h]; }
-    }
   }
+  if (lane < G) { sm[wave][lane][DH] = m_run; sm[wave][lane][DH + 1] = l_part; }
   __syncthreads();
+  // ---- merge the waves, fixed order -------------------------------------------------------------------
   float* dst = p.part + ((((int64_t)b * p.kv_heads + g) * p.splits + split) * G) * (DH + 2);
-  for (int idx = tid; idx < G * DH; idx += 256) {
+  for (int idx = tid; idx < G * DH; idx += NWAVES * 64) {
     const int h = idx / DH, d = idx % DH;
     float mn = sm[0][h][DH];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) mn = fmaxf(mn, sm[w][h][DH]);
+    for (int w = 1; w < NWAVES; ++w) mn = fmaxf(mn, sm[w][h][DH]);
     float o = 0.f, lt = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NWAVES; ++w) {
       const float a = __builtin_amdgcn_exp2f(sm[w][h][DH] - mn);
       o += sm[w][h][d] * a;
       lt += sm[w][h][DH + 1] * a;
@@ -171,25 +215,43 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(DecParams p) {
   }
 }
 
-// one block per (batch, query head): merge the splits in order and normalise
+// one block per (batch, query head): merge the splits in split order and normalise.  Lane s of
+// the first wave fetches (m, l) of split s, so the maximum and the weights cost one round trip;
+// the weighted sums then run with independent loads, four splits per step.
 template <int DH>
 __global__ __launch_bounds__(DH) void attn_decode_combine(const float* __restrict__ part,
                                                           bf16* __restrict__ out, int q_heads,
                                                           int kv_heads, int splits) {
+  __shared__ float wgt[64];
+  __shared__ float ltot;
   const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
   const int G = q_heads / kv_heads;
   const int g = h / G, hh = h % G;
   const float* src = part + ((((int64_t)b * kv_heads + g) * splits) * G + hh) * (DH + 2);
   const int64_t stride = (int64_t)G * (DH + 2);
-  float mn = -1e30f;
-  for (int s = 0; s < splits; ++s) mn = fmaxf(mn, src[s * stride + DH]);
-  float o = 0.f, lt = 0.f;
-  for (int s = 0; s < splits; ++s) {
-    const float a = __builtin_amdgcn_exp2f(src[s * stride + DH] - mn);
-    o += src[s * stride + d] * a;
-    lt += src[s * stride + DH + 1] * a;
+  if (d < 64) {
+    float m = -1e30f, l = 0.f;
+    if (d < splits) { m = src[d * stride + DH]; l = src[d * stride + DH + 1]; }
+    const float mn = wave_max(m);
+    const float a = __builtin_amdgcn_exp2f(m - mn);
+    wgt[d] = a;
+    // fixed-order sum of l over the splits: butterfly (the same tree every run)
+    const float lt = wave_sum(l * a);
+    if (d == 0) ltot = lt;
   }
-  out[((int64_t)b * q_heads + h) * DH + d] = (bf16)(o / lt);
+  __syncthreads();
+  float o = 0.f;
+  int s = 0;
+  for (; s + 4 <= splits; s += 4) {
+    const float v0 = src[(s + 0) * stride + d], v1 = src[(s + 1) * stride + d];
+    const float v2 = src[(s + 2) * stride + d], v3 = src[(s + 3) * stride + d];
+    o += v0 * wgt[s];
+    o += v1 * wgt[s + 1];
+    o += v2 * wgt[s + 2];
+    o += v3 * wgt[s + 3];
+  }
+  for (; s < splits; ++s) o += src[s * stride + d] * wgt[s];
+  out[((int64_t)b * q_heads + h) * DH + d] = (bf16)(o / ltot);
 }
 
 template <int DH, int G>
@@ -206,7 +268,8 @@ forge_status launch_dg(const AttnArgs& a, hipStream_t s) {
   p.kv_bs = a.kv_batch_stride;
   p.kv_hs = a.kv_head_stride;
   p.scale_log2e = a.scale * 1.4426950408889634f;
-  attn_decode_kernel<DH, G><<<dim3(p.splits, a.kv_heads, a.batch), 256, 0, s>>>(p);
+  if (p.splits > 64) return FORGE_ERR_UNSUPPORTED;   // the combine holds one split per lane
+  attn_decode_kernel<DH, G><<<dim3(p.splits, a.kv_heads, a.batch), NWAVES * 64, 0, s>>>(p);
   if (hipGetLastError() != hipSuccess) return FORGE_ERR_HIP;
   attn_decode_combine<DH><<<dim3(a.q_heads, a.batch), DH, 0, s>>>(p.part, (bf16*)a.out, a.q_heads,
                                                                   a.kv_heads, p.splits);
