@@ -89,6 +89,10 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnParams p) {
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks)
       qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + (2 * ks + fh) * 8);
+    // pin the fragments in registers: otherwise the compiler re-loads them from global memory
+    // inside the key loop and the score MFMAs wait on that latency every tile
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) asm volatile("" : "+v"(qf[ks]));
   }
 
   // keys a query may see: [0, limit]
@@ -151,14 +155,26 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnParams p) {
       // ---- S^T = K . Q^T --------------------------------------------------------------------
       floatx16 s_acc[2];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) s_acc[kb][e] = 0.f;
+      {
+        // K fragments run LA MFMAs ahead of their use so that no MFMA waits on an LDS read
+        constexpr int NF = 2 * NKS, LA = 4;
+        bf16x8 kf[LA];
+        auto kread = [&](int i) {
+          const int kb = i / NKS, ks = i % NKS;
+          return *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + fr) * KS + (2 * ks + fh) * 16);
+        };
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + fr) * KS + (2 * ks + fh) * 16);
-          s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s_acc[kb], 0, 0, 0);
+        for (int i = 0; i < LA; ++i) kf[i] = kread(i);
+#pragma unroll
+        for (int i = 0; i < NF; ++i) {
+          __builtin_amdgcn_sched_barrier(0);
+          s_acc[i / NKS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % LA], qf[i % NKS], s_acc[i / NKS], 0, 0, 0);
+          if (i + LA < NF) kf[i % LA] = kread(i + LA);
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
       // ---- mask (diagonal / tail tiles only) ---------------------------------------------------
       if (kv0 + BKV - 1 > wave_min_limit) {
@@ -197,21 +213,33 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnParams p) {
         for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
 
       // ---- O^T += V^T . P^T ---------------------------------------------------------------------
+      {
+        bf16x8 pf[4];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        bf16x8 pf;
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pf[e] = (bf16)s_acc[s >> 1][8 * (s & 1) + e];
-#pragma unroll
-        for (int dt = 0; dt < NDT; ++dt) {
+          for (int e = 0; e < 8; ++e) pf[s][e] = (bf16)s_acc[s >> 1][8 * (s & 1) + e];
+        // V^T fragments (two transposing reads each) run LA MFMAs ahead of their use
+        constexpr int NF = 4 * NDT, LA = 4;
+        typedef short v8i16 __attribute__((ext_vector_type(8)));
+        v4i16 lo[LA], hi[LA];
+        auto vread = [&](int i, v4i16& l, v4i16& h) {
+          const int s = i / NDT, dt = i % NDT;
           const char* va = sv + vt_lane + (16 * s) * VS + dt * 64;
-          const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(va));
-          const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(va + 8 * VS));
-          typedef short v8i16 __attribute__((ext_vector_type(8)));
-          v8i16 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-          const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
-          o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o_acc[dt], 0, 0, 0);
+          l = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(va));
+          h = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(va + 8 * VS));
+        };
+#pragma unroll
+        for (int i = 0; i < LA; ++i) vread(i, lo[i], hi[i]);
+#pragma unroll
+        for (int i = 0; i < NF; ++i) {
+          __builtin_amdgcn_sched_barrier(0);
+          const v4i16 l = lo[i % LA], h = hi[i % LA];
+          v8i16 both = {l[0], l[1], l[2], l[3], h[0], h[1], h[2], h[3]};
+          o_acc[i % NDT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[i / NDT], o_acc[i % NDT], 0, 0, 0);
+          if (i + LA < NF) vread(i + LA, lo[i % LA], hi[i % LA]);
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     if (more) store_tile((t + 1) & 1);

@@ -240,8 +240,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_generic_kernel(GemmPara
 
 typedef __attribute__((address_space(3))) void lds_void;
 
-// Fast path, see the file header.  STAGES = 2.
-template <int BM, int BN, int WM, int WN, int ACT, int MODE>
+// Fast path, see the file header.  STAGES LDS buffers: the loads of STAGES-1 slabs are in flight
+// while one slab is multiplied (2 for the compute-bound tiles, 4 for the weight-streaming ones).
+template <int BM, int BN, int WM, int WN, int ACT, int MODE, int STAGES>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dlds_kernel(GemmParams p) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -341,12 +342,21 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dlds_kernel(GemmParams 
   const int k_begin = MODE == MODE_SPLITK ? blockIdx.y * p.k_per_split : 0;
   const int k_end = MODE == MODE_SPLITK ? min(K, k_begin + p.k_per_split) : K;
   const int nk = (k_end - k_begin) / BK;
-  issue(k_begin, 0);
+#pragma unroll
+  for (int st = 0; st < STAGES - 1; ++st)
+    if (st < nk) issue(k_begin + st * BK, st);
   for (int kt = 0; kt < nk; ++kt) {
-    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this thread's loads of slab kt are in LDS
-    __syncthreads();                      // everyone's are; everyone is done reading the other buffer
-    if (kt + 1 < nk) issue(k_begin + (kt + 1) * BK, (kt + 1) & 1);
-    compute(kt & 1);
+    // this thread's loads of slab kt are in LDS once at most `ahead` younger slabs are outstanding
+    // (loads retire in order; L loads per thread and slab)
+    constexpr int L = IA + IB;
+    const int ahead = min(STAGES - 2, nk - 1 - kt);
+    if (ahead <= 0) __builtin_amdgcn_s_waitcnt(0x0f70);                                          // vmcnt(0)
+    else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0f70 | (L & 0xf) | ((L >> 4) << 14));      // vmcnt(L)
+    else __builtin_amdgcn_s_waitcnt(0x0f70 | ((2 * L) & 0xf) | (((2 * L) >> 4) << 14));          // vmcnt(2L)
+    // bare s_barrier (no fence: a fence would wait for the younger slabs too)
+    __builtin_amdgcn_s_barrier();   // everyone's are; everyone is done reading the buffer refilled next
+    if (kt + STAGES - 1 < nk) issue(k_begin + (kt + STAGES - 1) * BK, (kt + STAGES - 1) % STAGES);
+    compute(kt % STAGES);
   }
 
   // ---- epilogue: lane = output row m; registers = columns ---------------------------------------
@@ -451,6 +461,110 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dlds_kernel(GemmParams 
   }
 }
 
+// Weight-streaming kernel for M <= 64 (decode): HBM-bound, every weight byte is read once.
+// A block owns 64 weight rows (output columns) and one k range.  Weight slabs (8 KB) and
+// activation slabs (8 KB, L2 resident) both arrive by direct-to-LDS loads, but in SEPARATE rings
+// filled by different waves: waves 0-1 only issue weight loads into a ring of WS_W slabs, waves
+// 2-3 only issue activation loads into a ring of WS_X slabs.  The vector-memory counter retires
+// in order within a wave, so mixing the two streams in one wave would tie the HBM stream to the
+// depth of the L2 stream; split this way a block keeps (WS_W - 1) x 8 KB of weight in flight,
+// two blocks per CU.  All four waves multiply.  Output: fp32 partial sums D[n, m] for the
+// fixed-order split-K reduce.
+constexpr int WS_W = 6;   // weight ring depth
+constexpr int WS_X = 3;   // activation ring depth
+constexpr int WS_SMEM = (WS_W + WS_X) * 64 * BK * 2;
+
+__global__ __launch_bounds__(256) void gemm_bf16_wstream_kernel(GemmParams p) {
+  constexpr int SLAB = 64 * BK * 2;           // 8 KB: 64 rows of 64 bf16
+  constexpr int LPW = 4;                      // wave-wide 1 KB loads per loader wave per slab
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // [W ring | x ring]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int fr = lane & 31, fh = lane >> 5;
+  const int M = p.M, N = p.N, K = p.K;
+  const int n0 = blockIdx.x * 64;
+  const bool w_loader = wave < 2;             // wave-uniform role
+  const int lw = wave & 1;                    // index among the two loaders of a stream
+
+  // loader plan: wave-wide load i of loader lw fills slab rows (i*2 + lw)*8 .. +8
+  const bf16* src[LPW];
+#pragma unroll
+  for (int i = 0; i < LPW; ++i) {
+    const int r = (i * 2 + lw) * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    src[i] = w_loader ? p.w + (int64_t)min(n0 + r, N - 1) * K + c * 8
+                      : p.x + (int64_t)min(r, M - 1) * K + c * 8;
+  }
+  const int k_begin = blockIdx.y * p.k_per_split;
+  const int k_end = min(K, k_begin + p.k_per_split);
+  const int nk = (k_end - k_begin) / BK;
+  const int depth = w_loader ? WS_W : WS_X;
+  char* ring = smem + (w_loader ? 0 : WS_W * SLAB);
+
+  auto issue = [&](int kt) {      // slab kt of this wave's stream (clamped past the end: see below)
+    const int k = min(kt, nk - 1);
+    char* dst = ring + (k % depth) * SLAB;
+#pragma unroll
+    for (int i = 0; i < LPW; ++i)
+      __builtin_amdgcn_global_load_lds((const void*)(src[i] + k_begin + k * BK),
+                                       (lds_void*)(dst + (i * 2 + lw) * 1024), 16, 0, 0);
+  };
+
+  floatx16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+
+  // every iteration issues exactly LPW loads per wave (past the end the last slab is re-loaded into
+  // its own buffer: same bytes, harmless), so the in-order wait count is a constant per role
+  for (int st = 0; st < depth - 1; ++st) issue(st);
+  for (int kt = 0; kt < nk; ++kt) {
+    // slab kt of my stream has landed when at most (depth - 2) younger slabs are outstanding
+    if (w_loader) __builtin_amdgcn_s_waitcnt(0x0f70 | (((WS_W - 2) * LPW) & 0xf) | ((((WS_W - 2) * LPW) >> 4) << 14));
+    else __builtin_amdgcn_s_waitcnt(0x0f70 | (((WS_X - 2) * LPW) & 0xf) | ((((WS_X - 2) * LPW) >> 4) << 14));
+    // a bare s_barrier: __syncthreads() carries a fence that drains ALL outstanding loads
+    // (vmcnt(0)) and would collapse the ring to a single slab in flight
+    __builtin_amdgcn_s_barrier();   // both streams' slab kt are in LDS; slab kt-1's buffers are free
+    issue(kt + depth - 1);
+    const char* sw = smem + (kt % WS_W) * SLAB;
+    const char* sx = smem + WS_W * SLAB + (kt % WS_X) * SLAB;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const bf16x8 wf = *reinterpret_cast<const bf16x8*>(sw + lds_chunk_off(wn * 32 + fr, 2 * ks + fh));
+      const bf16x8 xf = *reinterpret_cast<const bf16x8*>(sx + lds_chunk_off(wm * 32 + fr, 2 * ks + fh));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc, 0, 0, 0);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0x0f70);   // drain the re-loads of the tail before the block ends
+  __syncthreads();
+
+  // ---- partial sums: lane = row m, registers = columns (see the fast kernel's epilogue) -----------
+  float run[2][8];
+#pragma unroll
+  for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      auto sw2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[4 * gp + r]),
+                                                  __float_as_uint(acc[4 * (gp + 2) + r]), false, false);
+      run[gp][r] = __uint_as_float(sw2[0]);
+      run[gp][4 + r] = __uint_as_float(sw2[1]);
+    }
+  const int m = wm * 32 + fr;
+  if (m >= M) return;
+  const bool vec_part = (N & 3) == 0;
+#pragma unroll
+  for (int gp = 0; gp < 2; ++gp) {
+    const int n = n0 + wn * 32 + 16 * fh + 8 * gp;
+    if (n >= N) continue;
+    float* dst = p.part + ((int64_t)blockIdx.y * M + m) * N + n;
+    if (n + 8 <= N && vec_part) {
+      Vec8<float>::store(dst, run[gp]);
+    } else {
+      for (int e = 0; e < 8 && n + e < N; ++e) dst[e] = run[gp][e];
+    }
+  }
+}
+
 // Split-K second stage: sums the fp32 partials of one output element in split order (fixed
 // order, no atomics), then applies the same epilogue as the single-pass kernel.  One thread
 // owns 4 consecutive columns.  For SwiGLU the partials hold 2N columns: gate n and up n + N.
@@ -463,20 +577,39 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p, int sp
   if (gid >= (int64_t)p.M * groups) return;
   const int m = (int)(gid / groups), n0 = (int)(gid % groups) * 4;
   const int64_t plane = (int64_t)p.M * ncols;
+  const float* src = p.part + (int64_t)m * ncols + n0;
+  float a[4] = {0.f, 0.f, 0.f, 0.f}, u[4] = {0.f, 0.f, 0.f, 0.f};
+  const bool vec = (ncols & 3) == 0 && n0 + 4 <= N && (!SWIGLU || (N & 3) == 0);
+  if (vec) {
+    // independent 128-bit loads, summed in split order
+#pragma unroll 4
+    for (int z = 0; z < splits; ++z) {
+      const floatx4 v = *reinterpret_cast<const floatx4*>(src + z * plane);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) a[e] += v[e];
+      if (SWIGLU) {
+        const floatx4 w = *reinterpret_cast<const floatx4*>(src + z * plane + N);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) u[e] += w[e];
+      }
+    }
+  } else {
+    for (int z = 0; z < splits; ++z)
+      for (int e = 0; e < 4 && n0 + e < N; ++e) {
+        a[e] += src[z * plane + e];
+        if (SWIGLU) u[e] += src[z * plane + e + N];
+      }
+  }
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const int n = n0 + e;
     if (n >= N) break;
-    float a = 0.f, u = 0.f;
-    for (int z = 0; z < splits; ++z) {
-      a += p.part[z * plane + (int64_t)m * ncols + n];
-      if (SWIGLU) u += p.part[z * plane + (int64_t)m * ncols + n + N];
-    }
+    float av = a[e], uv = u[e];
     if (p.bias != nullptr) {
-      a += (float)p.bias[n];
-      if (SWIGLU) u += (float)p.bias[n + N];
+      av += (float)p.bias[n];
+      if (SWIGLU) uv += (float)p.bias[n + N];
     }
-    float val = SWIGLU ? silu_f(a) * u : apply_act<ACT>(a);
+    float val = SWIGLU ? silu_f(av) * uv : apply_act<ACT>(av);
     if (QKV) {
       *split_dst_bf16(p.sp, m, n) = (bf16)val;
     } else {
@@ -486,14 +619,15 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p, int sp
   }
 }
 
-template <bool FAST, int BM, int BN, int WM, int WN, int ACT, int MODE>
+template <bool FAST, int BM, int BN, int WM, int WN, int ACT, int MODE, int STAGES = 2>
 forge_status launch_cfg(const GemmParams& p0, int splits, hipStream_t s) {
+  static_assert(STAGES >= 2 && STAGES <= 4 && (FAST || STAGES == 2), "stage count");
   GemmParams p = p0;
   constexpr int BN_OUT = ACT == FORGE_ACT_SWIGLU ? BN / 2 : BN;
   p.tiles_m = ceil_div(p.M, BM);
   p.tiles_n = ceil_div(p.N, BN_OUT);
-  constexpr int smem = 2 * (BM + BN) * BK * 2;
-  auto kern = FAST ? gemm_bf16_dlds_kernel<BM, BN, WM, WN, ACT, MODE>
+  constexpr int smem = STAGES * (BM + BN) * BK * 2;
+  auto kern = FAST ? gemm_bf16_dlds_kernel<BM, BN, WM, WN, ACT, MODE, STAGES>
                    : gemm_bf16_generic_kernel<BM, BN, WM, WN, ACT, MODE>;
   static bool configured = false;   // idempotent attribute, set once per instantiation
   if (!configured) {
@@ -531,7 +665,7 @@ inline SkinnyPlan plan_skinny(int N, int K, forge_act act) {
   const int tiles = ceil_div(sp.ncols, 64);
   const int slabs = ceil_div(K, BK);
   int want = ceil_div(512, tiles);                 // aim at >= 512 blocks
-  want = max(1, min(want, slabs / 4));             // but at least 4 slabs of work per block
+  want = max(1, min(want, slabs / 8));             // but at least 8 slabs of work per block
   const int per = ceil_div(slabs, want);
   sp.splits = ceil_div(slabs, per);
   sp.k_per_split = per * BK;
@@ -553,9 +687,21 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
   GemmParams q = p;
   q.N = sk.ncols;
   q.k_per_split = sk.k_per_split;
-  forge_status st = v == V_SKINNY_FAST
-      ? launch_cfg<true, 64, 64, 2, 2, FORGE_ACT_NONE, MODE_SPLITK>(q, sk.splits, s)
-      : launch_cfg<false, 64, 64, 2, 2, FORGE_ACT_NONE, MODE_SPLITK>(q, sk.splits, s);
+  forge_status st;
+  if (v == V_SKINNY_FAST) {
+    constexpr int smem = WS_SMEM;
+    static bool configured = false;
+    if (!configured) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_wstream_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+        return FORGE_ERR_HIP;
+      configured = true;
+    }
+    gemm_bf16_wstream_kernel<<<dim3(ceil_div(q.N, 64), sk.splits), 256, smem, s>>>(q);
+    st = launch_status();
+  } else {
+    st = launch_cfg<false, 64, 64, 2, 2, FORGE_ACT_NONE, MODE_SPLITK>(q, sk.splits, s);
+  }
   if (st != FORGE_OK) return st;
   const int64_t threads = (int64_t)p.M * ceil_div(p.N, 4);
   splitk_reduce_kernel<ACT, MODE == MODE_QKV><<<(unsigned)ceil_div64(threads, 256), 256, 0, s>>>(p, sk.splits, sk.ncols);
@@ -576,7 +722,7 @@ const char* gemm_bf16_variant(int M, int N, int K, int ldy, forge_act act) {
     case V_FAST_128: return "gemm_bf16_dlds<128,128,2,2>";
     case V_GEN_256: return "gemm_bf16_generic<256,256,2,4>";
     case V_GEN_128: return "gemm_bf16_generic<128,128,2,2>";
-    case V_SKINNY_FAST: return "gemm_bf16_dlds<64,64,2,2>+splitk";
+    case V_SKINNY_FAST: return "gemm_bf16_wstream<64>+splitk";
     default: return "gemm_bf16_generic<64,64,2,2>+splitk";
   }
 }

@@ -6,22 +6,27 @@ namespace forge {
 namespace {
 
 // One thread owns 8 consecutive pair indices i0..i0+7 of one sequence row s of one batch
-// element and walks over all heads: the angles p * theta_i depend on (s, i) only, so sin/cos
-// are evaluated once (in fp64: p * theta reaches thousands of radians, where an fp32 product
-// alone would already cost 1e-4 of absolute accuracy) and reused for every head.
+// element and walks over a GROUP of heads: the angles p * theta_i depend on (s, i) only, so sin/cos
+// are evaluated once per thread (in fp64: p * theta reaches thousands of radians, where an fp32
+// product alone would already cost 1e-4 of absolute accuracy) and reused for every head of the
+// group.  The launcher picks the number of head groups so that short inputs (a decode step has
+// one row per sequence) still fill the chip, while long ones amortise the sin/cos over many heads.
 template <typename T>
 __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ x, int batch, int heads,
                                                    int n_rows, int head_dim, int64_t batch_stride,
                                                    int64_t head_stride, int row0, int pos0,
-                                                   float base) {
+                                                   float base, int head_groups) {
   const int half = head_dim / 2;
   const int chunks = half / 8;
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t total = (int64_t)batch * n_rows * chunks;
+  const int64_t total = (int64_t)batch * n_rows * chunks * head_groups;
   if (gid >= total) return;
   const int c = (int)(gid % chunks);
-  const int s = (int)((gid / chunks) % n_rows);
-  const int b = (int)(gid / ((int64_t)chunks * n_rows));
+  const int hg = (int)((gid / chunks) % head_groups);
+  const int s = (int)((gid / ((int64_t)chunks * head_groups)) % n_rows);
+  const int b = (int)(gid / ((int64_t)chunks * head_groups * n_rows));
+  const int per = ceil_div(heads, head_groups);
+  const int h0 = hg * per, h1 = min(heads, h0 + per);
   const double p = (double)(pos0 + s);
   const double l2b = log2((double)base);
   float cs[8], sn[8];
@@ -34,7 +39,7 @@ __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ x, int batch,
     sn[i] = (float)sv;
   }
   T* row = x + (int64_t)b * batch_stride + (int64_t)(row0 + s) * head_dim + c * 8;
-  for (int h = 0; h < heads; ++h) {
+  for (int h = h0; h < h1; ++h) {
     T* p1 = row + (int64_t)h * head_stride;
     T* p2 = p1 + half;
     float a[8], d[8], oa[8], od[8];
@@ -76,14 +81,18 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
 forge_status launch_rope(void* x, int batch, int heads, int n_rows, int head_dim,
                          int64_t batch_stride, int64_t head_stride, int row0, int pos0, float base,
                          forge_dtype dt, hipStream_t s) {
-  const int64_t total = (int64_t)batch * n_rows * (head_dim / 16);
+  const int64_t base_threads = (int64_t)batch * n_rows * (head_dim / 16);
+  // enough head groups to reach ~128k threads, at most one group per head
+  int head_groups = (int)ceil_div64(131072, base_threads);
+  head_groups = head_groups < 1 ? 1 : (head_groups > heads ? heads : head_groups);
+  const int64_t total = base_threads * head_groups;
   dim3 grid((unsigned)ceil_div64(total, 256)), block(256);
   if (dt == FORGE_BF16)
     rope_kernel<bf16><<<grid, block, 0, s>>>((bf16*)x, batch, heads, n_rows, head_dim, batch_stride,
-                                             head_stride, row0, pos0, base);
+                                             head_stride, row0, pos0, base, head_groups);
   else
     rope_kernel<float><<<grid, block, 0, s>>>((float*)x, batch, heads, n_rows, head_dim,
-                                              batch_stride, head_stride, row0, pos0, base);
+                                              batch_stride, head_stride, row0, pos0, base, head_groups);
   return launch_status();
 }
 
