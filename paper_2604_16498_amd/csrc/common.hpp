@@ -97,9 +97,10 @@ __device__ inline float wave_max(float v) {
 __device__ inline float gelu_tanh_f(float x) {
   const float k0 = 0.7978845608028654f, k1 = 0.044715f;
   float u = k0 * (x + k1 * x * x * x);
-  return x / (1.0f + __expf(-2.0f * u));
+  // x * sigmoid(2u); hardware reciprocal (1 ulp) instead of an IEEE division
+  return x * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
 }
-__device__ inline float silu_f(float x) { return x / (1.0f + __expf(-x)); }
+__device__ inline float silu_f(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 
 template <int ACT> __device__ inline float apply_act(float x) {
   if (ACT == FORGE_ACT_GELU_TANH) return gelu_tanh_f(x);

@@ -8,14 +8,14 @@
 // Two kernels share the tiling (a block of WM x WN waves owns a BM x BN tile of y, each wave
 // (BM/WM) x (BN/WN) as TM x TN accumulators of 32 x 32, K walked in slabs of 64):
 //
-//  * gemm_bf16_dlds_kernel -- the fast path (K % 64 == 0, output rows 16-byte aligned).
-//    Slabs go HBM -> LDS directly (global_load_lds_dwordx4: each wave-wide load drops 1 KB into
-//    LDS at lane*16, no staging registers, no LDS store instructions) into a 2-stage ring: the
-//    loads of slab k+1 are in flight while slab k is multiplied; one barrier per slab.
+//  * gemm_bf16_pers_kernel -- the fast path (K % 64 == 0, output rows 16-byte aligned, operands
+//    below 4 GB).  Slabs go HBM -> LDS directly (global_load_lds_dwordx4: each wave-wide load drops
+//    1 KB into LDS at lane*16, no staging registers, no LDS store instructions) into a 2-stage
+//    ring: the loads of slab k+1 are in flight while slab k is multiplied; one barrier per slab.
 //    w is the MFMA A operand and x the B operand, so an accumulator holds D[n, m]: a lane owns
 //    ONE output row m and, after a permlane32 swap of register groups, two runs of 8 consecutive
-//    columns -- bias, residual and y move as 128-bit accesses, and the QKV head split needs one
-//    (batch, position) division per lane instead of one per element.
+//    columns.  The finished tile is transposed through LDS into whole output rows.  Blocks are
+//    persistent: see the comment at the kernel.
 //  * gemm_bf16_generic_kernel -- any K % 8 == 0 and any row stride: HBM -> registers -> LDS
 //    double buffering with zero fill of the K tail, x as the A operand, element stores.
 //
@@ -29,10 +29,10 @@
 // arranged so that accumulator (., t) is the gate and (., t + TN/2) the up projection of one
 // column block; the epilogue writes silu(gate) * up and no extra accumulators are needed.
 //
-// Work-group order: blocks are dealt round-robin over the 8 XCDs (each with its own L2), so the
-// block id is first remapped to give every XCD one contiguous run of tiles, and tiles are
-// numbered in groups of 8 tile rows, column-major inside a group, so that the tiles resident in
-// one XCD at a time share x and w panels in that L2.
+// Work-group order: blocks are dealt round-robin over the 8 XCDs (each with its own L2), so every
+// XCD gets one contiguous run of tiles, and tiles are numbered in groups of 8 tile rows,
+// column-major inside a group, so that the tiles resident in one XCD at a time share x and w
+// panels in that L2.
 //
 // M <= 64 (decode): the weight is streamed once; 64 x 64 tiles, K split over grid.y so that at
 // least 512 blocks run, fp32 partials, and a fixed-order reduce kernel that carries the epilogue.
@@ -240,10 +240,42 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_generic_kernel(GemmPara
 
 typedef __attribute__((address_space(3))) void lds_void;
 
-// Fast path, see the file header.  STAGES LDS buffers: the loads of STAGES-1 slabs are in flight
-// while one slab is multiplied (2 for the compute-bound tiles, 4 for the weight-streaming ones).
-template <int BM, int BN, int WM, int WN, int ACT, int MODE, int STAGES>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dlds_kernel(GemmParams p) {
+// Block barrier for data exchanged through LDS only: this wave's LDS traffic has completed
+// (lgkmcnt 0), vector-memory loads and stores stay in flight (__syncthreads would drain them too).
+__device__ inline void lds_barrier() {
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  __builtin_amdgcn_s_barrier();
+}
+
+// Persistent fast path: one block per LDS/register slot of the chip walks over a strided list
+// of tiles.
+//
+// Epilogue: a lane's own 16-byte runs sit on 32 different rows, and written that way the stores
+// reach a fraction of the write bandwidth.  So the finished tile is rounded to bf16 and
+// transposed through LDS (the operand ring is dead by then) into whole output rows: 16-byte chunk
+// c of staged row r sits at position c ^ (r mod chunks-per-row), which makes both the
+// accumulator-side accesses (32 rows, one chunk) and the row-side accesses (one row, all chunks)
+// bank-conflict free.  A residual tile is fetched INTO the staging area first (direct-to-LDS,
+// whole rows); each lane adds its runs in fp32 and overwrites them with the rounded result, so
+// there is still one rounding, at the end.
+//
+// Overlap across tiles:
+//  * the first slab of the next tile is requested BEFORE the epilogue of the current one (into
+//    ring buffer 0; the tile is staged through buffer 1, in row halves if it is larger than a
+//    buffer), so its latency hides behind the epilogue;
+//  * a tile that is staged in one pass (128 x 128, and the SwiGLU 256 x 128) is then parked in
+//    registers (32 per lane) and the next tile's k loop issues a few of these row stores per slab
+//    instead of all blocks of the chip storing at once.  The vector-memory counter retires in
+//    order, so the wait for slab k tolerates exactly the stores issued after its loads
+//    (STORES_PER_IT).  Stores of tiles that touch the matrix edge are predicated, hence not
+//    countable, and are issued at once.  The 256 x 256 tile has no registers to spare (its
+//    accumulators are half the file) and stores at once, pass by pass.
+//
+// Tiles: XCD x (blocks with id = x mod 8) owns a contiguous run of the grouped tile order, its
+// blocks stride through that run together, so at any time one L2 serves a compact patch of y.
+template <int BM, int BN, int WM, int WN, int ACT, int MODE>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams p) {
+  static_assert(MODE == MODE_PLAIN || MODE == MODE_QKV, "split-K does not use this kernel");
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr bool SWIGLU = ACT == FORGE_ACT_SWIGLU;
@@ -253,72 +285,87 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dlds_kernel(GemmParams 
   constexpr int IA = BM / 8 / NW, IB = BN / 8 / NW;   // wave-wide 1 KB loads per wave per slab
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile / wave mismatch");
   static_assert(!SWIGLU || TN % 2 == 0, "SwiGLU pairs accumulators");
+  // output staging
+  constexpr int NCH = BN_OUT / 8;                     // 16-byte chunks per output row
+  constexpr int RPL = 64 / NCH;                       // rows per wave-wide 1 KB access
+  constexpr int NPASS = (BM * BN_OUT * 2 + STAGE - 1) / STAGE;   // staging passes (row ranges)
+  constexpr int BMP = BM / NPASS;                     // rows per pass
+  constexpr int NITP = BMP / RPL / NW;                // wave-wide accesses per wave and pass
+  constexpr int NIT = NITP * NPASS;                   // 16-byte row pieces per lane and tile
+  // a tile staged in one pass is parked in registers; the large tile (two passes, accumulators
+  // alone take half the register file) is stored at once, pass by pass
+  constexpr bool PARK = NPASS == 1;
+  constexpr int NPARK = PARK ? NIT : 1;
+  constexpr int STORE_ITS = !PARK ? 1 : (NPARK < 8 ? NPARK : 8);   // k iterations that carry stores
+  constexpr int STORES_PER_IT = PARK ? NPARK / STORE_ITS : 0;
+  static_assert(BM % NPASS == 0 && BMP * BN_OUT * 2 <= STAGE, "a pass must fit one ring buffer");
+  static_assert(64 % NCH == 0 && BMP % (RPL * NW) == 0 && BMP % 32 == 0 && NCH <= 32, "staging plan");
+  static_assert(!PARK || (NPARK % STORE_ITS == 0 && STORES_PER_IT <= 3), "store plan");
   extern __shared__ __attribute__((aligned(16))) char smem[];   // [A0 | B0 | A1 | B1]
+  char* const stg = smem + STAGE;                     // staging area = ring buffer 1
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  int tile;
-  {
-    const int pid = blockIdx.x, nwg = gridDim.x;   // grid.y indexes the k split
-    const int xcd = pid & 7, idx = pid >> 3;
-    const int per = nwg >> 3, rem = nwg & 7;
-    tile = xcd * per + min(xcd, rem) + idx;
-  }
-  constexpr int GROUP_M = 8;
-  const int in_group = GROUP_M * p.tiles_n;
-  const int group = tile / in_group;
-  const int first_m = group * GROUP_M;
-  const int gsz = min(p.tiles_m - first_m, GROUP_M);
-  const int tile_m = first_m + (tile % in_group) % gsz;
-  const int tile_n = (tile % in_group) / gsz;
-  const int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
+  const int fr = lane & 31, fh = lane >> 5;
   const int M = p.M, N = p.N, K = p.K;
+  const int nk = K / BK;
 
-  // ---- direct-to-LDS copy plan ---------------------------------------------------------------
+  // ---- this block's tiles ----------------------------------------------------------------------
+  const int ntiles = p.tiles_m * p.tiles_n;
+  const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3, bpx = gridDim.x >> 3;
+  const int lo = xcd * (ntiles >> 3) + min(xcd, ntiles & 7);
+  const int cnt = (ntiles >> 3) + (xcd < (ntiles & 7) ? 1 : 0);
+  if (idx >= cnt) return;                             // uniform over the block
+  constexpr int GROUP_M = 8;
+  auto tile_origin = [&](int tile, int& m0, int& n0) {
+    const int in_group = GROUP_M * p.tiles_n;
+    const int group = tile / in_group;
+    const int first_m = group * GROUP_M;
+    const int gsz = min(p.tiles_m - first_m, GROUP_M);
+    m0 = (first_m + (tile % in_group) % gsz) * BM;
+    n0 = ((tile % in_group) / gsz) * BN_OUT;
+  };
+
+  // ---- direct-to-LDS copy plan, sources as 32-bit byte offsets ------------------------------------
   // wave-wide load i of this wave fills LDS rows (i*NW + wave)*8 .. +8 of a slab (1 KB at
   // lane*16): lane -> (row = base + lane/8, position = lane%8) -> logical chunk = position ^ f(row)
-  const bf16* a_src[IA];
-  const bf16* b_src[IB];
+  unsigned a_off[IA], b_off[IB];
+  auto set_sources = [&](int m0, int n0) {
 #pragma unroll
-  for (int i = 0; i < IA; ++i) {
-    const int r = (i * NW + wave) * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ ((r >> 1) & 7);
-    a_src[i] = p.x + (int64_t)min(m0 + r, M - 1) * K + c * 8;   // rows past the end re-read the last row
-  }
-#pragma unroll
-  for (int i = 0; i < IB; ++i) {
-    const int r = (i * NW + wave) * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ ((r >> 1) & 7);
-    int gn;
-    if (SWIGLU) {
-      const int wcol = r / (32 * TN), t = (r / 32) % TN, rr = r % 32;
-      const int col = n0 + (wcol * (TN / 2) + t % (TN / 2)) * 32 + rr;
-      gn = min(col, N - 1) + (t >= TN / 2 ? N : 0);
-    } else {
-      gn = min(n0 + r, N - 1);
+    for (int i = 0; i < IA; ++i) {
+      const int r = (i * NW + wave) * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ ((r >> 1) & 7);
+      a_off[i] = ((unsigned)min(m0 + r, M - 1) * (unsigned)K + c * 8) * 2u;
     }
-    b_src[i] = p.w + (int64_t)gn * K + c * 8;
-  }
+#pragma unroll
+    for (int i = 0; i < IB; ++i) {
+      const int r = (i * NW + wave) * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ ((r >> 1) & 7);
+      int gn;
+      if (SWIGLU) {
+        const int wcol = r / (32 * TN), t = (r / 32) % TN, rr = r % 32;
+        const int col = n0 + (wcol * (TN / 2) + t % (TN / 2)) * 32 + rr;
+        gn = min(col, N - 1) + (t >= TN / 2 ? N : 0);
+      } else {
+        gn = min(n0 + r, N - 1);
+      }
+      b_off[i] = ((unsigned)gn * (unsigned)K + c * 8) * 2u;
+    }
+  };
   auto issue = [&](int k0, int buf) {
     char* sa = smem + buf * STAGE;
     char* sb = sa + A_BYTES;
+    const char* xb = reinterpret_cast<const char*>(p.x) + k0 * 2;
+    const char* wb = reinterpret_cast<const char*>(p.w) + k0 * 2;
 #pragma unroll
     for (int i = 0; i < IA; ++i)
-      __builtin_amdgcn_global_load_lds((const void*)(a_src[i] + k0), (lds_void*)(sa + (i * NW + wave) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const void*)(xb + a_off[i]), (lds_void*)(sa + (i * NW + wave) * 1024), 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < IB; ++i)
-      __builtin_amdgcn_global_load_lds((const void*)(b_src[i] + k0), (lds_void*)(sb + (i * NW + wave) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const void*)(wb + b_off[i]), (lds_void*)(sb + (i * NW + wave) * 1024), 16, 0, 0);
   };
 
   floatx16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  const int fr = lane & 31, fh = lane >> 5;
   auto compute = [&](int buf) {
     const char* sa = smem + buf * STAGE;
     const char* sb = sa + A_BYTES;
@@ -339,30 +386,44 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dlds_kernel(GemmParams 
     }
   };
 
-  const int k_begin = MODE == MODE_SPLITK ? blockIdx.y * p.k_per_split : 0;
-  const int k_end = MODE == MODE_SPLITK ? min(K, k_begin + p.k_per_split) : K;
-  const int nk = (k_end - k_begin) / BK;
+  // ---- output pieces ---------------------------------------------------------------------------
+  // piece `it` of a tile: tile row and logical chunk of this lane (pass-major, the staging plan)
+  auto piece_row = [&](int it) { return (it / NITP) * BMP + ((it % NITP) * NW + wave) * RPL + lane / NCH; };
+  auto piece_chunk = [&](int row) { return (lane % NCH) ^ (row & (NCH - 1)); };
+  // head split: n / head_dim by multiplication (exact for n * head_dim < 2^32), (batch, position)
+  // of a row from those of the tile's first row
+  const unsigned dh_magic = MODE == MODE_QKV ? 0xffffffffu / (unsigned)p.sp.head_dim + 1u : 0u;
+  auto dst_of = [&](int t_b, int t_s, int m0_, int row, int n) -> bf16* {
+    if (MODE == MODE_QKV) {
+      // 8 consecutive columns never straddle a head (head_dim % 8 == 0, n % 8 == 0)
+      int sb_ = t_b, ss_ = t_s + row;
+      while (ss_ >= p.sp.q_len) { ss_ -= p.sp.q_len; ++sb_; }
+      const int dh = p.sp.head_dim, nq = p.sp.q_heads * dh, nkv = p.sp.kv_heads * dh;
+      const bool is_q = n < nq, is_k = n < nq + nkv;
+      const int nn = is_q ? n : (is_k ? n - nq : n - nq - nkv);
+      const int h = (int)__umulhi((unsigned)nn, dh_magic);
+      const int d = nn - h * dh;
+      if (is_q) return (bf16*)p.sp.q + (((int64_t)sb_ * p.sp.q_heads + h) * p.sp.q_len + ss_) * dh + d;
+      return (bf16*)(is_k ? p.sp.k_cache : p.sp.v_cache) +
+             (((int64_t)sb_ * p.sp.kv_heads + h) * p.sp.kv_cap + p.sp.pos0 + ss_) * dh + d;
+    }
+    return p.y + (int64_t)(m0_ + row) * p.ldy + n;
+  };
+  u32x4 parked[NPARK];
+  bool pending = false;                  // uniform
+  bool flushed = false;                  // uniform: the last NIT vector-memory operations of this wave
+                                         // are the unpredicated stores of the previous tile
+  int pm0 = 0, pn0 = 0, pb = 0, ps = 0;  // parked tile: origin, (batch, position) of its first row
+  // interior tiles only: every piece is a full, valid 16-byte store
+  auto store_parked = [&](int first, int count) {
 #pragma unroll
-  for (int st = 0; st < STAGES - 1; ++st)
-    if (st < nk) issue(k_begin + st * BK, st);
-  for (int kt = 0; kt < nk; ++kt) {
-    // this thread's loads of slab kt are in LDS once at most `ahead` younger slabs are outstanding
-    // (loads retire in order; L loads per thread and slab)
-    constexpr int L = IA + IB;
-    const int ahead = min(STAGES - 2, nk - 1 - kt);
-    if (ahead <= 0) __builtin_amdgcn_s_waitcnt(0x0f70);                                          // vmcnt(0)
-    else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0f70 | (L & 0xf) | ((L >> 4) << 14));      // vmcnt(L)
-    else __builtin_amdgcn_s_waitcnt(0x0f70 | ((2 * L) & 0xf) | (((2 * L) >> 4) << 14));          // vmcnt(2L)
-    // bare s_barrier (no fence: a fence would wait for the younger slabs too)
-    __builtin_amdgcn_s_barrier();   // everyone's are; everyone is done reading the buffer refilled next
-    if (kt + STAGES - 1 < nk) issue(k_begin + (kt + STAGES - 1) * BK, (kt + STAGES - 1) % STAGES);
-    compute(kt % STAGES);
-  }
+    for (int it = 0; it < NPARK; ++it) {
+      if (it < first || it >= first + count) continue;
+      const int row = piece_row(it);
+      *reinterpret_cast<u32x4*>(dst_of(pb, ps, pm0, row, pn0 + piece_chunk(row) * 8)) = parked[it];
+    }
+  };
 
-  // ---- epilogue: lane = output row m; registers = columns ---------------------------------------
-  // register v of accumulator (i, j) is column 8(v/4) + 4 fh + v%4 of its 32-column block.  Swapping
-  // register groups (0,2) and (1,3) between lanes l and l^32 leaves lanes 0-31 with columns 0..15 and
-  // lanes 32-63 with columns 16..31, each as two runs of 8 consecutive columns.
   auto runs_of = [&](const floatx16& a, float (&run)[2][8]) {
 #pragma unroll
     for (int gp = 0; gp < 2; ++gp)
@@ -374,91 +435,163 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dlds_kernel(GemmParams 
         run[gp][4 + r] = __uint_as_float(sw[1]);
       }
   };
-  const bool vec_y = (p.ldy & 7) == 0;          // plain mode: rows of y / residual 16-byte aligned
-  const bool vec_part = (N & 3) == 0;           // split-K mode: rows of the fp32 partials aligned
+  const bool has_res = MODE == MODE_PLAIN && p.residual != nullptr;
+
+  int tt = idx, m0, n0;
+  tile_origin(lo + tt, m0, n0);
+  set_sources(m0, n0);
+  if (nk > 0) issue(0, 0);
+  for (;;) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int m = m0 + (wm * TM + i) * 32 + fr;
-    const bool row_ok = m < M;
-    int sb_ = 0, ss_ = 0;
-    if (MODE == MODE_QKV) { sb_ = m / p.sp.q_len; ss_ = m - sb_ * p.sp.q_len; }
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN_OUT; ++j) {
-      float run[2][8], run2[2][8];
-      runs_of(acc[i][j], run);
-      if (SWIGLU) runs_of(acc[i][SWIGLU ? j + TN / 2 : j], run2);
-      const int nb = n0 + (wn * TN_OUT + j) * 32 + 16 * fh;
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int gp = 0; gp < 2; ++gp) {
-        const int n = nb + 8 * gp;
-        if (!row_ok || n >= N) continue;
-        const bool full = n + 8 <= N;
-        float o[8];
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // ---- k loop: slab kt multiplied while slab kt+1 loads and parked rows drain -----------------
+    for (int kt = 0; kt < nk; ++kt) {
+      // younger than the loads of slab kt: only the stores issued right after them
+      if (PARK && pending && kt >= 1 && kt <= STORE_ITS) __builtin_amdgcn_s_waitcnt(0x0f70 | STORES_PER_IT);
+      else if (!PARK && kt == 0 && flushed) __builtin_amdgcn_s_waitcnt(0x0f70 | (NIT & 0xf) | ((NIT >> 4) << 14));
+      else __builtin_amdgcn_s_waitcnt(0x0f70);
+      __builtin_amdgcn_s_barrier();   // slab kt is in LDS for everyone; buffer (kt+1)&1 is free
+      if (kt + 1 < nk) issue((kt + 1) * BK, (kt + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);   // the wait above counts on loads first, stores second
+      if (PARK && pending && kt < STORE_ITS) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = run[gp][e];
-        if (MODE == MODE_SPLITK) {     // raw partial sums; the reduce kernel carries the epilogue
-          float* dst = p.part + ((int64_t)blockIdx.y * M + m) * N + n;
-          if (full && vec_part) {
-            Vec8<float>::store(dst, o);
-          } else {
-            for (int e = 0; e < 8 && n + e < N; ++e) dst[e] = o[e];
-          }
-          continue;
+        for (int c = 0; c < STORE_ITS; ++c)
+          if (c == kt) store_parked(c * STORES_PER_IT, STORES_PER_IT);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      compute(kt & 1);
+    }
+    if (PARK && pending && nk < STORE_ITS) {
+#pragma unroll
+      for (int c = 0; c < STORE_ITS; ++c)
+        if (c >= nk) store_parked(c * STORES_PER_IT, STORES_PER_IT);
+    }
+    pending = false;
+
+    // ---- next tile's first slab, then the epilogue of this one ------------------------------------
+    const int next = tt + bpx;
+    const bool has_next = next < cnt;
+    int nm0 = 0, nn0 = 0;
+    lds_barrier();                    // every wave is done with the operand slabs
+    if (has_next) {
+      tile_origin(lo + next, nm0, nn0);
+      set_sources(nm0, nn0);
+      if (nk > 0) issue(0, 0);
+    }
+    const bool interior = m0 + BM <= M && n0 + BN_OUT <= N;
+    int tb = 0, ts = 0;
+    if (MODE == MODE_QKV) { tb = m0 / p.sp.q_len; ts = m0 - tb * p.sp.q_len; }
+#pragma unroll
+    for (int pass = 0; pass < NPASS; ++pass) {
+      if (pass > 0) lds_barrier();    // the previous pass has been read out
+      if (has_res) {
+        // the residual rows of this pass land in the staging area first (whole rows, swizzled)
+#pragma unroll
+        for (int itp = 0; itp < NITP; ++itp) {
+          const int row = piece_row(pass * NITP + itp);
+          const int gm = min(m0 + row, M - 1);
+          int gn = n0 + piece_chunk(row) * 8;
+          if (gn + 8 > N) gn = 0;     // chunks past the end fetch something valid, unused
+          __builtin_amdgcn_global_load_lds((const void*)(p.residual + (int64_t)gm * p.ldy + gn),
+                                           (lds_void*)(stg + (itp * NW + wave) * 1024), 16, 0, 0);
         }
-        if (p.bias != nullptr) {
-          if (full) {
-            float bb[8];
-            Vec8<bf16>::load(p.bias + n, bb);
+        __builtin_amdgcn_s_waitcnt(0x0f70);
+        lds_barrier();
+      }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] += bb[e];
-            if (SWIGLU) {
-              Vec8<bf16>::load(p.bias + N + n, bb);     // N % 8 == 0 is checked by the host for SwiGLU
+      for (int i = 0; i < TM; ++i) {
+        const int rl = (wm * TM + i) * 32 + fr;       // row inside the tile
+        if (rl / BMP != pass) continue;               // uniform over the wave
+        const int rp = rl - pass * BMP;               // row inside the pass
 #pragma unroll
-              for (int e = 0; e < 8; ++e) run2[gp][e] += bb[e];
+        for (int j = 0; j < TN_OUT; ++j) {
+          float run[2][8], run2[2][8];
+          runs_of(acc[i][j], run);
+          if (SWIGLU) runs_of(acc[i][SWIGLU ? j + TN / 2 : j], run2);
+#pragma unroll
+          for (int gp = 0; gp < 2; ++gp) {
+            const int cl = (wn * TN_OUT + j) * 4 + 2 * fh + gp;   // chunk inside the tile row
+            const int n = n0 + cl * 8;
+            // bias / residual only with N % 8 == 0 (host): a chunk is all in or all out
+            const bool in = n + 8 <= N;
+            float o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = run[gp][e];
+            if (p.bias != nullptr && in) {
+              float bb[8];
+              Vec8<bf16>::load(p.bias + n, bb);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) o[e] += bb[e];
+              if (SWIGLU) {
+                Vec8<bf16>::load(p.bias + N + n, bb);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) run2[gp][e] += bb[e];
+              }
             }
-          } else {
-            for (int e = 0; e < 8 && n + e < N; ++e) {
-              o[e] += (float)p.bias[n + e];
-              if (SWIGLU) run2[gp][e] += (float)p.bias[N + n + e];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = SWIGLU ? silu_f(o[e]) * run2[gp][e] : apply_act<ACT>(o[e]);
+            bf16* slot = reinterpret_cast<bf16*>(stg + (rp * NCH + (cl ^ (rp & (NCH - 1)))) * 16);
+            if (has_res && in) {
+              float rr[8];
+              Vec8<bf16>::load(slot, rr);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) o[e] += rr[e];
             }
+            Vec8<bf16>::store(slot, o);
           }
         }
+      }
+      lds_barrier();
+      if (interior && PARK) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = SWIGLU ? silu_f(o[e]) * run2[gp][e] : apply_act<ACT>(o[e]);
-        if (MODE == MODE_QKV) {
-          // 8 consecutive columns never straddle a head (head_dim % 8 == 0, n % 8 == 0)
-          const int dh = p.sp.head_dim, nq = p.sp.q_heads * dh, nkv = p.sp.kv_heads * dh;
-          bf16* dst;
-          if (n < nq) {
-            dst = (bf16*)p.sp.q + (((int64_t)sb_ * p.sp.q_heads + n / dh) * p.sp.q_len + ss_) * dh + n % dh;
+        for (int itp = 0; itp < NITP; ++itp)
+          parked[itp] = *reinterpret_cast<const u32x4*>(stg + (itp * NW + wave) * 1024 + lane * 16);
+      } else if (interior) {
+#pragma unroll
+        for (int itp = 0; itp < NITP; ++itp) {
+          const int row = piece_row(pass * NITP + itp);
+          *reinterpret_cast<u32x4*>(dst_of(tb, ts, m0, row, n0 + piece_chunk(row) * 8)) =
+              *reinterpret_cast<const u32x4*>(stg + (itp * NW + wave) * 1024 + lane * 16);
+        }
+      } else {
+        // edge tile: predicated stores straight from the staging area
+#pragma unroll 1
+        for (int itp = 0; itp < NITP; ++itp) {
+          const int row = pass * BMP + (itp * NW + wave) * RPL + lane / NCH;
+          const int m = m0 + row, n = n0 + piece_chunk(row) * 8;
+          if (m >= M || n >= N) continue;
+          const u32x4 v = *reinterpret_cast<const u32x4*>(stg + (itp * NW + wave) * 1024 + lane * 16);
+          bf16* dst = dst_of(tb, ts, m0, row, n);
+          if (n + 8 <= N) {
+            *reinterpret_cast<u32x4*>(dst) = v;
           } else {
-            const bool is_k = n < nq + nkv;
-            const int nn = is_k ? n - nq : n - nq - nkv;
-            dst = (bf16*)(is_k ? p.sp.k_cache : p.sp.v_cache) +
-                  (((int64_t)sb_ * p.sp.kv_heads + nn / dh) * p.sp.kv_cap + p.sp.pos0 + ss_) * dh + nn % dh;
-          }
-          Vec8<bf16>::store(dst, o);     // the host checks N % 8 == 0 for the split
-          continue;
-        }
-        const int64_t at = (int64_t)m * p.ldy + n;
-        if (full && vec_y) {
-          if (p.residual != nullptr) {
-            float rr[8];
-            Vec8<bf16>::load(p.residual + at, rr);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] += rr[e];
-          }
-          Vec8<bf16>::store(p.y + at, o);
-        } else {
-          for (int e = 0; e < 8 && n + e < N; ++e) {
-            float val = o[e];
-            if (p.residual != nullptr) val += (float)p.residual[at + e];
-            p.y[at + e] = (bf16)val;
+            const bf16* src = reinterpret_cast<const bf16*>(stg + (itp * NW + wave) * 1024 + lane * 16);
+            for (int e = 0; n + e < N; ++e) dst[e] = src[e];
           }
         }
       }
     }
+    flushed = !PARK && interior && !has_res;
+    if (interior && PARK) {
+      pending = true;
+      pm0 = m0;
+      pn0 = n0;
+      pb = tb;
+      ps = ts;
+    }
+    if (!has_next) break;
+    // the staging area is ring buffer 1: the barrier of the next k loop's first iteration comes
+    // before anything is loaded into it
+    tt = next;
+    m0 = nm0;
+    n0 = nn0;
   }
+  if (PARK && pending) store_parked(0, NPARK);
 }
 
 // Weight-streaming kernel for M <= 64 (decode): HBM-bound, every weight byte is read once.
@@ -619,16 +752,14 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p, int sp
   }
 }
 
-template <bool FAST, int BM, int BN, int WM, int WN, int ACT, int MODE, int STAGES = 2>
-forge_status launch_cfg(const GemmParams& p0, int splits, hipStream_t s) {
-  static_assert(STAGES >= 2 && STAGES <= 4 && (FAST || STAGES == 2), "stage count");
+template <int BM, int BN, int WM, int WN, int ACT, int MODE>
+forge_status launch_generic(const GemmParams& p0, int splits, hipStream_t s) {
   GemmParams p = p0;
   constexpr int BN_OUT = ACT == FORGE_ACT_SWIGLU ? BN / 2 : BN;
   p.tiles_m = ceil_div(p.M, BM);
   p.tiles_n = ceil_div(p.N, BN_OUT);
-  constexpr int smem = STAGES * (BM + BN) * BK * 2;
-  auto kern = FAST ? gemm_bf16_dlds_kernel<BM, BN, WM, WN, ACT, MODE, STAGES>
-                   : gemm_bf16_generic_kernel<BM, BN, WM, WN, ACT, MODE>;
+  constexpr int smem = 2 * (BM + BN) * BK * 2;
+  auto kern = gemm_bf16_generic_kernel<BM, BN, WM, WN, ACT, MODE>;
   static bool configured = false;   // idempotent attribute, set once per instantiation
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -641,14 +772,54 @@ forge_status launch_cfg(const GemmParams& p0, int splits, hipStream_t s) {
   return launch_status();
 }
 
+// Persistent launch: one block per resident slot (the 256 x 256 tile fills a CU, two 128 x 128
+// blocks share one), in multiples of the 8 XCDs.
+inline int compute_units() {
+  static int cus = 0;     // same value on every device of a homogeneous node
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      v = 256;
+    cus = v;
+  }
+  return cus;
+}
+
+template <int BM, int BN, int WM, int WN, int ACT, int MODE>
+forge_status launch_pers(const GemmParams& p0, hipStream_t s) {
+  GemmParams p = p0;
+  constexpr int BN_OUT = ACT == FORGE_ACT_SWIGLU ? BN / 2 : BN;
+  p.tiles_m = ceil_div(p.M, BM);
+  p.tiles_n = ceil_div(p.N, BN_OUT);
+  constexpr int smem = 2 * (BM + BN) * BK * 2;
+  constexpr int per_cu = smem <= 80 * 1024 ? 2 : 1;
+  auto kern = gemm_bf16_pers_kernel<BM, BN, WM, WN, ACT, MODE>;
+  static bool configured = false;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+      return FORGE_ERR_HIP;
+    configured = true;
+  }
+  const int slots = compute_units() * per_cu / 8 * 8;
+  const int ntiles = p.tiles_m * p.tiles_n;
+  const int blocks = min(slots, (ntiles + 7) / 8 * 8);
+  kern<<<dim3(blocks), dim3(WM * WN * 64), smem, s>>>(p);
+  return launch_status();
+}
+
 // Which kernel and tile a problem gets.  Fast path: K a multiple of the slab and 16-byte aligned
 // output rows (the head split and the fp32 partials have their own alignment rules).
 enum Variant { V_FAST_256 = 0, V_FAST_128 = 1, V_GEN_256 = 2, V_GEN_128 = 3, V_SKINNY_FAST = 4, V_SKINNY_GEN = 5 };
-inline Variant choose_variant(int M, int N, int K, int ldy, forge_act act, bool qkv) {
+inline Variant choose_variant(int M, int N, int K, int ldy, forge_act act, bool qkv, bool epi_loads) {
   const bool k_ok = K % BK == 0;
+  // the fast kernels address x and w with 32-bit byte offsets
+  const int64_t w_rows = act == FORGE_ACT_SWIGLU ? 2 * (int64_t)N : N;
+  const bool small_ok = (int64_t)M * K * 2 < (1ll << 32) && w_rows * K * 2 < (1ll << 32);
   if (M <= 64) return k_ok ? V_SKINNY_FAST : V_SKINNY_GEN;
-  const bool rows_ok = qkv ? N % 8 == 0 : (ldy % 8 == 0 && (act != FORGE_ACT_SWIGLU || N % 8 == 0));
-  const bool fast = k_ok && rows_ok;
+  const bool rows_ok = qkv ? N % 8 == 0 : (ldy % 8 == 0 && (N % 8 == 0 || (act != FORGE_ACT_SWIGLU && !epi_loads)));
+  const bool fast = k_ok && rows_ok && small_ok;
   const int64_t big = (int64_t)ceil_div(M, 256) * ceil_div(N, act == FORGE_ACT_SWIGLU ? 128 : 256);
   if (big >= 512) return fast ? V_FAST_256 : V_GEN_256;
   return fast ? V_FAST_128 : V_GEN_128;
@@ -674,12 +845,13 @@ inline SkinnyPlan plan_skinny(int N, int K, forge_act act) {
 
 template <int ACT, int MODE>
 forge_status launch_act(const GemmParams& p, hipStream_t s) {
-  const Variant v = choose_variant(p.M, p.N, p.K, p.ldy, (forge_act)ACT, MODE == MODE_QKV);
+  const Variant v = choose_variant(p.M, p.N, p.K, p.ldy, (forge_act)ACT, MODE == MODE_QKV,
+                                   p.bias != nullptr || p.residual != nullptr);
   switch (v) {
-    case V_FAST_256: return launch_cfg<true, 256, 256, 2, 4, ACT, MODE>(p, 1, s);
-    case V_FAST_128: return launch_cfg<true, 128, 128, 2, 2, ACT, MODE>(p, 1, s);
-    case V_GEN_256: return launch_cfg<false, 256, 256, 2, 4, ACT, MODE>(p, 1, s);
-    case V_GEN_128: return launch_cfg<false, 128, 128, 2, 2, ACT, MODE>(p, 1, s);
+    case V_FAST_256: return launch_pers<256, 256, 2, 4, ACT, MODE>(p, s);
+    case V_FAST_128: return launch_pers<128, 128, 2, 2, ACT, MODE>(p, s);
+    case V_GEN_256: return launch_generic<256, 256, 2, 4, ACT, MODE>(p, 1, s);
+    case V_GEN_128: return launch_generic<128, 128, 2, 2, ACT, MODE>(p, 1, s);
     default: break;
   }
   // skinny: raw split-K GEMM over all weight rows into fp32 partials, then reduce + epilogue
@@ -700,7 +872,7 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
     gemm_bf16_wstream_kernel<<<dim3(ceil_div(q.N, 64), sk.splits), 256, smem, s>>>(q);
     st = launch_status();
   } else {
-    st = launch_cfg<false, 64, 64, 2, 2, FORGE_ACT_NONE, MODE_SPLITK>(q, sk.splits, s);
+    st = launch_generic<64, 64, 2, 2, FORGE_ACT_NONE, MODE_SPLITK>(q, sk.splits, s);
   }
   if (st != FORGE_OK) return st;
   const int64_t threads = (int64_t)p.M * ceil_div(p.N, 4);
@@ -717,9 +889,9 @@ size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act) {
 }
 
 const char* gemm_bf16_variant(int M, int N, int K, int ldy, forge_act act) {
-  switch (choose_variant(M, N, K, ldy, act, false)) {
-    case V_FAST_256: return "gemm_bf16_dlds<256,256,2,4>";
-    case V_FAST_128: return "gemm_bf16_dlds<128,128,2,2>";
+  switch (choose_variant(M, N, K, ldy, act, false, false)) {
+    case V_FAST_256: return "gemm_bf16_pers<256,256,2,4>";
+    case V_FAST_128: return "gemm_bf16_pers<128,128,2,2>";
     case V_GEN_256: return "gemm_bf16_generic<256,256,2,4>";
     case V_GEN_128: return "gemm_bf16_generic<128,128,2,2>";
     case V_SKINNY_FAST: return "gemm_bf16_wstream<64>+splitk";

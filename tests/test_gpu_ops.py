@@ -81,7 +81,7 @@ def test_gemm_padded_row_stride(F, M, N, K, ld):
     r = I.normal(67, 0, "residual", (M, ld), 1.0, bf16=True)
     ref = O.gemm_bias_act(x, w, b, r[:, :N], "gelu_tanh")
     ty = torch.full((M, ld), 7.0, dtype=torch.bfloat16, device="cuda")
-    assert "dlds" in F.forge_gemm_variant(M, N, K, "gelu_tanh", torch.bfloat16, ldy=ld)
+    assert "pers" in F.forge_gemm_variant(M, N, K, "gelu_tanh", torch.bfloat16, ldy=ld)
     F.forge_gemm_bias_gelu(dev(x, True), dev(w, True), dev(b, True), dev(r, True), ty, "gelu_tanh", n=N)
     torch.cuda.synchronize()
     check(ty[:, :N], ref, True, "padded-stride gemm")
