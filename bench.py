@@ -35,7 +35,98 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="stop adding oracle samples once this much CPU time is spent")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="launch a plain copy of known size, then the per-launch GEMM loop of the roofline "
+                         "section, and exit: the program to run under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`")
+    ap.add_argument("--traffic-summarize", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="turn the two counter_collection.csv files of the probe runs into "
+                         "profiles/hbm_traffic.json (no GPU needed)")
     return ap.parse_args()
+
+
+# ---------------------------------------------------------------------------------------------
+# HBM traffic of the dominant kernel from hardware counters (collected offline, see --traffic-probe)
+# ---------------------------------------------------------------------------------------------
+
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+KERNEL_SOURCES = ["gemm_bf16.hip", "common.hpp"]
+COPY_BYTES = 256 << 20          # the probe's copy kernel reads and writes this many bytes
+
+
+def kernel_source_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2604_16498_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def recorded_traffic(workload, kernel):
+    """Bytes per launch measured for `kernel` on `workload`, or None when there is no record or
+    the kernel sources have changed since the counters were taken."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if rec.get("source_sha256") != kernel_source_digest() or rec.get("workload") != workload:
+        return None
+    # "gemm_bf16_pers<128,128,2,2> act=none" -> template instantiation "<128,128,2,2,ACT,MODE>"
+    variant, _, act = kernel.partition(" act=")
+    from paper_2604_16498_amd import binding as F
+    inst = "%s,%d,0>" % (variant[:-1], F.ACT.get(act, 0))
+    ent = rec.get("kernels", {}).get(inst)
+    return None if ent is None else round(ent["fetch_bytes_per_launch"] + ent["write_bytes_per_launch"])
+
+
+def summarize_traffic(fetch_csv, write_csv):
+    """FETCH_SIZE / WRITE_SIZE are reported in KiB per dispatch; both are scaled by what the same
+    counter reads for the copy kernel of COPY_BYTES (read once, written once)."""
+    import csv
+    import re
+
+    def per_kernel(path, counter):
+        acc = {}
+        with open(path) as f:
+            for r in csv.DictReader(f):
+                if r["Counter_Name"] != counter:
+                    continue
+                acc.setdefault((r["Kernel_Name"], r["Dispatch_Id"]), 0.0)
+                acc[(r["Kernel_Name"], r["Dispatch_Id"])] += float(r["Counter_Value"])
+        out = {}
+        for (name, _), v in acc.items():
+            out.setdefault(name, []).append(v)
+        return out
+
+    def short(name):
+        m = re.search(r"(gemm_bf16_\w+?)_kernel<([^>]*)>", name)
+        return "%s<%s>" % (m.group(1), m.group(2).replace(" ", "")) if m else name[:60]
+
+    fetch, write = per_kernel(fetch_csv, "FETCH_SIZE"), per_kernel(write_csv, "WRITE_SIZE")
+    copy = [k for k in fetch if "copy" in k.lower()]
+    if not copy:
+        raise SystemExit("no copy kernel found in %s" % fetch_csv)
+    ck = max(copy, key=lambda k: max(fetch[k]))
+    # skip the first launch of every kernel (cold caches, first-touch)
+    mean = lambda v: sum(v[1:]) / max(1, len(v) - 1) if len(v) > 1 else v[0]
+    # the runtime's copy kernel also serves small transfers: keep the probe's large copies only
+    big = lambda v: [x for x in v if x > 0.5 * max(v)]
+    f_scale = COPY_BYTES / (mean(big(fetch[ck])) * 1024.0)
+    w_scale = COPY_BYTES / (mean(big(write[ck])) * 1024.0)
+    kernels = {}
+    for k in fetch:
+        if "gemm_bf16" not in k:
+            continue
+        kernels[short(k)] = {
+            "launches": len(fetch[k]),
+            "fetch_bytes_per_launch": mean(fetch[k]) * 1024.0 * f_scale,
+            "write_bytes_per_launch": mean(write.get(k, [0.0])) * 1024.0 * w_scale,
+        }
+    rec = {"workload": None, "source_sha256": kernel_source_digest(), "copy_kernel": ck[:80],
+           "copy_bytes": COPY_BYTES, "fetch_scale": f_scale, "write_scale": w_scale, "kernels": kernels}
+    return rec
+
 
 
 # ---------------------------------------------------------------------------------------------
@@ -153,6 +244,14 @@ def step_bytes(wl):
 
 def main():
     args = parse()
+    if args.traffic_summarize:
+        from paper_2604_16498_amd import inputs as I
+        rec = summarize_traffic(*args.traffic_summarize)
+        rec["workload"] = I.WORKLOADS[int(args.workload[1])].name
+        with open(TRAFFIC_FILE, "w") as f:
+            json.dump(rec, f, indent=1)
+        print(json.dumps(rec, indent=1))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -169,6 +268,12 @@ def main():
     wl = I.WORKLOADS[int(args.workload[1])]
     m = build_model(wl, F, torch, I)
     pos0 = wl.pos0
+    if args.traffic_probe:
+        src = torch.empty(COPY_BYTES, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     def step():
         F.forge_model_forward(m["model"], m["inp"], m["out"], m["kc"], m["vc"], pos0, m["ws"])
@@ -177,11 +282,11 @@ def main():
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(1 if args.traffic_probe else args.steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / (1 if args.traffic_probe else args.steps)
     tokens = wl.batch * wl.seq
     value = tokens / (ms_per_step * 1e-3)
     gemm_fl, attn_fl = step_flops(wl)
@@ -192,7 +297,7 @@ def main():
     dt = torch.bfloat16 if wl.bf16 else torch.float32
     sh = wl.block
     groups = {}
-    reps = max(3, min(args.steps, 10))
+    reps = 3 if args.traffic_probe else max(3, min(args.steps, 10))
     for name, M, N, K, act, count in gemm_launches(wl):
         if name == "lm_head":
             w, b = m["mw"]["wte"], None
@@ -223,6 +328,8 @@ def main():
         gr["flops"] += 2.0 * M * nw * K * len(durs)
         gr["launches"] += len(durs)
         del x, y, res
+    if args.traffic_probe:
+        return
     dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["time"])
     avg_dur = dom["time"] / dom["launches"]
     flops_per_launch = dom["flops"] / dom["launches"]
@@ -236,7 +343,8 @@ def main():
         achieved = flops_per_launch / avg_dur / 1e12
         roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS if wl.bf16 else 157.3,
                     "unit": "TFLOP/s", "frac": round(achieved / (PEAK_BF16_TFLOPS if wl.bf16 else 157.3), 4),
-                    "traffic": None, "kernel": dom_name, "avg_launch_us": round(avg_dur * 1e6, 2),
+                    "traffic": recorded_traffic(wl.name, dom_name), "kernel": dom_name,
+                    "avg_launch_us": round(avg_dur * 1e6, 2),
                     "launches_timed": dom["launches"],
                     "groups": {k: {"tflops": round(v["flops"] / v["time"] / 1e12, 1),
                                    "avg_us": round(v["time"] / v["launches"] * 1e6, 2)} for k, v in groups.items()}}

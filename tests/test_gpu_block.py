@@ -73,6 +73,26 @@ def test_block_prefill_then_decode(F, sh, bf16):
     check(tk, kc, bf16, "k cache after decode")
 
 
+@pytest.mark.parametrize("flavour", ["gpt", "llama"])
+def test_block_many_short_sequences(F, flavour):
+    """400 sequences of 96 tokens: the QKV GEMM has more 128-row tiles (600) than resident blocks,
+    and every tile spans two sequences, so the head split of the persistent kernel resolves
+    (sequence, position) across tile rows and across the tiles one block walks over."""
+    if flavour == "gpt":
+        sh = I.BlockShape(128, 2, 1, 64, 128)
+    else:
+        sh = I.BlockShape(128, 2, 1, 64, 192, norm="rmsnorm", mlp_act="swiglu", use_rope=True,
+                          rope_base=500000.0, has_bias=False)
+    B, S = 400, 96
+    w = I.block_weights(sh, 75, 0, bf16=True, bias_std=0.05, random_affine=True, weight_std=0.06)
+    x = I.normal(75, 0, "x", (B, S, sh.d_model), 1.0, bf16=True)
+    kc = np.zeros((B, sh.kv_heads, S, sh.head_dim)); vc = np.zeros_like(kc)
+    ref = O.decoder_block(sh, w, x, kc, vc, pos0=0)
+    out, tk, tv = run_block(F, sh, w, x, True, S)
+    check(tk, kc, True, "k cache"); check(tv, vc, True, "v cache")
+    check(out, ref, True, "block, many short sequences", chain=True)
+
+
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
 def test_block_in_place(F, bf16):
     sh = SMALL_GPT

@@ -88,6 +88,39 @@ def test_gemm_padded_row_stride(F, M, N, K, ld):
     assert torch.all(ty[:, N:] == 7.0)
 
 
+@pytest.mark.parametrize("M,N,K,act,use_b,use_r,ld", [
+    (5137, 1832, 128, "none", True, True, 0),        # 128-tiles: 615 > resident blocks, K shorter than the store window
+    (5137, 1832, 640, "gelu_tanh", True, False, 0),  # parked rows drain inside the next k loop
+    (5137, 1825, 640, "none", False, False, 1832),   # ragged last column chunk, padded row stride
+    (5200, 1792, 192, "none", False, True, 0),       # residual only
+    (5893, 5896, 192, "none", True, True, 0),        # 256-tiles: 576 > resident blocks, ragged edges
+    (5893, 5891, 64, "relu", False, False, 5896),    # 256-tiles, odd N
+    (5893, 2824, 128, "swiglu", True, False, 0),     # gated 256 x 128 output tiles
+])
+def test_gemm_many_tiles_per_block(F, M, N, K, act, use_b, use_r, ld):
+    """More tiles than resident blocks: every persistent block walks over several tiles, edge
+    tiles included, so the cross-tile prefetch and the deferred row stores are exercised."""
+    wn = 2 * N if act == "swiglu" else N
+    ldy = ld or N
+    x = I.normal(68, 0, "x", (M, K), 1.0, bf16=True)
+    w = I.normal(68, 0, "w_up", (wn, K), 1.0 / math.sqrt(K), bf16=True)
+    b = I.normal(68, 0, "b_up", (wn,), 0.5, bf16=True) if use_b else None
+    r = I.normal(68, 0, "residual", (M, ldy), 1.0, bf16=True) if use_r else None
+    ref = O.gemm_bias_act(x, w, b, None if r is None else r[:, :N], act)
+    assert "pers" in F.forge_gemm_variant(M, N, K, act, torch.bfloat16, ldy=ldy)
+    ty = torch.full((M, ldy), 7.0, dtype=torch.bfloat16, device="cuda")
+    F.forge_gemm_bias_gelu(dev(x, True), dev(w, True), None if b is None else dev(b, True),
+                           None if r is None else dev(r, True), ty, act, n=N)
+    torch.cuda.synchronize()
+    check(ty[:, :N], ref, True, "persistent gemm %s" % act)
+    assert torch.all(ty[:, N:] == 7.0)
+    again = torch.full((M, ldy), 7.0, dtype=torch.bfloat16, device="cuda")
+    F.forge_gemm_bias_gelu(dev(x, True), dev(w, True), None if b is None else dev(b, True),
+                           None if r is None else dev(r, True), again, act, n=N)
+    torch.cuda.synchronize()
+    assert torch.equal(again, ty)
+
+
 def test_gemm_residual_in_place(F):
     M, N, K = 200, 256, 128
     x = I.normal(62, 0, "x", (M, K), 1.0, bf16=True)
