@@ -595,36 +595,53 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
 }
 
 // Weight-streaming kernel for M <= 64 (decode): HBM-bound, every weight byte is read once.
-// A block owns 64 weight rows (output columns) and one k range.  Weight slabs (8 KB) and
-// activation slabs (8 KB, L2 resident) both arrive by direct-to-LDS loads, but in SEPARATE rings
-// filled by different waves: waves 0-1 only issue weight loads into a ring of WS_W slabs, waves
-// 2-3 only issue activation loads into a ring of WS_X slabs.  The vector-memory counter retires
-// in order within a wave, so mixing the two streams in one wave would tie the HBM stream to the
-// depth of the L2 stream; split this way a block keeps (WS_W - 1) x 8 KB of weight in flight,
-// two blocks per CU.  All four waves multiply.  Output: fp32 partial sums D[n, m] for the
-// fixed-order split-K reduce.
-constexpr int WS_W = 6;   // weight ring depth
-constexpr int WS_X = 3;   // activation ring depth
-constexpr int WS_SMEM = (WS_W + WS_X) * 64 * BK * 2;
+// A block owns BN weight rows (output columns) and one k range.  Weight slabs (BN x 64) and
+// activation slabs (64 x 64, L2 resident) both arrive by direct-to-LDS loads, but in SEPARATE rings
+// filled by different waves: the first half of the waves only issue weight loads, the second half
+// only activation loads.  The vector-memory counter retires in order within a wave, so mixing the
+// two streams in one wave would tie the HBM stream to the depth of the L2 stream.
+//
+// What bounds this kernel is the number of requests a CU's vector-memory pipeline keeps in
+// flight, and an activation line (an L2 hit) occupies a slot just like a weight line (an HBM
+// miss): with BN = 64 half of all requests are activation re-reads and the weight stream gets
+// half of the pipeline.  Wider blocks re-read the activations less often per weight byte
+// (1 : 2 at BN = 128, 1 : 4 at BN = 256); the launcher picks the widest block that still gives
+// every CU work.  All waves multiply: a wave owns 32 weight rows and both halves of the
+// activation rows.  Output: fp32 partial sums D[n, m] for the fixed-order split-K reduce.
+template <int BN>
+struct WStream {
+  static constexpr int NWV = BN >= 256 ? 8 : 4;            // waves per block
+  static constexpr int NG = BN / 32;                       // 32-row groups of weight rows
+  static constexpr int TMW = NG >= NWV ? 2 : 1;            // activation halves per wave
+  static constexpr int NWL = NWV / 2, NXL = NWV - NWL;     // loader waves per stream
+  static constexpr int LPW_W = BN / 8 / NWL;               // wave-wide 1 KB loads per loader and slab
+  static constexpr int LPW_X = 8 / NXL;
+  static constexpr int WS_W = BN == 128 ? 3 : 4;           // weight ring depth
+  static constexpr int WS_X = 3;                           // activation ring depth
+  static constexpr int SLAB_W = BN * BK * 2, SLAB_X = 64 * BK * 2;
+  static constexpr int SMEM = WS_W * SLAB_W + WS_X * SLAB_X;
+  static_assert(NG * (2 / TMW) == NWV, "waves cover the block tile");
+};
 
-__global__ __launch_bounds__(256) void gemm_bf16_wstream_kernel(GemmParams p) {
-  constexpr int SLAB = 64 * BK * 2;           // 8 KB: 64 rows of 64 bf16
-  constexpr int LPW = 4;                      // wave-wide 1 KB loads per loader wave per slab
+template <int BN>
+__global__ __launch_bounds__(WStream<BN>::NWV * 64) void gemm_bf16_wstream_kernel(GemmParams p) {
+  using C = WStream<BN>;
   extern __shared__ __attribute__((aligned(16))) char smem[];   // [W ring | x ring]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wn = wave % C::NG, wm0 = wave / C::NG;   // wm0: the activation half of a TMW == 1 wave
   const int fr = lane & 31, fh = lane >> 5;
   const int M = p.M, N = p.N, K = p.K;
-  const int n0 = blockIdx.x * 64;
-  const bool w_loader = wave < 2;             // wave-uniform role
-  const int lw = wave & 1;                    // index among the two loaders of a stream
+  const int n0 = blockIdx.x * BN;
+  const bool w_loader = wave < C::NWL;        // wave-uniform role
+  const int lw = w_loader ? wave : wave - C::NWL;   // index among the loaders of a stream
 
-  // loader plan: wave-wide load i of loader lw fills slab rows (i*2 + lw)*8 .. +8
-  const bf16* src[LPW];
+  // loader plan: wave-wide load i of loader lw fills slab rows (i * loaders + lw)*8 .. +8
+  constexpr int LPW_MAX = C::LPW_W > C::LPW_X ? C::LPW_W : C::LPW_X;
+  const bf16* src[LPW_MAX];
 #pragma unroll
-  for (int i = 0; i < LPW; ++i) {
-    const int r = (i * 2 + lw) * 8 + (lane >> 3);
+  for (int i = 0; i < LPW_MAX; ++i) {
+    const int r = (i * (w_loader ? C::NWL : C::NXL) + lw) * 8 + (lane >> 3);
     const int c = (lane & 7) ^ ((r >> 1) & 7);
     src[i] = w_loader ? p.w + (int64_t)min(n0 + r, N - 1) * K + c * 8
                       : p.x + (int64_t)min(r, M - 1) * K + c * 8;
@@ -632,68 +649,90 @@ __global__ __launch_bounds__(256) void gemm_bf16_wstream_kernel(GemmParams p) {
   const int k_begin = blockIdx.y * p.k_per_split;
   const int k_end = min(K, k_begin + p.k_per_split);
   const int nk = (k_end - k_begin) / BK;
-  const int depth = w_loader ? WS_W : WS_X;
-  char* ring = smem + (w_loader ? 0 : WS_W * SLAB);
+  char* const xring = smem + C::WS_W * C::SLAB_W;
 
-  auto issue = [&](int kt) {      // slab kt of this wave's stream (clamped past the end: see below)
+  // slab kt of this wave's stream; past the end the last slab is re-loaded into its own buffer
+  // (same bytes, harmless), so every iteration issues the same number of loads per wave and the
+  // in-order wait count is a constant per role
+  auto issue = [&](int kt) {
     const int k = min(kt, nk - 1);
-    char* dst = ring + (k % depth) * SLAB;
+    if (w_loader) {
+      char* dst = smem + (k % C::WS_W) * C::SLAB_W;
 #pragma unroll
-    for (int i = 0; i < LPW; ++i)
-      __builtin_amdgcn_global_load_lds((const void*)(src[i] + k_begin + k * BK),
-                                       (lds_void*)(dst + (i * 2 + lw) * 1024), 16, 0, 0);
+      for (int i = 0; i < C::LPW_W; ++i)
+        __builtin_amdgcn_global_load_lds((const void*)(src[i] + k_begin + k * BK),
+                                         (lds_void*)(dst + (i * C::NWL + lw) * 1024), 16, 0, 0);
+    } else {
+      char* dst = xring + (k % C::WS_X) * C::SLAB_X;
+#pragma unroll
+      for (int i = 0; i < C::LPW_X; ++i)
+        __builtin_amdgcn_global_load_lds((const void*)(src[i] + k_begin + k * BK),
+                                         (lds_void*)(dst + (i * C::NXL + lw) * 1024), 16, 0, 0);
+    }
   };
 
-  floatx16 acc;
+  floatx16 acc[C::TMW];
 #pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  for (int t = 0; t < C::TMW; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
 
-  // every iteration issues exactly LPW loads per wave (past the end the last slab is re-loaded into
-  // its own buffer: same bytes, harmless), so the in-order wait count is a constant per role
-  for (int st = 0; st < depth - 1; ++st) issue(st);
+  if (w_loader) {
+    for (int st = 0; st < C::WS_W - 1; ++st) issue(st);
+  } else {
+    for (int st = 0; st < C::WS_X - 1; ++st) issue(st);
+  }
   for (int kt = 0; kt < nk; ++kt) {
     // slab kt of my stream has landed when at most (depth - 2) younger slabs are outstanding
-    if (w_loader) __builtin_amdgcn_s_waitcnt(0x0f70 | (((WS_W - 2) * LPW) & 0xf) | ((((WS_W - 2) * LPW) >> 4) << 14));
-    else __builtin_amdgcn_s_waitcnt(0x0f70 | (((WS_X - 2) * LPW) & 0xf) | ((((WS_X - 2) * LPW) >> 4) << 14));
+    constexpr int AW = (C::WS_W - 2) * C::LPW_W, AX = (C::WS_X - 2) * C::LPW_X;
+    if (w_loader) __builtin_amdgcn_s_waitcnt(0x0f70 | (AW & 0xf) | ((AW >> 4) << 14));
+    else __builtin_amdgcn_s_waitcnt(0x0f70 | (AX & 0xf) | ((AX >> 4) << 14));
     // a bare s_barrier: __syncthreads() carries a fence that drains ALL outstanding loads
     // (vmcnt(0)) and would collapse the ring to a single slab in flight
     __builtin_amdgcn_s_barrier();   // both streams' slab kt are in LDS; slab kt-1's buffers are free
-    issue(kt + depth - 1);
-    const char* sw = smem + (kt % WS_W) * SLAB;
-    const char* sx = smem + WS_W * SLAB + (kt % WS_X) * SLAB;
+    issue(kt + (w_loader ? C::WS_W : C::WS_X) - 1);
+    const char* sw = smem + (kt % C::WS_W) * C::SLAB_W;
+    const char* sx = xring + (kt % C::WS_X) * C::SLAB_X;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       const bf16x8 wf = *reinterpret_cast<const bf16x8*>(sw + lds_chunk_off(wn * 32 + fr, 2 * ks + fh));
-      const bf16x8 xf = *reinterpret_cast<const bf16x8*>(sx + lds_chunk_off(wm * 32 + fr, 2 * ks + fh));
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc, 0, 0, 0);
+#pragma unroll
+      for (int t = 0; t < C::TMW; ++t) {
+        const int mh = C::TMW == 2 ? t : wm0;
+        const bf16x8 xf = *reinterpret_cast<const bf16x8*>(sx + lds_chunk_off(mh * 32 + fr, 2 * ks + fh));
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[t], 0, 0, 0);
+      }
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0f70);   // drain the re-loads of the tail before the block ends
   __syncthreads();
 
   // ---- partial sums: lane = row m, registers = columns (see the fast kernel's epilogue) -----------
-  float run[2][8];
-#pragma unroll
-  for (int gp = 0; gp < 2; ++gp)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      auto sw2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[4 * gp + r]),
-                                                  __float_as_uint(acc[4 * (gp + 2) + r]), false, false);
-      run[gp][r] = __uint_as_float(sw2[0]);
-      run[gp][4 + r] = __uint_as_float(sw2[1]);
-    }
-  const int m = wm * 32 + fr;
-  if (m >= M) return;
   const bool vec_part = (N & 3) == 0;
 #pragma unroll
-  for (int gp = 0; gp < 2; ++gp) {
-    const int n = n0 + wn * 32 + 16 * fh + 8 * gp;
-    if (n >= N) continue;
-    float* dst = p.part + ((int64_t)blockIdx.y * M + m) * N + n;
-    if (n + 8 <= N && vec_part) {
-      Vec8<float>::store(dst, run[gp]);
-    } else {
-      for (int e = 0; e < 8 && n + e < N; ++e) dst[e] = run[gp][e];
+  for (int t = 0; t < C::TMW; ++t) {
+    float run[2][8];
+#pragma unroll
+    for (int gp = 0; gp < 2; ++gp)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        auto sw2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[t][4 * gp + r]),
+                                                    __float_as_uint(acc[t][4 * (gp + 2) + r]), false, false);
+        run[gp][r] = __uint_as_float(sw2[0]);
+        run[gp][4 + r] = __uint_as_float(sw2[1]);
+      }
+    const int m = (C::TMW == 2 ? t : wm0) * 32 + fr;
+    if (m >= M) continue;
+#pragma unroll
+    for (int gp = 0; gp < 2; ++gp) {
+      const int n = n0 + wn * 32 + 16 * fh + 8 * gp;
+      if (n >= N) continue;
+      float* dst = p.part + ((int64_t)blockIdx.y * M + m) * N + n;
+      if (n + 8 <= N && vec_part) {
+        Vec8<float>::store(dst, run[gp]);
+      } else {
+        for (int e = 0; e < 8 && n + e < N; ++e) dst[e] = run[gp][e];
+      }
     }
   }
 }
@@ -752,6 +791,20 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p, int sp
   }
 }
 
+// Persistent launch: one block per resident slot (the 256 x 256 tile fills a CU, two 128 x 128
+// blocks share one), in multiples of the 8 XCDs.
+inline int compute_units() {
+  static int cus = 0;     // same value on every device of a homogeneous node
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      v = 256;
+    cus = v;
+  }
+  return cus;
+}
+
 template <int BM, int BN, int WM, int WN, int ACT, int MODE>
 forge_status launch_generic(const GemmParams& p0, int splits, hipStream_t s) {
   GemmParams p = p0;
@@ -770,20 +823,6 @@ forge_status launch_generic(const GemmParams& p0, int splits, hipStream_t s) {
   dim3 grid(p.tiles_m * p.tiles_n, splits), block(WM * WN * 64);
   kern<<<grid, block, smem, s>>>(p);
   return launch_status();
-}
-
-// Persistent launch: one block per resident slot (the 256 x 256 tile fills a CU, two 128 x 128
-// blocks share one), in multiples of the 8 XCDs.
-inline int compute_units() {
-  static int cus = 0;     // same value on every device of a homogeneous node
-  if (cus == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-      v = 256;
-    cus = v;
-  }
-  return cus;
 }
 
 template <int BM, int BN, int WM, int WN, int ACT, int MODE>
@@ -827,20 +866,41 @@ inline Variant choose_variant(int M, int N, int K, int ldy, forge_act act, bool 
 
 struct SkinnyPlan {
   int ncols;        // columns of the partial planes (2N for SwiGLU)
+  int bn;           // weight rows per block of the streaming kernel
   int splits;
   int k_per_split;
 };
 inline SkinnyPlan plan_skinny(int N, int K, forge_act act) {
   SkinnyPlan sp;
   sp.ncols = act == FORGE_ACT_SWIGLU ? 2 * N : N;
-  const int tiles = ceil_div(sp.ncols, 64);
   const int slabs = ceil_div(K, BK);
-  int want = ceil_div(512, tiles);                 // aim at >= 512 blocks
-  want = max(1, min(want, slabs / 8));             // but at least 8 slabs of work per block
+  const int cus = compute_units();
+  // About one block per CU measured best on the decode shapes: more blocks mean more k ranges,
+  // i.e. more partial-sum traffic and a longer reduce.  256-row blocks (fewest activation re-reads
+  // per weight byte) when two k ranges of them already cover the chip, 128-row blocks otherwise.
+  sp.bn = ceil_div(sp.ncols, 256) * 8 >= cus * 3 ? 256 : 128;
+  const int tiles = ceil_div(sp.ncols, sp.bn);
+  int want = (cus + tiles / 2) / tiles;              // k ranges for ~ one block per CU
+  want = max(1, min(want, min(8, slabs / 8)));       // at least 8 slabs of work per block
   const int per = ceil_div(slabs, want);
   sp.splits = ceil_div(slabs, per);
   sp.k_per_split = per * BK;
   return sp;
+}
+
+template <int BN>
+forge_status launch_wstream(const GemmParams& q, int splits, hipStream_t s) {
+  using C = WStream<BN>;
+  auto kern = gemm_bf16_wstream_kernel<BN>;
+  static bool configured = false;
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM) != hipSuccess)
+      return FORGE_ERR_HIP;
+    configured = true;
+  }
+  kern<<<dim3(ceil_div(q.N, BN), splits), C::NWV * 64, C::SMEM, s>>>(q);
+  return launch_status();
 }
 
 template <int ACT, int MODE>
@@ -861,16 +921,7 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
   q.k_per_split = sk.k_per_split;
   forge_status st;
   if (v == V_SKINNY_FAST) {
-    constexpr int smem = WS_SMEM;
-    static bool configured = false;
-    if (!configured) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_wstream_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-        return FORGE_ERR_HIP;
-      configured = true;
-    }
-    gemm_bf16_wstream_kernel<<<dim3(ceil_div(q.N, 64), sk.splits), 256, smem, s>>>(q);
-    st = launch_status();
+    st = sk.bn == 256 ? launch_wstream<256>(q, sk.splits, s) : launch_wstream<128>(q, sk.splits, s);
   } else {
     st = launch_generic<64, 64, 2, 2, FORGE_ACT_NONE, MODE_SPLITK>(q, sk.splits, s);
   }
@@ -894,7 +945,7 @@ const char* gemm_bf16_variant(int M, int N, int K, int ldy, forge_act act) {
     case V_FAST_128: return "gemm_bf16_pers<128,128,2,2>";
     case V_GEN_256: return "gemm_bf16_generic<256,256,2,4>";
     case V_GEN_128: return "gemm_bf16_generic<128,128,2,2>";
-    case V_SKINNY_FAST: return "gemm_bf16_wstream<64>+splitk";
+    case V_SKINNY_FAST: return "gemm_bf16_wstream+splitk";
     default: return "gemm_bf16_generic<64,64,2,2>+splitk";
   }
 }
