@@ -859,8 +859,13 @@ inline Variant choose_variant(int M, int N, int K, int ldy, forge_act act, bool 
   if (M <= 64) return k_ok ? V_SKINNY_FAST : V_SKINNY_GEN;
   const bool rows_ok = qkv ? N % 8 == 0 : (ldy % 8 == 0 && (N % 8 == 0 || (act != FORGE_ACT_SWIGLU && !epi_loads)));
   const bool fast = k_ok && rows_ok && small_ok;
+  // the 256-row tile multiplies faster (half the operand traffic per flop) but fills a CU on its
+  // own: take it when its tiles come to whole rounds over the CUs, or to many rounds
   const int64_t big = (int64_t)ceil_div(M, 256) * ceil_div(N, act == FORGE_ACT_SWIGLU ? 128 : 256);
-  if (big >= 512) return fast ? V_FAST_256 : V_GEN_256;
+  const int64_t cus = compute_units();
+  const int64_t rounds = (big + cus - 1) / cus;
+  const bool use_256 = big >= 4 * cus || (big * 10 >= cus * 9 && big * 100 >= rounds * cus * 85);
+  if (use_256) return fast ? V_FAST_256 : V_GEN_256;
   return fast ? V_FAST_128 : V_GEN_128;
 }
 
