@@ -155,6 +155,9 @@ forge_status forge_embed(const int32_t* ids, const void* wte, const void* wpe, v
  * w_qkv rows: Hq*dh query rows, then Hkv*dh key rows, then Hkv*dh value rows.
  * mlp_act: FORGE_ACT_GELU_TANH (w_up [d_ff,d]) or FORGE_ACT_SWIGLU (w_up [2*d_ff,d]).
  * Biases and norm shifts may be NULL.  All pointers in the descriptor are device pointers.
+ * With at most 64 rows (a decode step) the projections take a split-K path whose reduce step
+ * also carries RoPE (QKV projection) and Norm2 (output projection): same results up to rounding
+ * order, fewer launches.
  * ------------------------------------------------------------------------------------ */
 typedef struct {
   int d_model, q_heads, kv_heads, head_dim, d_ff;

@@ -110,12 +110,15 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
   st = launch_residual_norm(x_in, nullptr, d->norm1_g, d->norm1_b, nullptr, y, T, dm, d->eps, d->norm, d->dt, s);
   if (st != FORGE_OK) return st;
   // 2. QKV projection, written head-major: q to the workspace, k and v into the cache rows
-  QkvSplit sp = {q, k_cache, v_cache, d->q_heads, d->kv_heads, dh, q_len, kv_cap, pos0};
-  GemmArgs g = {y, d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, 0, FORGE_ACT_NONE, &sp, gws, pl.gemm};
+  // (a decode-sized QKV projection rotates q and k in its own reduce step)
+  const bool rope_in_gemm = d->use_rope && gemm_fuses_tail(T, nqkv, d->dt);
+  QkvSplit sp = {q, k_cache, v_cache, d->q_heads, d->kv_heads, dh, q_len, kv_cap, pos0,
+                 rope_in_gemm ? 1 : 0, d->rope_base};
+  GemmArgs g = {y, d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, 0, FORGE_ACT_NONE, &sp, nullptr, gws, pl.gemm};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
   // 3. rotary embedding of the new q and k rows
-  if (d->use_rope) {
+  if (d->use_rope && !rope_in_gemm) {
     st = launch_rope(q, batch, d->q_heads, q_len, dh, (int64_t)d->q_heads * q_len * dh,
                      (int64_t)q_len * dh, 0, pos0, d->rope_base, d->dt, s);
     if (st != FORGE_OK) return st;
@@ -128,18 +131,24 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
   st = attn_dispatch(at, d->dt, s);
   if (st != FORGE_OK) return st;
   // 5. output projection + bias + residual
-  g = GemmArgs{o, d->w_o, d->b_o, x_in, x_out, T, dm, hd, 0, FORGE_ACT_NONE, nullptr, gws, pl.gemm};
+  //    (decode-sized: the reduce step of the projection also produces the second norm)
+  const bool norm_in_gemm = gemm_fuses_tail(T, dm, d->dt);
+  NormTail nt = {d->norm2_g, d->norm2_b, y, d->eps, d->norm};
+  g = GemmArgs{o, d->w_o, d->b_o, x_in, x_out, T, dm, hd, 0, FORGE_ACT_NONE, nullptr,
+               norm_in_gemm ? &nt : nullptr, gws, pl.gemm};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
   // 6. second norm
-  st = launch_residual_norm(x_out, nullptr, d->norm2_g, d->norm2_b, nullptr, y, T, dm, d->eps, d->norm, d->dt, s);
-  if (st != FORGE_OK) return st;
+  if (!norm_in_gemm) {
+    st = launch_residual_norm(x_out, nullptr, d->norm2_g, d->norm2_b, nullptr, y, T, dm, d->eps, d->norm, d->dt, s);
+    if (st != FORGE_OK) return st;
+  }
   // 7. MLP up projection + bias + activation (SwiGLU: gate and up in one pass)
-  g = GemmArgs{y, d->w_up, d->b_up, nullptr, u, T, d->d_ff, dm, 0, d->mlp_act, nullptr, gws, pl.gemm};
+  g = GemmArgs{y, d->w_up, d->b_up, nullptr, u, T, d->d_ff, dm, 0, d->mlp_act, nullptr, nullptr, gws, pl.gemm};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
   // 8. MLP down projection + bias + residual
-  g = GemmArgs{u, d->w_down, d->b_down, x_out, x_out, T, dm, d->d_ff, 0, FORGE_ACT_NONE, nullptr, gws, pl.gemm};
+  g = GemmArgs{u, d->w_down, d->b_down, x_out, x_out, T, dm, d->d_ff, 0, FORGE_ACT_NONE, nullptr, nullptr, gws, pl.gemm};
   return gemm_dispatch(g, d->dt, s);
 }
 
@@ -232,7 +241,7 @@ forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias
   if (y == x || y == w) return FORGE_ERR_INVALID_ARG;
   const size_t need = gemm_ws(M, N, K, act, dt);
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FORGE_ERR_WORKSPACE;
-  GemmArgs a = {x, w, bias, residual, y, M, N, K, ldy, act, nullptr, workspace, workspace_bytes};
+  GemmArgs a = {x, w, bias, residual, y, M, N, K, ldy, act, nullptr, nullptr, workspace, workspace_bytes};
   return gemm_dispatch(a, dt, static_cast<hipStream_t>(stream));
 }
 
@@ -357,7 +366,7 @@ forge_status forge_model_forward(const forge_model_desc* model, const void* inpu
   if (st != FORGE_OK || !tokens) return st;
   // tied LM head: the token table is the weight of the last projection
   GemmArgs g = {yf, model->wte, nullptr, nullptr, output, T, model->vocab, dm, model->logits_ld, FORGE_ACT_NONE,
-                nullptr, bws, pl.block};
+                nullptr, nullptr, bws, pl.block};
   return gemm_dispatch(g, dt, s);
 }
 

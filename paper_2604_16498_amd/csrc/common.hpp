@@ -125,6 +125,18 @@ struct QkvSplit {
   void* k_cache;  // [B,Hkv,kv_cap,dh]
   void* v_cache;
   int q_heads, kv_heads, head_dim, q_len, kv_cap, pos0;
+  int rope;         // the GEMM rotates the new q and k rows itself (only where gemm_fuses_tail() says so)
+  float rope_base;
+};
+
+// Optional tail of a GEMM with a residual: y_norm = Norm(y) of the rows just produced, from the
+// fp32 values before y is rounded (the contract of the residual + norm operator).
+struct NormTail {
+  const void* gamma;
+  const void* beta;   // NULL: no shift
+  void* y_norm;       // [M, N]
+  float eps;
+  forge_norm kind;
 };
 
 struct GemmArgs {
@@ -137,12 +149,17 @@ struct GemmArgs {
   int ldy;                // row stride of y and residual in elements (0: N)
   forge_act act;
   const QkvSplit* split;  // NULL: plain row-major output
+  const NormTail* norm;   // NULL: none; honoured only where gemm_fuses_tail() says so
   void* workspace;
   size_t workspace_bytes;
 };
 
 forge_status launch_gemm_f32(const GemmArgs& a, hipStream_t s);
 forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
+// True when this problem takes the split-K path (M <= 64), whose reduce kernel can also rotate
+// the q / k heads of a head split (QkvSplit::rope) and normalise the rows of a residual GEMM
+// (GemmArgs::norm).  Otherwise both fields are ignored and the caller launches those operators.
+bool gemm_fuses_tail(int M, int N, forge_dtype dt);
 size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act);
 const char* gemm_bf16_variant(int M, int N, int K, int ldy, forge_act act);
 size_t gemm_f32_workspace_bytes(int M, int N, int K, forge_act act);

@@ -73,6 +73,7 @@ struct GemmParams {
   int k_per_split;    // split-K: k range of one block (multiple of 64); otherwise >= K
   float* part;        // split-K: fp32 partial sums [splits, M, N]
   QkvSplit sp;
+  NormTail nt;        // nt.y_norm == nullptr: none
 };
 
 enum Mode { MODE_PLAIN = 0, MODE_QKV = 1, MODE_SPLITK = 2 };
@@ -805,6 +806,121 @@ inline int compute_units() {
   return cus;
 }
 
+// Split-K second stage of the QKV projection with the rotary embedding applied to the q and k
+// heads before the single rounding to bf16.  One thread owns 4 consecutive pair indices of one
+// head of one row: columns d..d+3 and d+dh/2..d+dh/2+3.  Angles as in rope_kernel: fp64
+// position * theta, theta_i = base^(-2i/dh).
+__global__ __launch_bounds__(256) void splitk_reduce_qkv_rope_kernel(GemmParams p, int splits) {
+  const int dh = p.sp.head_dim, half = dh / 2, groups = half / 4;
+  const int heads = p.sp.q_heads + 2 * p.sp.kv_heads;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (int64_t)p.M * heads * groups) return;
+  const int j = (int)(gid % groups);
+  const int hg = (int)((gid / groups) % heads);
+  const int m = (int)(gid / ((int64_t)groups * heads));
+  const int N = p.N;
+  const int n_lo = hg * dh + 4 * j, n_hi = n_lo + half;
+  const int64_t plane = (int64_t)p.M * N;
+  const float* src = p.part + (int64_t)m * N;
+  floatx4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int z = 0; z < splits; ++z) {       // split order, independent 128-bit loads
+    lo += *reinterpret_cast<const floatx4*>(src + z * plane + n_lo);
+    hi += *reinterpret_cast<const floatx4*>(src + z * plane + n_hi);
+  }
+  if (p.bias != nullptr) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { lo[e] += (float)p.bias[n_lo + e]; hi[e] += (float)p.bias[n_hi + e]; }
+  }
+  if (hg < p.sp.q_heads + p.sp.kv_heads) {   // q and k heads rotate, v heads do not
+    const double pos = (double)(p.sp.pos0 + m % p.sp.q_len);
+    const double l2b = log2((double)p.sp.rope_base);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const double theta = exp2(-2.0 * (double)(4 * j + e) / (double)dh * l2b);
+      double sv, cv;
+      sincos(pos * theta, &sv, &cv);
+      const float c = (float)cv, sn = (float)sv, a = lo[e], d = hi[e];
+      lo[e] = a * c - d * sn;
+      hi[e] = d * c + a * sn;
+    }
+  }
+  u32x2 plo, phi;
+  plo[0] = pack_bf2(lo[0], lo[1]); plo[1] = pack_bf2(lo[2], lo[3]);
+  phi[0] = pack_bf2(hi[0], hi[1]); phi[1] = pack_bf2(hi[2], hi[3]);
+  *reinterpret_cast<u32x2*>(split_dst_bf16(p.sp, m, n_lo)) = plo;   // 4 columns stay inside a head half
+  *reinterpret_cast<u32x2*>(split_dst_bf16(p.sp, m, n_hi)) = phi;
+}
+
+// Split-K second stage of a projection with residual, followed by the normalisation of the
+// finished rows: one block per row; h = sum + bias + residual stays in fp32 registers, is stored
+// rounded to y, and y_norm = Norm(h) is computed from the fp32 values (mean, then centred
+// variance, as residual_norm_kernel does).  N <= 256 * 4 * NORM_TAIL_MAX_G columns.
+constexpr int NORM_TAIL_MAX_G = 16;
+__device__ inline float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();                      // red may still be read from the previous call
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+__global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(GemmParams p, int splits) {
+  __shared__ float red[4];
+  const int N = p.N, m = blockIdx.x;
+  const int64_t plane = (int64_t)p.M * N;
+  const float* src = p.part + (int64_t)m * N;
+  floatx4 h[NORM_TAIL_MAX_G];
+  float sum = 0.f;
+#pragma unroll
+  for (int g = 0; g < NORM_TAIL_MAX_G; ++g) {
+    const int n = (g * 256 + threadIdx.x) * 4;
+    h[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+    if (n >= N) continue;                 // N % 4 == 0 (host)
+    floatx4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int z = 0; z < splits; ++z) a += *reinterpret_cast<const floatx4*>(src + z * plane + n);
+    const int64_t at = (int64_t)m * p.ldy + n;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (p.bias != nullptr) a[e] += (float)p.bias[n + e];
+      if (p.residual != nullptr) a[e] += (float)p.residual[at + e];
+      sum += a[e];
+    }
+    u32x2 pk;
+    pk[0] = pack_bf2(a[0], a[1]); pk[1] = pack_bf2(a[2], a[3]);
+    *reinterpret_cast<u32x2*>(p.y + at) = pk;
+    h[g] = a;
+  }
+  const bool rms = p.nt.kind == FORGE_NORM_RMSNORM;
+  const float mean = rms ? 0.f : block_sum_256(sum, red) / (float)N;
+  float sq = 0.f;
+#pragma unroll
+  for (int g = 0; g < NORM_TAIL_MAX_G; ++g) {
+    const int n = (g * 256 + threadIdx.x) * 4;
+    if (n >= N) continue;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { const float d = h[g][e] - mean; sq += d * d; }
+  }
+  const float rstd = rsqrtf(block_sum_256(sq, red) / (float)N + p.nt.eps);
+  const bf16* gamma = (const bf16*)p.nt.gamma;
+  const bf16* beta = (const bf16*)p.nt.beta;
+  bf16* yn = (bf16*)p.nt.y_norm + (int64_t)m * N;
+#pragma unroll
+  for (int g = 0; g < NORM_TAIL_MAX_G; ++g) {
+    const int n = (g * 256 + threadIdx.x) * 4;
+    if (n >= N) continue;
+    float o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      o[e] = (h[g][e] - mean) * rstd * (float)gamma[n + e];
+      if (beta != nullptr) o[e] += (float)beta[n + e];
+    }
+    u32x2 pk;
+    pk[0] = pack_bf2(o[0], o[1]); pk[1] = pack_bf2(o[2], o[3]);
+    *reinterpret_cast<u32x2*>(yn + n) = pk;
+  }
+}
+
 template <int BM, int BN, int WM, int WN, int ACT, int MODE>
 forge_status launch_generic(const GemmParams& p0, int splits, hipStream_t s) {
   GemmParams p = p0;
@@ -931,6 +1047,15 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
     st = launch_generic<64, 64, 2, 2, FORGE_ACT_NONE, MODE_SPLITK>(q, sk.splits, s);
   }
   if (st != FORGE_OK) return st;
+  if (MODE == MODE_QKV && p.sp.rope) {
+    const int64_t threads = (int64_t)p.M * (p.sp.q_heads + 2 * p.sp.kv_heads) * (p.sp.head_dim / 8);
+    splitk_reduce_qkv_rope_kernel<<<(unsigned)ceil_div64(threads, 256), 256, 0, s>>>(p, sk.splits);
+    return launch_status();
+  }
+  if (MODE == MODE_PLAIN && ACT == FORGE_ACT_NONE && p.nt.y_norm != nullptr) {
+    splitk_reduce_norm_kernel<<<p.M, 256, 0, s>>>(p, sk.splits);
+    return launch_status();
+  }
   const int64_t threads = (int64_t)p.M * ceil_div(p.N, 4);
   splitk_reduce_kernel<ACT, MODE == MODE_QKV><<<(unsigned)ceil_div64(threads, 256), 256, 0, s>>>(p, sk.splits, sk.ncols);
   return launch_status();
@@ -942,6 +1067,10 @@ size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act) {
   if (M > 64) return 0;
   const SkinnyPlan sk = plan_skinny(N, K, act);
   return (size_t)sk.splits * M * sk.ncols * sizeof(float);
+}
+
+bool gemm_fuses_tail(int M, int N, forge_dtype dt) {
+  return dt == FORGE_BF16 && M <= 64 && N % 4 == 0 && N <= 256 * 4 * NORM_TAIL_MAX_G;
 }
 
 const char* gemm_bf16_variant(int M, int N, int K, int ldy, forge_act act) {
@@ -970,9 +1099,15 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   p.part = (float*)a.workspace;
   const size_t need = gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act);
   if (need > a.workspace_bytes || (need > 0 && a.workspace == nullptr)) return FORGE_ERR_WORKSPACE;
+  const bool tails = gemm_fuses_tail(a.M, a.N, FORGE_BF16);
+  if (a.norm != nullptr && tails && a.split == nullptr && a.act == FORGE_ACT_NONE) {
+    if (p.ldy != a.N) return FORGE_ERR_UNSUPPORTED;   // the norm tail writes dense rows
+    p.nt = *a.norm;
+  }
   if (a.split != nullptr) {
     if (a.act != FORGE_ACT_NONE || a.residual != nullptr) return FORGE_ERR_UNSUPPORTED;
     p.sp = *a.split;
+    if (!tails) p.sp.rope = 0;
     return launch_act<FORGE_ACT_NONE, MODE_QKV>(p, s);
   }
   switch (a.act) {
