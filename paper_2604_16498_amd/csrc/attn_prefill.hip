@@ -1,8 +1,8 @@
 // bf16 fused causal attention for prefill on the gfx950 matrix cores: scores, scale, mask,
 // softmax and the product with V in one kernel; S and P live only in registers.
 //
-// Work split: a 256-thread block (4 waves) owns 128 consecutive queries of one (batch, head);
-// each wave owns 32 of them and walks the keys in tiles of 64 up to its diagonal.
+// Work split: a 512-thread block (8 waves, one block per CU) owns 256 consecutive queries of one
+// (batch, head); each wave owns 32 of them and walks the keys in tiles of 64 up to its diagonal.
 //
 // Both contractions are computed TRANSPOSED so that the two MFMAs chain without any data
 // movement:
@@ -17,15 +17,26 @@
 // A lane therefore owns ONE query throughout: its 32 scores per tile sit in its own registers,
 // the row maximum needs a single exchange with lane^32 (the other half of the keys), the row
 // sum is kept as a per-lane partial and combined once at the end, and the rescale factor of
-// the online softmax is a per-lane scalar.
+// the online softmax is a per-lane scalar (applied only when some lane's maximum moved).
 //
 // The contraction order over keys inside a 16-key MFMA step is permuted (the same permutation
 // on both operands, so the sum is unchanged): element e of lane-half h is key
 // 16 s + 8 (e / 4) + 4 h + e % 4, which is what the S^T accumulator registers 8 (s % 2) + e hold.
 //
+// Pipeline: the softmax of a tile is ~1200 cycles of vector ALU work per wave against ~1000
+// cycles of MFMA, and within one wave the two cannot overlap (in-order issue).  So the scores
+// run ONE TILE AHEAD of softmax and P.V: S(t+1) does not depend on tile t, and the two waves
+// that share a SIMD (wave w and w+4) take the three steps in different orders --
+//   waves 0-3:  S(t+1) -> softmax(t) -> P.V(t)        waves 4-7:  softmax(t) -> P.V(t) -> S(t+1)
+// -- so that one is on the matrix core while the other is on the vector ALU, although the block
+// barrier per tile puts them back in step every time.  K is therefore fetched two tiles ahead
+// and V one tile ahead; since K(t) is dead once S(t) exists, two LDS buffers each still suffice.
+//
 // LDS: K tile rows padded by 16 B and V tile rows by 64 B so that the row reads (K) and the
-// 4-rows-by-64-B transposing reads (V) of a half wave fall on disjoint banks.  K and V tiles
-// are double buffered: the global loads of tile t+1 are issued before the MFMAs of tile t.
+// 4-rows-by-64-B transposing reads (V) of a half wave fall on disjoint banks.  Tiles go
+// HBM -> registers -> LDS: the loads are issued before the tile's arithmetic, the LDS stores
+// after it.  (Direct-to-LDS loads were measured slower here: issuing them costs more than the
+// staging they save, with only 32 MFMAs per wave and tile to hide it.)
 #include "common.hpp"
 
 namespace forge {
@@ -57,25 +68,29 @@ __device__ inline float xchg32_sum(float x) {
 }
 
 template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnParams p) {
-  constexpr int BQ = 128, BKV = 64;
+__global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
+  constexpr int BQ = 256, BKV = 64, NT = 512;
   constexpr int CPR = DH / 8;                 // 16-byte chunks per row
   constexpr int KS = DH * 2 + 16;             // K row stride in LDS (bytes)
   constexpr int VS = DH * 2 + 64;             // V row stride in LDS (bytes)
   constexpr int K_BYTES = BKV * KS, V_BYTES = BKV * VS;
-  constexpr int LPT = BKV * CPR / 256;        // chunks per thread per tensor per tile
+  constexpr int LPT = BKV * CPR / NT;         // chunks per thread per tensor per tile
   constexpr int NKS = DH / 16;                // MFMA k-steps over dh
   constexpr int NDT = DH / 32;                // 32-row tiles of O^T
-  extern __shared__ __attribute__((aligned(16))) char smem[];   // [K0 | V0 | K1 | V1]
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // [K0 | K1 | V0 | V1]
+  char* const kbuf = smem;
+  char* const vbuf = smem + 2 * K_BYTES;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int fr = lane & 31, fh = lane >> 5;
-  // late (long) query blocks first: they carry the most key tiles under the causal mask
-  const int qb = p.n_qblocks - 1 - blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z;
+  // late (long) query blocks first, over all heads: they carry the most key tiles under the
+  // causal mask, and blocks are handed out in launch order
+  const int qb = p.n_qblocks - 1 - blockIdx.y;
+  const int h = blockIdx.x % p.q_heads, b = blockIdx.x / p.q_heads;
   const int g = h / (p.q_heads / p.kv_heads);
   const int q0 = qb * BQ, q0w = q0 + wave * 32;
   const int off = p.kv_len - p.q_len;
+  const bool scores_first = wave < 4;         // the two waves of a SIMD alternate (see above)
 
   const bf16* kbase = p.k + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
   const bf16* vbase = p.v + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
@@ -102,31 +117,31 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnParams p) {
   const int wave_max_limit = p.causal ? min(q0w + 31, p.q_len - 1) + off : p.kv_len - 1;
   const int wave_min_limit = p.causal ? q0w + off : p.kv_len - 1;
 
-  // ---- global -> LDS copy plan ---------------------------------------------------------------
+  // ---- global -> registers -> LDS copy plan ----------------------------------------------------
   int ld_row[LPT], ld_c[LPT];
 #pragma unroll
   for (int i = 0; i < LPT; ++i) {
-    const int idx = tid + i * 256;
+    const int idx = tid + i * NT;
     ld_row[i] = idx / CPR;
     ld_c[i] = idx % CPR;
   }
   u32x4 rk[LPT], rv[LPT];
-  auto load_tile = [&](int t) {
+  auto load_rows = [&](const bf16* base, int t, u32x4 (&r)[LPT]) {
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int key = min(t * BKV + ld_row[i], p.kv_len - 1);   // rows past the end re-read the last key
-      rk[i] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)key * DH + ld_c[i] * 8);
-      rv[i] = *reinterpret_cast<const u32x4*>(vbase + (int64_t)key * DH + ld_c[i] * 8);
+      r[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)key * DH + ld_c[i] * 8);
     }
   };
-  auto store_tile = [&](int buf) {
-    char* sk = smem + buf * (K_BYTES + V_BYTES);
-    char* sv = sk + K_BYTES;
+  auto store_k = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-      *reinterpret_cast<u32x4*>(sk + ld_row[i] * KS + ld_c[i] * 16) = rk[i];
-      *reinterpret_cast<u32x4*>(sv + ld_row[i] * VS + ld_c[i] * 16) = rv[i];
-    }
+    for (int i = 0; i < LPT; ++i)
+      *reinterpret_cast<u32x4*>(kbuf + buf * K_BYTES + ld_row[i] * KS + ld_c[i] * 16) = rk[i];
+  };
+  auto store_v = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < LPT; ++i)
+      *reinterpret_cast<u32x4*>(vbuf + buf * V_BYTES + ld_row[i] * VS + ld_c[i] * 16) = rv[i];
   };
 
   floatx16 o_acc[NDT];
@@ -140,110 +155,132 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(AttnParams p) {
   // per-lane byte offset of the transposing V read inside a tile (without key step / d tile)
   const int vt_lane = (((lane & 15) >> 2) + 4 * fh) * VS + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
 
-  load_tile(0);
-  store_tile(0);
-  __syncthreads();
+  // ---- S^T = K . Q^T of one tile ---------------------------------------------------------------
+  floatx16 s_cur[2], s_nxt[2];
+  auto scores = [&](int t, floatx16 (&s_acc)[2]) {
+    const char* sk = kbuf + (t & 1) * K_BYTES;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s_acc[kb][e] = 0.f;
+    // K fragments run LA MFMAs ahead of their use so that no MFMA waits on an LDS read
+    constexpr int NF = 2 * NKS, LA = 4;
+    bf16x8 kf[LA];
+    auto kread = [&](int i) {
+      const int kb = i / NKS, ks = i % NKS;
+      return *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + fr) * KS + (2 * ks + fh) * 16);
+    };
+#pragma unroll
+    for (int i = 0; i < LA; ++i) kf[i] = kread(i);
+#pragma unroll
+    for (int i = 0; i < NF; ++i) {
+      __builtin_amdgcn_sched_barrier(0);
+      s_acc[i / NKS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % LA], qf[i % NKS], s_acc[i / NKS], 0, 0, 0);
+      if (i + LA < NF) kf[i % LA] = kread(i + LA);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
 
-  for (int t = 0; t < n_tiles; ++t) {
-    const bool more = t + 1 < n_tiles;
-    if (more) load_tile(t + 1);
+  // ---- mask, online softmax and O^T += V^T . P^T of one tile ---------------------------------------
+  auto softmax_pv = [&](int t, floatx16 (&s_acc)[2]) {
     const int kv0 = t * BKV;
-    if (kv0 <= wave_max_limit) {   // wave-uniform: tiles wholly above this wave's diagonal are skipped
-      const char* sk = smem + (t & 1) * (K_BYTES + V_BYTES);
-      const char* sv = sk + K_BYTES;
-
-      // ---- S^T = K . Q^T --------------------------------------------------------------------
-      floatx16 s_acc[2];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s_acc[kb][e] = 0.f;
-      {
-        // K fragments run LA MFMAs ahead of their use so that no MFMA waits on an LDS read
-        constexpr int NF = 2 * NKS, LA = 4;
-        bf16x8 kf[LA];
-        auto kread = [&](int i) {
-          const int kb = i / NKS, ks = i % NKS;
-          return *reinterpret_cast<const bf16x8*>(sk + (kb * 32 + fr) * KS + (2 * ks + fh) * 16);
-        };
-#pragma unroll
-        for (int i = 0; i < LA; ++i) kf[i] = kread(i);
-#pragma unroll
-        for (int i = 0; i < NF; ++i) {
-          __builtin_amdgcn_sched_barrier(0);
-          s_acc[i / NKS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % LA], qf[i % NKS], s_acc[i / NKS], 0, 0, 0);
-          if (i + LA < NF) kf[i % LA] = kread(i + LA);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      // ---- mask (diagonal / tail tiles only) ---------------------------------------------------
-      if (kv0 + BKV - 1 > wave_min_limit) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int key = kv0 + kb * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
-            if (key > my_limit) s_acc[kb][v] = -INFINITY;
-          }
-      }
-      // ---- online softmax ----------------------------------------------------------------------
-      float mx = s_acc[0][0];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s_acc[kb][v]);
-      mx = xchg32_max(mx);
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-      const float mc = m_new * c;
-      float psum = 0.f;
+    const char* sv = vbuf + (t & 1) * V_BYTES;
+    if (kv0 + BKV - 1 > wave_min_limit) {       // diagonal / tail tiles only
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const float pv = __builtin_amdgcn_exp2f(s_acc[kb][v] * c - mc);
-          s_acc[kb][v] = pv;
-          psum += pv;
+          const int key = kv0 + kb * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
+          if (key > my_limit) s_acc[kb][v] = -INFINITY;
         }
-      l_run = l_run * alpha + psum;
-      m_run = m_new;
+    }
+    float mx = s_acc[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s_acc[kb][v]);
+    mx = xchg32_max(mx);
+    const float m_new = fmaxf(m_run, mx);
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {   // wave-uniform: some maximum moved
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+      l_run *= alpha;
 #pragma unroll
       for (int i = 0; i < NDT; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
-
-      // ---- O^T += V^T . P^T ---------------------------------------------------------------------
-      {
-        bf16x8 pf[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) pf[s][e] = (bf16)s_acc[s >> 1][8 * (s & 1) + e];
-        // V^T fragments (two transposing reads each) run LA MFMAs ahead of their use
-        constexpr int NF = 4 * NDT, LA = 4;
-        typedef short v8i16 __attribute__((ext_vector_type(8)));
-        v4i16 lo[LA], hi[LA];
-        auto vread = [&](int i, v4i16& l, v4i16& h) {
-          const int s = i / NDT, dt = i % NDT;
-          const char* va = sv + vt_lane + (16 * s) * VS + dt * 64;
-          l = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(va));
-          h = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(va + 8 * VS));
-        };
-#pragma unroll
-        for (int i = 0; i < LA; ++i) vread(i, lo[i], hi[i]);
-#pragma unroll
-        for (int i = 0; i < NF; ++i) {
-          __builtin_amdgcn_sched_barrier(0);
-          const v4i16 l = lo[i % LA], h = hi[i % LA];
-          v8i16 both = {l[0], l[1], l[2], l[3], h[0], h[1], h[2], h[3]};
-          o_acc[i % NDT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[i / NDT], o_acc[i % NDT], 0, 0, 0);
-          if (i + LA < NF) vread(i + LA, lo[i % LA], hi[i % LA]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      m_run = m_new;
     }
-    if (more) store_tile((t + 1) & 1);
+    const float mc = m_run * c;
+    float psum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float pv = __builtin_amdgcn_exp2f(s_acc[kb][v] * c - mc);
+        s_acc[kb][v] = pv;
+        psum += pv;
+      }
+    l_run += psum;
+
+    bf16x8 pf[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pf[s][e] = (bf16)s_acc[s >> 1][8 * (s & 1) + e];
+    // V^T fragments (two transposing reads each) run LA MFMAs ahead of their use
+    constexpr int NF = 4 * NDT, LA = 4;
+    typedef short v8i16 __attribute__((ext_vector_type(8)));
+    v4i16 lo[LA], hi[LA];
+    auto vread = [&](int i, v4i16& l, v4i16& hh) {
+      const int s = i / NDT, dt = i % NDT;
+      const char* va = sv + vt_lane + (16 * s) * VS + dt * 64;
+      l = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(va));
+      hh = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(va + 8 * VS));
+    };
+#pragma unroll
+    for (int i = 0; i < LA; ++i) vread(i, lo[i], hi[i]);
+#pragma unroll
+    for (int i = 0; i < NF; ++i) {
+      __builtin_amdgcn_sched_barrier(0);
+      const v4i16 l = lo[i % LA], hh = hi[i % LA];
+      v8i16 both = {l[0], l[1], l[2], l[3], hh[0], hh[1], hh[2], hh[3]};
+      o_acc[i % NDT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[i / NDT], o_acc[i % NDT], 0, 0, 0);
+      if (i + LA < NF) vread(i + LA, lo[i % LA], hi[i % LA]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto wave_needs = [&](int t) { return t < n_tiles && t * BKV <= wave_max_limit; };   // wave-uniform
+
+  // ---- prologue: K(0), V(0), K(1) in LDS, S(0) in registers ---------------------------------------
+  load_rows(kbase, 0, rk);
+  load_rows(vbase, 0, rv);
+  store_k(0);
+  store_v(0);
+  if (n_tiles > 1) {
+    load_rows(kbase, 1, rk);
+    store_k(1);
+  }
+  __syncthreads();
+  if (wave_needs(0)) scores(0, s_cur);
+  __syncthreads();                     // K(0) is dead from here on: its buffer takes K(2)
+
+  for (int t = 0; t < n_tiles; ++t) {
+    // LDS now: K(t+1) in K buffer (t+1)&1, V(t) in V buffer t&1; K buffer t&1 and V buffer (t+1)&1 are free
+    if (t + 2 < n_tiles) load_rows(kbase, t + 2, rk);
+    if (t + 1 < n_tiles) load_rows(vbase, t + 1, rv);
+    const bool cur = wave_needs(t), nxt = wave_needs(t + 1);
+    if (scores_first) {
+      if (nxt) scores(t + 1, s_nxt);
+      if (cur) softmax_pv(t, s_cur);
+    } else {
+      if (cur) softmax_pv(t, s_cur);
+      if (nxt) scores(t + 1, s_nxt);
+    }
+    if (t + 2 < n_tiles) store_k(t & 1);
+    if (t + 1 < n_tiles) store_v((t + 1) & 1);
     __syncthreads();
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) s_cur[kb] = s_nxt[kb];
   }
 
   // ---- normalise and store: lane owns query my_q; registers 4g..4g+3 are 4 consecutive d -----
@@ -278,7 +315,7 @@ forge_status launch_dh(const AttnArgs& a, hipStream_t s) {
   p.kv_hs = a.kv_head_stride;
   p.scale_log2e = a.scale * 1.4426950408889634f;
   p.causal = a.causal;
-  p.n_qblocks = ceil_div(a.q_len, 128);
+  p.n_qblocks = ceil_div(a.q_len, 256);
   constexpr int smem = 2 * 64 * ((DH * 2 + 16) + (DH * 2 + 64));
   auto kern = attn_prefill_kernel<DH>;
   static bool configured = false;
@@ -288,7 +325,7 @@ forge_status launch_dh(const AttnArgs& a, hipStream_t s) {
       return FORGE_ERR_HIP;
     configured = true;
   }
-  dim3 grid(p.n_qblocks, a.q_heads, a.batch), block(256);
+  dim3 grid(a.q_heads * a.batch, p.n_qblocks), block(512);
   kern<<<grid, block, smem, s>>>(p);
   return launch_status();
 }
