@@ -212,23 +212,22 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
     }
     const float mc = m_run * c;
     float psum = 0.f;
+    // first 32 keys of the tile now; the exponentials of the other 32 fill the shadow of the first
+    // half of the P.V MFMAs (in-order issue: only vector work placed between them can overlap them)
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float pv = __builtin_amdgcn_exp2f(s_acc[kb][v] * c - mc);
-        s_acc[kb][v] = pv;
-        psum += pv;
-      }
-    l_run += psum;
-
+    for (int v = 0; v < 16; ++v) {
+      const float pv = __builtin_amdgcn_exp2f(s_acc[0][v] * c - mc);
+      s_acc[0][v] = pv;
+      psum += pv;
+    }
     bf16x8 pf[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
+    for (int s = 0; s < 2; ++s)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pf[s][e] = (bf16)s_acc[s >> 1][8 * (s & 1) + e];
+      for (int e = 0; e < 8; ++e) pf[s][e] = (bf16)s_acc[0][8 * s + e];
     // V^T fragments (two transposing reads each) run LA MFMAs ahead of their use
     constexpr int NF = 4 * NDT, LA = 4;
+    constexpr int EPI = 16 / (NF / 2);          // exponentials per MFMA of the first half
     typedef short v8i16 __attribute__((ext_vector_type(8)));
     v4i16 lo[LA], hi[LA];
     auto vread = [&](int i, v4i16& l, v4i16& hh) {
@@ -246,8 +245,24 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
       v8i16 both = {l[0], l[1], l[2], l[3], hh[0], hh[1], hh[2], hh[3]};
       o_acc[i % NDT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[i / NDT], o_acc[i % NDT], 0, 0, 0);
       if (i + LA < NF) vread(i + LA, lo[i % LA], hi[i % LA]);
+      if (i < NF / 2) {
+#pragma unroll
+        for (int e = 0; e < EPI; ++e) {
+          const int v = i * EPI + e;
+          const float pv = __builtin_amdgcn_exp2f(s_acc[1][v] * c - mc);
+          s_acc[1][v] = pv;
+          psum += pv;
+        }
+      }
+      if (i == NF / 2 - 1) {
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) pf[2 + s2][e] = (bf16)s_acc[1][8 * s2 + e];
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
+    l_run += psum;
   };
   auto wave_needs = [&](int t) { return t < n_tiles && t * BKV <= wave_max_limit; };   // wave-uniform
 
