@@ -853,19 +853,25 @@ __global__ __launch_bounds__(256) void splitk_reduce_qkv_rope_kernel(GemmParams 
 }
 
 // Split-K second stage of a projection with residual, followed by the normalisation of the
-// finished rows: one block per row; h = sum + bias + residual stays in fp32 registers, is stored
-// rounded to y, and y_norm = Norm(h) is computed from the fp32 values (mean, then centred
-// variance, as residual_norm_kernel does).  N <= 256 * 4 * NORM_TAIL_MAX_G columns.
-constexpr int NORM_TAIL_MAX_G = 16;
-__device__ inline float block_sum_256(float v, float* red) {
+// finished rows: one 1024-thread block per row (the partials of a row are 10^5 bytes that sit in
+// L2; many loads in flight per CU are what makes a single CU per row fast enough); h = sum + bias
+// + residual stays in fp32 registers, is stored rounded to y, and y_norm = Norm(h) is computed
+// from the fp32 values (mean, then centred variance, as residual_norm_kernel does).
+// N <= 1024 * 4 * NORM_TAIL_MAX_G columns.
+constexpr int NORM_TAIL_MAX_G = 4;
+constexpr int NORM_TAIL_THREADS = 1024;
+__device__ inline float block_sum_1024(float v, float* red) {
   v = wave_sum(v);
   __syncthreads();                      // red may still be read from the previous call
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   __syncthreads();
-  return red[0] + red[1] + red[2] + red[3];
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < NORM_TAIL_THREADS / 64; ++i) t += red[i];
+  return t;
 }
-__global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(GemmParams p, int splits) {
-  __shared__ float red[4];
+__global__ __launch_bounds__(NORM_TAIL_THREADS) void splitk_reduce_norm_kernel(GemmParams p, int splits) {
+  __shared__ float red[NORM_TAIL_THREADS / 64];
   const int N = p.N, m = blockIdx.x;
   const int64_t plane = (int64_t)p.M * N;
   const float* src = p.part + (int64_t)m * N;
@@ -873,11 +879,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(GemmParams p, i
   float sum = 0.f;
 #pragma unroll
   for (int g = 0; g < NORM_TAIL_MAX_G; ++g) {
-    const int n = (g * 256 + threadIdx.x) * 4;
+    const int n = (g * NORM_TAIL_THREADS + threadIdx.x) * 4;
     h[g] = floatx4{0.f, 0.f, 0.f, 0.f};
     if (n >= N) continue;                 // N % 4 == 0 (host)
     floatx4 a = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
+#pragma unroll 8
     for (int z = 0; z < splits; ++z) a += *reinterpret_cast<const floatx4*>(src + z * plane + n);
     const int64_t at = (int64_t)m * p.ldy + n;
 #pragma unroll
@@ -892,22 +898,22 @@ __global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(GemmParams p, i
     h[g] = a;
   }
   const bool rms = p.nt.kind == FORGE_NORM_RMSNORM;
-  const float mean = rms ? 0.f : block_sum_256(sum, red) / (float)N;
+  const float mean = rms ? 0.f : block_sum_1024(sum, red) / (float)N;
   float sq = 0.f;
 #pragma unroll
   for (int g = 0; g < NORM_TAIL_MAX_G; ++g) {
-    const int n = (g * 256 + threadIdx.x) * 4;
+    const int n = (g * NORM_TAIL_THREADS + threadIdx.x) * 4;
     if (n >= N) continue;
 #pragma unroll
     for (int e = 0; e < 4; ++e) { const float d = h[g][e] - mean; sq += d * d; }
   }
-  const float rstd = rsqrtf(block_sum_256(sq, red) / (float)N + p.nt.eps);
+  const float rstd = rsqrtf(block_sum_1024(sq, red) / (float)N + p.nt.eps);
   const bf16* gamma = (const bf16*)p.nt.gamma;
   const bf16* beta = (const bf16*)p.nt.beta;
   bf16* yn = (bf16*)p.nt.y_norm + (int64_t)m * N;
 #pragma unroll
   for (int g = 0; g < NORM_TAIL_MAX_G; ++g) {
-    const int n = (g * 256 + threadIdx.x) * 4;
+    const int n = (g * NORM_TAIL_THREADS + threadIdx.x) * 4;
     if (n >= N) continue;
     float o[4];
 #pragma unroll
@@ -1053,7 +1059,7 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
     return launch_status();
   }
   if (MODE == MODE_PLAIN && ACT == FORGE_ACT_NONE && p.nt.y_norm != nullptr) {
-    splitk_reduce_norm_kernel<<<p.M, 256, 0, s>>>(p, sk.splits);
+    splitk_reduce_norm_kernel<<<p.M, NORM_TAIL_THREADS, 0, s>>>(p, sk.splits);
     return launch_status();
   }
   const int64_t threads = (int64_t)p.M * ceil_div(p.N, 4);
@@ -1070,7 +1076,7 @@ size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act) {
 }
 
 bool gemm_fuses_tail(int M, int N, forge_dtype dt) {
-  return dt == FORGE_BF16 && M <= 64 && N % 4 == 0 && N <= 256 * 4 * NORM_TAIL_MAX_G;
+  return dt == FORGE_BF16 && M <= 64 && N % 4 == 0 && N <= NORM_TAIL_THREADS * 4 * NORM_TAIL_MAX_G;
 }
 
 const char* gemm_bf16_variant(int M, int N, int K, int ldy, forge_act act) {
