@@ -291,6 +291,21 @@ def main():
     value = tokens / (ms_per_step * 1e-3)
     gemm_fl, attn_fl = step_flops(wl)
 
+    # ---- per-step latency distribution (outside the timed region): HIP events around single steps
+    latency = None
+    if not args.traffic_probe:
+        evs = []
+        for _ in range(50):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            step()
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        ds = sorted(a.elapsed_time(b) for a, b in evs)
+        latency = {"steps": len(ds), "mean": round(sum(ds) / len(ds), 4), "p50": round(ds[len(ds) // 2], 4),
+                   "p90": round(ds[int(len(ds) * 0.9)], 4), "p99": round(ds[min(len(ds) - 1, int(len(ds) * 0.99))], 4)}
+
     # ---- roofline of the dominant kernel: HIP events on the launch stream around every launch
     # of each plain GEMM of one step (same shapes, same weights), repeated; the group with the
     # largest total time is reported.
@@ -330,6 +345,34 @@ def main():
         del x, y, res
     if args.traffic_probe:
         return
+    # ---- the fused attention call of one layer, at the workload's shape, timed the same way -------
+    attn = None
+    if wl.bf16:
+        kvl = wl.pos0 + wl.seq
+        q = torch.randn(wl.batch, sh.q_heads, wl.seq, sh.head_dim, device="cuda", dtype=torch.float32).to(dt)
+        kc0, vc0 = m["kc"][0], m["vc"][0]
+        o = torch.empty(wl.batch, wl.seq, sh.q_heads * sh.head_dim, device="cuda", dtype=dt)
+        aws = F.workspace(F.forge_attn_fused_workspace_bytes(wl.batch, sh.q_heads, sh.kv_heads, wl.seq, kvl,
+                                                             sh.head_dim, dt))
+        evs = []
+        for _ in range(3 + reps * 4):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            F.forge_attn_fused(q, kc0, vc0, o, kv_len=kvl, workspace=aws)
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        ad = [a.elapsed_time(b) * 1e-3 for a, b in evs[3:]]
+        at = sum(ad) / len(ad)
+        if wl.seq == 1:
+            kvb = 2.0 * wl.batch * sh.kv_heads * kvl * sh.head_dim * 2
+            attn = {"kernel": "attn_decode (split-KV) + combine", "avg_us": round(at * 1e6, 2),
+                    "hbm_gbs": round(kvb / at / 1e9, 1), "frac_of_hbm_peak": round(kvb / at / 1e9 / PEAK_HBM_GBS, 4)}
+        else:
+            attn = {"kernel": "attn_prefill<%d>" % sh.head_dim, "avg_us": round(at * 1e6, 2),
+                    "tflops": round(attn_fl / wl.layers / at / 1e12, 1),
+                    "frac_of_bf16_peak": round(attn_fl / wl.layers / at / 1e12 / PEAK_BF16_TFLOPS, 4)}
+        del q, o
     dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["time"])
     avg_dur = dom["time"] / dom["launches"]
     flops_per_launch = dom["flops"] / dom["launches"]
@@ -364,6 +407,8 @@ def main():
                    "kv_pos0": wl.pos0, "d_model": sh.d_model, "parallelism": "single-gpu"},
         "step_tflops": round((gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12, 1),
         "step_frac_of_bf16_peak": round((gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "latency_ms": latency,
+        "attention": attn,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

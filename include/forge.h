@@ -54,7 +54,9 @@ typedef enum {
   FORGE_ACT_GELU_TANH = 1,     /* 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))         */
   FORGE_ACT_RELU = 2,
   FORGE_ACT_SILU = 3,          /* x / (1 + exp(-x))                                       */
-  FORGE_ACT_SWIGLU = 4         /* silu(gate) * up, gate and up from one [2N,K] weight     */
+  FORGE_ACT_SWIGLU = 4,        /* silu(gate) * up, gate and up from one [2N,K] weight     */
+  FORGE_ACT_GELU_ERF = 5       /* 0.5 x (1 + erf(x / sqrt 2)): the exact form; the paper says
+                                  "GELU" only, the tanh form is the reading taken for it    */
 } forge_act;
 
 typedef enum { FORGE_NORM_LAYERNORM = 0, FORGE_NORM_RMSNORM = 1 } forge_norm;
@@ -153,7 +155,8 @@ forge_status forge_embed(const int32_t* ids, const void* wte, const void* wpe, v
  *   k,v -> cache rows pos0..pos0+q_len-1;  o = attention(q, cache[0..pos0+q_len));
  *   h = x + o.Wo^T + b_o;  m = Norm2(h);  u = act(m.Wup^T + b_up);  x_out = h + u.Wdown^T + b_down
  * w_qkv rows: Hq*dh query rows, then Hkv*dh key rows, then Hkv*dh value rows.
- * mlp_act: FORGE_ACT_GELU_TANH (w_up [d_ff,d]) or FORGE_ACT_SWIGLU (w_up [2*d_ff,d]).
+ * mlp_act: FORGE_ACT_GELU_TANH / GELU_ERF / RELU / SILU (w_up [d_ff,d]) or FORGE_ACT_SWIGLU
+ * (w_up [2*d_ff,d]).
  * Biases and norm shifts may be NULL.  All pointers in the descriptor are device pointers.
  * With at most 64 rows (a decode step) the projections take a split-K path whose reduce step
  * also carries RoPE (QKV projection) and Norm2 (output projection): same results up to rounding

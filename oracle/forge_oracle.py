@@ -41,7 +41,7 @@ import math
 import numpy as np
 
 __all__ = [
-    "layer_norm", "rms_norm", "residual_norm", "linear", "gelu_tanh", "silu", "relu",
+    "layer_norm", "rms_norm", "residual_norm", "linear", "gelu_tanh", "gelu_erf", "silu", "relu",
     "gemm_bias_act", "rope", "attention_probs", "attention", "embed", "lm_head",
     "decoder_block", "gpt_forward",
 ]
@@ -119,6 +119,14 @@ def gelu_tanh(x):
     return 0.5 * x * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (x + 0.044715 * x ** 3)))
 
 
+def gelu_erf(x):
+    """0.5 x (1 + erf(x / sqrt 2)): the exact form (the tanh form is the reading taken for the
+    paper's "GELU"; this one is offered as the other fusion variant)."""
+    from scipy.special import erf
+    x = _f64(x)
+    return 0.5 * x * (1.0 + erf(x / math.sqrt(2.0)))
+
+
 def silu(x):
     """x / (1 + exp(-x))."""
     x = _f64(x)
@@ -132,7 +140,7 @@ def relu(x):
 def gemm_bias_act(x, w, bias=None, residual=None, act="none"):
     """act(x w^T + bias) (+ residual): matmul, then bias, then activation, then the add.
 
-    act: "none" | "gelu_tanh" | "relu" | "silu" | "swiglu".
+    act: "none" | "gelu_tanh" | "gelu_erf" | "relu" | "silu" | "swiglu".
     "swiglu": w is [2F, K], rows 0..F-1 are the gate projection and rows F..2F-1
     the up projection; the result is silu(gate) * up, shape [..., F].
     """
@@ -141,6 +149,8 @@ def gemm_bias_act(x, w, bias=None, residual=None, act="none"):
         y = z
     elif act == "gelu_tanh":
         y = gelu_tanh(z)
+    elif act == "gelu_erf":
+        y = gelu_erf(z)
     elif act == "relu":
         y = relu(z)
     elif act == "silu":

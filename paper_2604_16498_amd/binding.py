@@ -18,7 +18,7 @@ import torch
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libforge.so")
 
 FORGE_F32, FORGE_BF16 = 0, 1
-ACT = {"none": 0, "gelu_tanh": 1, "relu": 2, "silu": 3, "swiglu": 4}
+ACT = {"none": 0, "gelu_tanh": 1, "relu": 2, "silu": 3, "swiglu": 4, "gelu_erf": 5}
 NORM = {"layernorm": 0, "rmsnorm": 1}
 
 

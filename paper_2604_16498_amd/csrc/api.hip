@@ -51,7 +51,7 @@ forge_status check_block_desc(const forge_block_desc* d) {
   if (d->head_dim != 64 && d->head_dim != 128) return FORGE_ERR_UNSUPPORTED;
   if (d->d_model % 8 != 0 || d->d_ff % 8 != 0 || d->d_model > 16384) return FORGE_ERR_UNSUPPORTED;
   if (d->mlp_act != FORGE_ACT_GELU_TANH && d->mlp_act != FORGE_ACT_SWIGLU &&
-      d->mlp_act != FORGE_ACT_RELU && d->mlp_act != FORGE_ACT_SILU)
+      d->mlp_act != FORGE_ACT_RELU && d->mlp_act != FORGE_ACT_SILU && d->mlp_act != FORGE_ACT_GELU_ERF)
     return FORGE_ERR_UNSUPPORTED;
   if (d->norm != FORGE_NORM_LAYERNORM && d->norm != FORGE_NORM_RMSNORM) return FORGE_ERR_INVALID_ARG;
   if (!req(d->norm1_g) || !req(d->w_qkv) || !req(d->w_o) || !req(d->norm2_g) || !req(d->w_up) ||
@@ -236,7 +236,7 @@ forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias
   if (!dtype_ok(dt) || !req(x) || !req(w) || !req(y) || !opt(bias) || !opt(residual) || !opt(workspace))
     return FORGE_ERR_INVALID_ARG;
   if (M < 1 || N < 1 || K < 1 || ldy < 0 || (ldy > 0 && ldy < N)) return FORGE_ERR_INVALID_ARG;
-  if (act < FORGE_ACT_NONE || act > FORGE_ACT_SWIGLU) return FORGE_ERR_INVALID_ARG;
+  if (act < FORGE_ACT_NONE || act > FORGE_ACT_GELU_ERF) return FORGE_ERR_INVALID_ARG;
   if (K % (dt == FORGE_BF16 ? 8 : 4) != 0) return FORGE_ERR_UNSUPPORTED;
   if (y == x || y == w) return FORGE_ERR_INVALID_ARG;
   const size_t need = gemm_ws(M, N, K, act, dt);

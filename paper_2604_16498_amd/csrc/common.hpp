@@ -101,11 +101,13 @@ __device__ inline float gelu_tanh_f(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
 }
 __device__ inline float silu_f(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+__device__ inline float gelu_erf_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.7071067811865476f)); }
 
 template <int ACT> __device__ inline float apply_act(float x) {
   if (ACT == FORGE_ACT_GELU_TANH) return gelu_tanh_f(x);
   if (ACT == FORGE_ACT_RELU) return fmaxf(x, 0.0f);
   if (ACT == FORGE_ACT_SILU) return silu_f(x);
+  if (ACT == FORGE_ACT_GELU_ERF) return gelu_erf_f(x);
   return x;
 }
 

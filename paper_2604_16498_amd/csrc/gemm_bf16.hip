@@ -1122,6 +1122,7 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
     case FORGE_ACT_RELU: return launch_act<FORGE_ACT_RELU, MODE_PLAIN>(p, s);
     case FORGE_ACT_SILU: return launch_act<FORGE_ACT_SILU, MODE_PLAIN>(p, s);
     case FORGE_ACT_SWIGLU: return launch_act<FORGE_ACT_SWIGLU, MODE_PLAIN>(p, s);
+    case FORGE_ACT_GELU_ERF: return launch_act<FORGE_ACT_GELU_ERF, MODE_PLAIN>(p, s);
     default: return FORGE_ERR_INVALID_ARG;
   }
 }

@@ -138,6 +138,7 @@ forge_status launch_gemm_f32(const GemmArgs& a, hipStream_t s) {
     FORGE_CASE(FORGE_ACT_RELU);
     FORGE_CASE(FORGE_ACT_SILU);
     FORGE_CASE(FORGE_ACT_SWIGLU);
+    FORGE_CASE(FORGE_ACT_GELU_ERF);
 #undef FORGE_CASE
     default: return FORGE_ERR_INVALID_ARG;
   }

@@ -55,8 +55,12 @@ SMALL_LLAMA128 = I.BlockShape(512, 4, 1, 128, 1408, norm="rmsnorm", mlp_act="swi
                               rope_base=500000.0, has_bias=False)
 
 
+SMALL_GPT_ERF = I.BlockShape(256, 4, 4, 64, 1024, mlp_act="gelu_erf")
+
+
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
-@pytest.mark.parametrize("sh", [SMALL_GPT, SMALL_LLAMA, SMALL_LLAMA128], ids=["gpt", "llama64", "llama128"])
+@pytest.mark.parametrize("sh", [SMALL_GPT, SMALL_LLAMA, SMALL_LLAMA128, SMALL_GPT_ERF],
+                         ids=["gpt", "llama64", "llama128", "gpt-erf-gelu"])
 def test_block_prefill_then_decode(F, sh, bf16):
     B, S, cap = 2, 150, 160
     w = I.block_weights(sh, 70, 0, bf16=bf16, bias_std=0.05, random_affine=True, weight_std=0.04)

@@ -54,7 +54,7 @@ GEMM_SHAPES = [(128, 2304, 768), (100, 200, 72), (1, 8, 8), (300, 515, 264), (25
 
 
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
-@pytest.mark.parametrize("act", ["none", "gelu_tanh", "relu", "silu", "swiglu"])
+@pytest.mark.parametrize("act", ["none", "gelu_tanh", "gelu_erf", "relu", "silu", "swiglu"])
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
 def test_gemm_bias_act(F, bf16, act, M, N, K):
     wn = 2 * N if act == "swiglu" else N

@@ -248,6 +248,13 @@ def test_gelu_and_silu_closed_forms():
     for xv in (-2.5, -0.3, 0.7, 1.0, 3.1):
         u = math.sqrt(2 / math.pi) * (xv + 0.044715 * xv ** 3)
         assert abs(O.gelu_tanh(np.array([xv]))[0] - xv / (1 + math.exp(-2 * u))) < 1e-14
+    # the exact (erf) form: library routine, scalar evaluation, odd part, and Phi as a distribution
+    ge = O.gelu_erf(x)
+    assert np.abs(ge - erf).max() < 1e-14
+    assert np.allclose(ge - O.gelu_erf(-x), x, atol=1e-14)
+    for xv in (-2.5, -0.3, 0.7, 1.0, 3.1):
+        assert abs(O.gelu_erf(np.array([xv]))[0] - 0.5 * xv * (1 + math.erf(xv / math.sqrt(2)))) < 1e-15
+    assert abs(O.gelu_erf(np.array([1.0]))[0] - 0.8413447460685429) < 1e-15   # Phi(1)
     s = O.silu(x)
     assert np.allclose(s - O.silu(-x), x, atol=1e-14)
     assert np.abs(s - F.silu(torch.from_numpy(x)).numpy()).max() < 1e-14
@@ -278,7 +285,7 @@ def test_linear_brute_force_and_identity():
     assert np.abs(z - ref).max() < 1e-13
 
 
-@pytest.mark.parametrize("act", ["none", "gelu_tanh", "relu", "silu", "swiglu"])
+@pytest.mark.parametrize("act", ["none", "gelu_tanh", "gelu_erf", "relu", "silu", "swiglu"])
 def test_gemm_bias_act_order(act):
     M, K, N = 4, 6, 8
     x, w, b = rnd(M, K), rnd(N, K), rnd(N)
@@ -300,6 +307,8 @@ def test_gemm_bias_act_order(act):
             elif act == "gelu_tanh":
                 t = z[m][n]
                 e = 0.5 * t * (1 + math.tanh(math.sqrt(2 / math.pi) * (t + 0.044715 * t ** 3)))
+            elif act == "gelu_erf":
+                e = 0.5 * z[m][n] * (1 + math.erf(z[m][n] / math.sqrt(2)))
             else:
                 gate, up = z[m][n], z[m][n + nout]      # gate rows first, up rows after
                 e = gate * sig(gate) * up
