@@ -105,11 +105,15 @@ forge_status forge_attn_fused(const void* q, const void* k, const void* v, void*
  * 8 elements keeps every output row 16-byte aligned, which the fast store path needs; a
  * vocabulary-sized N such as 50257 is best given a padded stride (50264).
  * Requirements: M,N,K >= 1; K % 8 == 0 for bf16, K % 4 == 0 for fp32; ldy == 0 or ldy >= N.
+ * Workspace: problems that are split along K (bf16 with M <= 64; fp32 with fewer output tiles
+ * than CUs) need forge_gemm_workspace_bytes() bytes of device memory for the fp32 partial sums
+ * (0 otherwise; FORGE_ERR_WORKSPACE if too little is given); the partial sums are added in a
+ * fixed order, so results stay bitwise reproducible.
  * ------------------------------------------------------------------------------------ */
 size_t forge_gemm_workspace_bytes(int M, int N, int K, forge_act act, forge_dtype dt);
 
 /* Diagnostic: the name of the kernel variant (tile shape and wave layout) that
- * forge_gemm_bias_gelu launches for this problem, e.g. "gemm_bf16<256,256,2,4>"; static
+ * forge_gemm_bias_gelu launches for this problem, e.g. "gemm_bf16_pers<256,256,2,4>"; static
  * storage, never NULL.  Lets a profiler trace be matched to the calls that produced it. */
 const char* forge_gemm_variant(int M, int N, int K, int ldy, forge_act act, forge_dtype dt);
 

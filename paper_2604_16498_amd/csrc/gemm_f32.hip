@@ -9,6 +9,11 @@
 // disjoint banks.  The MFMA contracts two k per issue (lanes 0-31 supply one, lanes 32-63 the
 // other); lanes 0-31 walk k = 0..15 of the slab and lanes 32-63 walk k = 16..31, so every
 // lane reads four consecutive floats per 128-bit LDS read.
+//
+// Small problems (fewer tiles than CUs -- the 128-token fp32 layer has 24 to 96 of them, and a
+// block walks K slab by slab with a barrier each) are split along K over grid.z: raw fp32
+// partial sums go to the workspace and a second kernel adds them in split order (fixed order, no
+// atomics: bitwise reproducible) and carries the epilogue.
 #include "common.hpp"
 
 namespace forge {
@@ -34,7 +39,8 @@ __device__ inline void* split_dst(const QkvSplit& sp, int m, int n, size_t esz) 
 template <int ACT, bool SPLIT>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(
     const float* __restrict__ x, const float* __restrict__ w, const float* __restrict__ bias,
-    const float* residual, float* y, int M, int N, int K, int ldy, QkvSplit sp) {
+    const float* residual, float* y, int M, int N, int K, int ldy, QkvSplit sp,
+    int k_per_split, float* part) {
   constexpr bool SWIGLU = ACT == FORGE_ACT_SWIGLU;
   constexpr int NB = SWIGLU ? 2 : 1;
   __shared__ __attribute__((aligned(16))) float As[BM][LDK];
@@ -53,7 +59,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
   const int lrow = tid >> 3;        // 0..31
   const int lcol = (tid & 7) * 4;   // 0,4,..,28
 
-  for (int k0 = 0; k0 < K; k0 += BK) {
+  const int k_begin = blockIdx.z * k_per_split;           // multiple of BK
+  const int k_end = min(K, k_begin + k_per_split);
+  for (int k0 = k_begin; k0 < k_end; k0 += BK) {
     // global -> LDS (zero fill outside the matrix)
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
@@ -87,9 +95,20 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
     __syncthreads();
   }
 
-  // epilogue on the accumulator: + bias, activation, + residual, store
   const int n = n0 + wn * 32 + (lane & 31);
   if (n >= N) return;
+  if (part != nullptr) {       // split-K: raw partial sums [split, M, NB * N]; the reduce kernel does the rest
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int m = m0 + wm * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      if (m >= M) continue;
+      float* dst = part + ((int64_t)blockIdx.z * M + m) * (NB * N) + n;
+      dst[0] = acc[0][v];
+      if (SWIGLU) dst[N] = acc[NB - 1][v];
+    }
+    return;
+  }
+  // epilogue on the accumulator: + bias, activation, + residual, store
   float bv = 0.f, bv2 = 0.f;
   if (bias != nullptr) {
     bv = bias[n];
@@ -111,12 +130,63 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
   }
 }
 
+// Second stage of the split: one thread per output element.
+template <int ACT, bool SPLIT>
+__global__ __launch_bounds__(256) void gemm_f32_reduce_kernel(
+    const float* __restrict__ part, const float* __restrict__ bias, const float* residual, float* y,
+    int M, int N, int ldy, int splits, QkvSplit sp) {
+  constexpr bool SWIGLU = ACT == FORGE_ACT_SWIGLU;
+  const int ncols = SWIGLU ? 2 * N : N;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (int64_t)M * N) return;
+  const int m = (int)(gid / N), n = (int)(gid % N);
+  const int64_t plane = (int64_t)M * ncols;
+  const float* src = part + (int64_t)m * ncols + n;
+  float a = 0.f, u = 0.f;
+  for (int z = 0; z < splits; ++z) {
+    a += src[z * plane];
+    if (SWIGLU) u += src[z * plane + N];
+  }
+  if (bias != nullptr) {
+    a += bias[n];
+    if (SWIGLU) u += bias[n + N];
+  }
+  float val = SWIGLU ? silu_f(a) * u : apply_act<ACT>(a);
+  if (SPLIT) {
+    *reinterpret_cast<float*>(split_dst(sp, m, n, sizeof(float))) = val;
+  } else {
+    if (residual != nullptr) val += residual[(int64_t)m * ldy + n];
+    y[(int64_t)m * ldy + n] = val;
+  }
+}
+
+// k ranges for a problem: none while the tiles fill the chip; otherwise towards two blocks per
+// CU, each with at least four slabs.
+struct SplitPlan { int splits, k_per_split; };
+SplitPlan plan_split(int M, int N, int K) {
+  const int tiles = ceil_div(M, BM) * ceil_div(N, BN);
+  const int slabs = ceil_div(K, BK);
+  int want = tiles >= 256 ? 1 : min(ceil_div(512, tiles), slabs / 4);
+  want = max(1, want);
+  const int per = ceil_div(slabs, want);
+  return SplitPlan{ceil_div(slabs, per), per * BK};
+}
+
 }  // namespace
 
-size_t gemm_f32_workspace_bytes(int, int, int, forge_act) { return 0; }
+size_t gemm_f32_workspace_bytes(int M, int N, int K, forge_act act) {
+  const SplitPlan sp = plan_split(M, N, K);
+  if (sp.splits == 1) return 0;
+  return (size_t)sp.splits * M * (act == FORGE_ACT_SWIGLU ? 2 * N : N) * sizeof(float);
+}
 
 forge_status launch_gemm_f32(const GemmArgs& a, hipStream_t s) {
-  dim3 grid(ceil_div(a.N, BN), ceil_div(a.M, BM)), block(256);
+  const SplitPlan pl = plan_split(a.M, a.N, a.K);
+  const size_t need = gemm_f32_workspace_bytes(a.M, a.N, a.K, a.act);
+  if (need > a.workspace_bytes || (need > 0 && a.workspace == nullptr)) return FORGE_ERR_WORKSPACE;
+  float* part = pl.splits > 1 ? (float*)a.workspace : nullptr;
+  dim3 grid(ceil_div(a.N, BN), ceil_div(a.M, BM), pl.splits), block(256);
+  const unsigned rblocks = (unsigned)ceil_div64((int64_t)a.M * a.N, 256);
   const float* x = (const float*)a.x;
   const float* w = (const float*)a.w;
   const float* bias = (const float*)a.bias;
@@ -127,12 +197,20 @@ forge_status launch_gemm_f32(const GemmArgs& a, hipStream_t s) {
   if (a.split != nullptr) {
     if (a.act != FORGE_ACT_NONE || a.residual != nullptr) return FORGE_ERR_UNSUPPORTED;
     sp = *a.split;
-    gemm_f32_kernel<FORGE_ACT_NONE, true><<<grid, block, 0, s>>>(x, w, bias, res, y, a.M, a.N, a.K, ldy, sp);
+    gemm_f32_kernel<FORGE_ACT_NONE, true><<<grid, block, 0, s>>>(x, w, bias, res, y, a.M, a.N, a.K, ldy, sp,
+                                                                 pl.k_per_split, part);
+    if (part != nullptr)
+      gemm_f32_reduce_kernel<FORGE_ACT_NONE, true><<<rblocks, 256, 0, s>>>(part, bias, res, y, a.M, a.N, ldy, pl.splits, sp);
     return launch_status();
   }
   switch (a.act) {
-#define FORGE_CASE(ACT) \
-  case ACT: gemm_f32_kernel<ACT, false><<<grid, block, 0, s>>>(x, w, bias, res, y, a.M, a.N, a.K, ldy, sp); break
+#define FORGE_CASE(ACT)                                                                                        \
+  case ACT:                                                                                                    \
+    gemm_f32_kernel<ACT, false><<<grid, block, 0, s>>>(x, w, bias, res, y, a.M, a.N, a.K, ldy, sp,             \
+                                                       pl.k_per_split, part);                                  \
+    if (part != nullptr)                                                                                       \
+      gemm_f32_reduce_kernel<ACT, false><<<rblocks, 256, 0, s>>>(part, bias, res, y, a.M, a.N, ldy, pl.splits, sp); \
+    break
     FORGE_CASE(FORGE_ACT_NONE);
     FORGE_CASE(FORGE_ACT_GELU_TANH);
     FORGE_CASE(FORGE_ACT_RELU);
