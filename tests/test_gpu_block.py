@@ -178,3 +178,44 @@ def test_model_forward_hidden_llama(F):
     mx, l2 = rel_err(host(out), ref)
     print("llama hidden: max rel %.3e l2 %.3e" % (mx, l2))
     assert l2 < 2e-2 and mx < 6e-2
+
+
+@pytest.mark.parametrize("decode", [False, True], ids=["prefill", "decode"])
+def test_block_under_hip_graph_capture(F, decode):
+    """The launch list allocates nothing and never synchronises (Sec. "Code Generation:
+    CompiledNPUExecutor": pre-resolved callables, no run-time allocation, fixed order), so a caller
+    can capture it into a HIP graph.  Every replay, with eager work and synchronisations in
+    between, must reproduce the eager result bit for bit."""
+    sh = SMALL_LLAMA
+    B, S, cap = (4, 1, 96) if decode else (2, 80, 96)
+    pos0 = 64 if decode else 0
+    w = I.block_weights(sh, 76, 0, bf16=True, weight_std=0.05)
+    tw = dev_dict(w, True)
+    desc = F.make_block_desc(sh, tw)
+    x = dev(I.normal(76, 0, "x", (B, S, sh.d_model), 1.0, bf16=True), True)
+    kc0 = dev(I.normal(76, 0, "k_cache", (B, sh.kv_heads, cap, sh.head_dim), 1.0, bf16=True), True)
+    vc0 = dev(I.normal(76, 0, "v_cache", (B, sh.kv_heads, cap, sh.head_dim), 1.0, bf16=True), True)
+    ws = F.workspace(F.forge_decoder_block_workspace_bytes(desc, B, S, cap))
+
+    def fresh():
+        return kc0.clone(), vc0.clone(), torch.empty_like(x)
+
+    kc, vc, out = fresh()
+    F.forge_decoder_block(desc, x, out, kc, vc, pos0, ws)       # eager (also the one-time kernel set-up)
+    torch.cuda.synchronize()
+    ref_out, ref_k = out.clone(), kc.clone()
+
+    kc, vc, out = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            F.forge_decoder_block(desc, x, out, kc, vc, pos0, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        kc.copy_(kc0); vc.copy_(vc0); out.fill_(0)          # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref_out) and torch.equal(kc, ref_k)
