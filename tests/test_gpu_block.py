@@ -180,6 +180,40 @@ def test_model_forward_hidden_llama(F):
     assert l2 < 2e-2 and mx < 6e-2
 
 
+def test_model_generation_loop(F):
+    """Prefill of 24 tokens, then 8 single-token steps on the growing KV cache (teacher-forced
+    ids): the logits of step i equal row 24 + i of one causal forward over all 32 tokens, which
+    is what the oracle computes."""
+    sh = SMALL_GPT
+    L, B, S0, steps, V = 2, 3, 24, 8, 520
+    cap = 64
+    wl = I.scaled(I.WORKLOADS[2], block=sh, layers=L, vocab=V, n_pos=64, batch=B, seq=S0 + steps, bf16=True)
+    mw = I.model_weights(wl, random_affine=True)
+    layers = [I.block_weights(sh, 77, l, bf16=True, random_affine=True) for l in range(L)]
+    ids = I.token_ids(77, B, S0 + steps, V)
+    ref = O.gpt_forward(sh, layers, mw, ids=ids)                     # [B, S0 + steps, V]
+    tl = [dev_dict(w, True) for w in layers]
+    tm = dev_dict(mw, True)
+    model = F.make_model_desc([F.make_block_desc(sh, w) for w in tl], tm)
+    kc = torch.zeros(L, B, sh.kv_heads, cap, sh.head_dim, dtype=torch.bfloat16, device="cuda"); vc = torch.zeros_like(kc)
+    tids = torch.from_numpy(ids).cuda()
+    logits = torch.empty(B, S0, V, dtype=torch.bfloat16, device="cuda")
+    ws = F.workspace(max(F.forge_model_workspace_bytes(model, B, S0, cap), F.forge_model_workspace_bytes(model, B, 1, cap)))
+    F.forge_model_forward(model, tids[:, :S0].contiguous(), logits, kc, vc, 0, ws)
+    torch.cuda.synchronize()
+    mx, l2 = rel_err(host(logits), ref[:, :S0])
+    assert l2 < 2e-2 and mx < 6e-2
+    step_logits = torch.empty(B, 1, V, dtype=torch.bfloat16, device="cuda")
+    worst = 0.0
+    for i in range(steps):
+        F.forge_model_forward(model, tids[:, S0 + i:S0 + i + 1].contiguous(), step_logits, kc, vc, S0 + i, ws)
+        torch.cuda.synchronize()
+        mx, l2 = rel_err(host(step_logits), ref[:, S0 + i:S0 + i + 1])
+        worst = max(worst, l2)
+        assert l2 < 2e-2 and mx < 6e-2, "decode step %d: l2 %.3e max %.3e" % (i, l2, mx)
+    print("generation loop: worst l2 over %d steps %.3e" % (steps, worst))
+
+
 @pytest.mark.parametrize("decode", [False, True], ids=["prefill", "decode"])
 def test_block_under_hip_graph_capture(F, decode):
     """The launch list allocates nothing and never synchronises (Sec. "Code Generation:
