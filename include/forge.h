@@ -91,6 +91,21 @@ forge_status forge_attn_fused(const void* q, const void* k, const void* v, void*
                               float scale, int causal, forge_dtype dt,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same operator with the optional mask node of the paper's attention chain
+ * (Sec. "Pass 4: Attention Fusion": Q.K^T -> scale -> [mask] -> softmax -> [dropout] -> .V):
+ *   P[b,h,i,:] = softmax_j( scale * q.k + mask[b,h,i,j] ),  causal != 0 cuts keys as above too.
+ * mask: fp32 device pointer, 4-byte aligned, rows of kv_len values ([q_len, kv_len] per plane);
+ * mask_batch_stride / mask_head_stride in elements, 0 broadcasts over that axis; values are
+ * finite or -inf (a padded key).  Every query row must keep at least one key with a finite
+ * mask; rows that do not have no defined result.  No workspace; q_len == 1 is allowed.
+ * Same requirements and errors as forge_attn_fused otherwise. */
+forge_status forge_attn_fused_masked(const void* q, const void* k, const void* v, const float* mask,
+                                     void* out, int batch, int q_heads, int kv_heads, int q_len,
+                                     int kv_len, int head_dim, int64_t kv_batch_stride,
+                                     int64_t kv_head_stride, int64_t mask_batch_stride,
+                                     int64_t mask_head_stride, float scale, int causal,
+                                     forge_dtype dt, void* stream);
+
 /* ---------------------------------------------------------------------------------------
  * Fused linear: y = act(x . w^T + bias) (+ residual)   (Sec. "Pass 5: Operator Fusion").
  *

@@ -193,12 +193,14 @@ def rope(x, positions, base):
 # ----------------------------------------------------------------------------
 
 
-def attention_probs(q, k, scale, causal):
+def attention_probs(q, k, scale, causal, mask=None):
     """P[b, h, i, j]: the probability matrix of the unfused chain, written out.
 
     q [B, Hq, Sq, dh]; k [B, Hkv, Skv, dh] un-transposed, as the fused op takes it.
-    S = scale * q k^T;  if causal, S_ij = -inf for j > i + (Skv - Sq);  row softmax
-    with the row maximum subtracted.  Query head h reads kv head h // (Hq / Hkv).
+    S = scale * q k^T;  the optional mask node of the chain (Sec. "Pass 4: Attention Fusion")
+    adds mask[b or 0, h or 0, i, j] (finite or -inf) to S;  if causal, S_ij = -inf for
+    j > i + (Skv - Sq);  row softmax with the row maximum subtracted.  Query head h reads kv head
+    h // (Hq / Hkv).  Every row must keep at least one key.
     """
     q, k = _f64(q), _f64(k)
     B, Hq, Sq, dh = q.shape
@@ -208,6 +210,9 @@ def attention_probs(q, k, scale, causal):
     for b in range(B):
         for h in range(Hq):
             S = (q[b, h] @ k[b, h // group].T) * scale
+            if mask is not None:
+                mk = _f64(mask)
+                S = S + mk[b if mk.shape[0] > 1 else 0, h if mk.shape[1] > 1 else 0]
             if causal:
                 i = np.arange(Sq)[:, None]
                 j = np.arange(Skv)[None, :]
@@ -218,8 +223,9 @@ def attention_probs(q, k, scale, causal):
     return P
 
 
-def attention(q, k, v, scale, causal):
-    """out[B, Sq, Hq*dh] = softmax(mask(scale q k^T)) v, heads concatenated per token."""
+def attention(q, k, v, scale, causal, mask=None):
+    """out[B, Sq, Hq*dh] = softmax(mask(scale q k^T)) v, heads concatenated per token.
+    mask: optional additive [B or 1, Hq or 1, Sq, Skv]."""
     q, v = _f64(q), _f64(v)
     B, Hq, Sq, dh = q.shape
     Hkv = v.shape[1]
@@ -227,7 +233,8 @@ def attention(q, k, v, scale, causal):
     out = np.empty((B, Sq, Hq * dh), dtype=np.float64)
     for b in range(B):
         # one batch element at a time keeps the written-out P at Hq*Sq*Skv doubles
-        P = attention_probs(q[b:b + 1], _f64(k)[b:b + 1], scale, causal)[0]
+        mb = None if mask is None else (mask[b:b + 1] if np.shape(mask)[0] > 1 else mask)
+        P = attention_probs(q[b:b + 1], _f64(k)[b:b + 1], scale, causal, mb)[0]
         for h in range(Hq):
             out[b, :, h * dh:(h + 1) * dh] = P[h] @ v[b, h // group]
     return out

@@ -57,6 +57,8 @@ SIGNATURES = {
     "forge_version": (_i, []),
     "forge_attn_fused_workspace_bytes": (_sz, [_i, _i, _i, _i, _i, _i, _i]),
     "forge_attn_fused": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _i, _vp, _sz, _vp]),
+    "forge_attn_fused_masked": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i64, _i64, _i64, _i64, _f, _i,
+                                     _i, _vp]),
     "forge_gemm_workspace_bytes": (_sz, [_i, _i, _i, _i, _i]),
     "forge_gemm_variant": (C.c_char_p, [_i, _i, _i, _i, _i, _i]),
     "forge_gemm_bias_gelu": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
@@ -144,6 +146,24 @@ def forge_attn_fused(q, k, v, out, kv_len=None, scale=None, causal=True, workspa
     wp, wb = _ws(workspace)
     _check(lib().forge_attn_fused(_p(q), _p(k), _p(v), _p(out), B, Hq, Hkv, Sq, kv_len, dh, bs, hs,
                                   scale, int(causal), _dt(q), wp, wb, _stream()), "forge_attn_fused")
+    return out
+
+
+def forge_attn_fused_masked(q, k, v, mask, out, kv_len=None, scale=None, causal=False):
+    """As forge_attn_fused, with an additive fp32 mask [B or 1, Hq or 1, Sq, kv_len] on the
+    scaled scores (size-1 axes broadcast)."""
+    B, Hq, Sq, dh = q.shape
+    Hkv, cap = k.shape[1], k.shape[2]
+    kv_len = cap if kv_len is None else kv_len
+    scale = dh ** -0.5 if scale is None else scale
+    hs = cap * dh
+    bs = Hkv * hs
+    assert mask.dtype == torch.float32 and mask.is_contiguous() and mask.shape[2:] == (Sq, kv_len)
+    mhs = 0 if mask.shape[1] == 1 else Sq * kv_len
+    mbs = 0 if mask.shape[0] == 1 else mask.shape[1] * Sq * kv_len
+    _check(lib().forge_attn_fused_masked(_p(q), _p(k), _p(v), _p(mask), _p(out), B, Hq, Hkv, Sq, kv_len, dh,
+                                         bs, hs, mbs, mhs, scale, int(causal), _dt(q), _stream()),
+           "forge_attn_fused_masked")
     return out
 
 

@@ -25,7 +25,7 @@ struct Carver {
 
 forge_status attn_dispatch(const AttnArgs& a, forge_dtype dt, hipStream_t s) {
   if (dt == FORGE_F32) return launch_attn_f32(a, s);
-  if (a.q_len == 1) return launch_attn_decode_bf16(a, s);
+  if (a.q_len == 1 && a.mask == nullptr) return launch_attn_decode_bf16(a, s);
   return launch_attn_prefill_bf16(a, s);
 }
 
@@ -127,7 +127,7 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
   }
   // 4. fused causal attention over cache rows [0, pos0 + q_len)
   AttnArgs at = {q, k_cache, v_cache, o, batch, d->q_heads, d->kv_heads, q_len, pos0 + q_len, dh,
-                 kv_bs, kv_hs, 1.0f / sqrtf((float)dh), 1, aws, pl.attn};
+                 kv_bs, kv_hs, 1.0f / sqrtf((float)dh), 1, aws, pl.attn, nullptr, 0, 0};
   st = attn_dispatch(at, d->dt, s);
   if (st != FORGE_OK) return st;
   // 5. output projection + bias + residual
@@ -215,7 +215,34 @@ forge_status forge_attn_fused(const void* q, const void* k, const void* v, void*
   const size_t need = attn_ws(batch, q_heads, kv_heads, q_len, kv_len, head_dim, dt);
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FORGE_ERR_WORKSPACE;
   AttnArgs a = {q, k, v, out, batch, q_heads, kv_heads, q_len, kv_len, head_dim,
-                kv_batch_stride, kv_head_stride, scale, causal, workspace, workspace_bytes};
+                kv_batch_stride, kv_head_stride, scale, causal, workspace, workspace_bytes, nullptr, 0, 0};
+  return attn_dispatch(a, dt, static_cast<hipStream_t>(stream));
+}
+
+forge_status forge_attn_fused_masked(const void* q, const void* k, const void* v, const float* mask,
+                                     void* out, int batch, int q_heads, int kv_heads, int q_len,
+                                     int kv_len, int head_dim, int64_t kv_batch_stride,
+                                     int64_t kv_head_stride, int64_t mask_batch_stride,
+                                     int64_t mask_head_stride, float scale, int causal,
+                                     forge_dtype dt, void* stream) {
+  if (!dtype_ok(dt) || !req(q) || !req(k) || !req(v) || !req(out) || mask == nullptr ||
+      (reinterpret_cast<uintptr_t>(mask) & 3u) != 0)
+    return FORGE_ERR_INVALID_ARG;
+  if (batch < 1 || q_heads < 1 || kv_heads < 1 || q_len < 1 || kv_len < 1) return FORGE_ERR_INVALID_ARG;
+  if (q_heads % kv_heads != 0) return FORGE_ERR_INVALID_ARG;
+  if (causal && kv_len < q_len) return FORGE_ERR_INVALID_ARG;
+  if (head_dim != 64 && head_dim != 128) return FORGE_ERR_UNSUPPORTED;
+  if (kv_head_stride < (int64_t)kv_len * head_dim || kv_batch_stride < kv_head_stride * kv_heads)
+    return FORGE_ERR_INVALID_ARG;
+  if (kv_head_stride % 8 != 0 || kv_batch_stride % 8 != 0) return FORGE_ERR_INVALID_ARG;
+  const int64_t plane = (int64_t)q_len * kv_len;
+  if ((mask_head_stride != 0 && mask_head_stride < plane) ||
+      (mask_batch_stride != 0 && mask_batch_stride < (mask_head_stride != 0 ? mask_head_stride * q_heads : plane)))
+    return FORGE_ERR_INVALID_ARG;
+  if (out == q || out == k || out == v) return FORGE_ERR_INVALID_ARG;
+  AttnArgs a = {q, k, v, out, batch, q_heads, kv_heads, q_len, kv_len, head_dim,
+                kv_batch_stride, kv_head_stride, scale, causal, nullptr, 0,
+                mask, mask_batch_stride, mask_head_stride};
   return attn_dispatch(a, dt, static_cast<hipStream_t>(stream));
 }
 

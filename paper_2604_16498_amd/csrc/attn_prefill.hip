@@ -55,6 +55,8 @@ struct AttnParams {
   float scale_log2e;
   int causal;
   int n_qblocks;
+  const float* mask;        // additive, fp32 [*, *, q_len, kv_len]; only read by the MASKED kernel
+  int64_t mask_bs, mask_hs;
 };
 
 __device__ inline float xchg32_max(float x) {
@@ -67,7 +69,10 @@ __device__ inline float xchg32_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int DH>
+// MASKED: an additive mask (the optional mask node of the paper's attention chain) is added to
+// the scaled scores before the softmax; its values are fetched when the tile's softmax starts
+// (not hidden behind anything: this variant trades speed for generality).
+template <int DH, bool MASKED>
 __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   constexpr int BQ = 256, BKV = 64, NT = 512;
   constexpr int CPR = DH / 8;                 // 16-byte chunks per row
@@ -150,7 +155,12 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) o_acc[i][e] = 0.f;
   float m_run = -1e30f, l_run = 0.f;   // finite start: no inf - inf anywhere
-  const float c = p.scale_log2e;
+  // MASKED works on pre-scaled scores (s * scale * log2e + mask * log2e), so the factor inside
+  // the softmax is 1 there
+  const float c = MASKED ? 1.0f : p.scale_log2e;
+  const float* mask_row = nullptr;
+  if (MASKED)
+    mask_row = p.mask + b * p.mask_bs + h * p.mask_hs + (int64_t)min(my_q, p.q_len - 1) * p.kv_len;
 
   // per-lane byte offset of the transposing V read inside a tile (without key step / d tile)
   const int vt_lane = (((lane & 15) >> 2) + 4 * fh) * VS + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
@@ -185,6 +195,17 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   auto softmax_pv = [&](int t, floatx16 (&s_acc)[2]) {
     const int kv0 = t * BKV;
     const char* sv = vbuf + (t & 1) * V_BYTES;
+    if (MASKED) {
+      constexpr float LOG2E = 1.4426950408889634f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = kv0 + kb * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
+          const float mk = key < p.kv_len ? mask_row[key] : 0.f;      // keys past the end are cut below
+          s_acc[kb][v] = s_acc[kb][v] * p.scale_log2e + mk * LOG2E;
+        }
+    }
     if (kv0 + BKV - 1 > wave_min_limit) {       // diagonal / tail tiles only
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -315,7 +336,7 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   }
 }
 
-template <int DH>
+template <int DH, bool MASKED>
 forge_status launch_dh(const AttnArgs& a, hipStream_t s) {
   AttnParams p;
   p.q = (const bf16*)a.q;
@@ -331,8 +352,11 @@ forge_status launch_dh(const AttnArgs& a, hipStream_t s) {
   p.scale_log2e = a.scale * 1.4426950408889634f;
   p.causal = a.causal;
   p.n_qblocks = ceil_div(a.q_len, 256);
+  p.mask = a.mask;
+  p.mask_bs = a.mask_batch_stride;
+  p.mask_hs = a.mask_head_stride;
   constexpr int smem = 2 * 64 * ((DH * 2 + 16) + (DH * 2 + 64));
-  auto kern = attn_prefill_kernel<DH>;
+  auto kern = attn_prefill_kernel<DH, MASKED>;
   static bool configured = false;
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -348,8 +372,8 @@ forge_status launch_dh(const AttnArgs& a, hipStream_t s) {
 }  // namespace
 
 forge_status launch_attn_prefill_bf16(const AttnArgs& a, hipStream_t s) {
-  if (a.head_dim == 64) return launch_dh<64>(a, s);
-  if (a.head_dim == 128) return launch_dh<128>(a, s);
+  if (a.head_dim == 64) return a.mask ? launch_dh<64, true>(a, s) : launch_dh<64, false>(a, s);
+  if (a.head_dim == 128) return a.mask ? launch_dh<128, true>(a, s) : launch_dh<128, false>(a, s);
   return FORGE_ERR_UNSUPPORTED;
 }
 

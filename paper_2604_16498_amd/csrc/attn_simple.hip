@@ -13,7 +13,8 @@ template <typename T, int DH>
 __global__ __launch_bounds__(256) void attn_simple_kernel(
     const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
     T* __restrict__ out, int batch, int q_heads, int kv_heads, int q_len, int kv_len,
-    int64_t kv_bs, int64_t kv_hs, float scale, int causal) {
+    int64_t kv_bs, int64_t kv_hs, float scale, int causal, const float* __restrict__ mask,
+    int64_t mask_bs, int64_t mask_hs) {
   constexpr int NO = DH / 64;
   __shared__ __attribute__((aligned(16))) float qs[4][DH];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -33,7 +34,8 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(
   __syncthreads();
 
   const int limit = causal ? i + (kv_len - q_len) + 1 : kv_len;   // keys [0, limit)
-  float m = -INFINITY, l = 0.f, acc[NO];
+  const float* mrow = mask == nullptr ? nullptr : mask + b * mask_bs + h * mask_hs + (int64_t)i * kv_len;
+  float m = -1e30f, l = 0.f, acc[NO];      // finite start: a chunk that is masked out entirely stays 0
 #pragma unroll
   for (int t = 0; t < NO; ++t) acc[t] = 0.f;
 
@@ -51,10 +53,11 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(
         for (int u = 0; u < 8; ++u) d += kv[u] * qs[wave][e + u];
       }
       s = d * scale;
+      if (mrow != nullptr) s += mrow[j];
     }
     const float m_new = fmaxf(m, wave_max(s));
     const float p = __expf(s - m_new);        // exp(-inf) = 0 for lanes past the limit
-    const float corr = __expf(m - m_new);     // first chunk: exp(-inf) = 0
+    const float corr = __expf(m - m_new);     // first chunk: exp(-1e30 - m_new) = 0
     l = l * corr + wave_sum(p);
 #pragma unroll
     for (int t = 0; t < NO; ++t) acc[t] *= corr;
@@ -81,11 +84,13 @@ forge_status launch_t(const AttnArgs& a, hipStream_t s) {
   if (a.head_dim == 64)
     attn_simple_kernel<T, 64><<<grid, block, 0, s>>>(
         (const T*)a.q, (const T*)a.k, (const T*)a.v, (T*)a.out, a.batch, a.q_heads, a.kv_heads,
-        a.q_len, a.kv_len, a.kv_batch_stride, a.kv_head_stride, a.scale, a.causal);
+        a.q_len, a.kv_len, a.kv_batch_stride, a.kv_head_stride, a.scale, a.causal, a.mask,
+        a.mask_batch_stride, a.mask_head_stride);
   else if (a.head_dim == 128)
     attn_simple_kernel<T, 128><<<grid, block, 0, s>>>(
         (const T*)a.q, (const T*)a.k, (const T*)a.v, (T*)a.out, a.batch, a.q_heads, a.kv_heads,
-        a.q_len, a.kv_len, a.kv_batch_stride, a.kv_head_stride, a.scale, a.causal);
+        a.q_len, a.kv_len, a.kv_batch_stride, a.kv_head_stride, a.scale, a.causal, a.mask,
+        a.mask_batch_stride, a.mask_head_stride);
   else
     return FORGE_ERR_UNSUPPORTED;
   return launch_status();

@@ -177,6 +177,8 @@ struct AttnArgs {
   int causal;
   void* workspace;
   size_t workspace_bytes;
+  const float* mask;                 // additive fp32 [*, *, q_len, kv_len], NULL: none
+  int64_t mask_batch_stride, mask_head_stride;   // elements; 0 broadcasts
 };
 
 forge_status launch_attn_f32(const AttnArgs& a, hipStream_t s);

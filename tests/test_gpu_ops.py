@@ -135,6 +135,36 @@ def test_gemm_residual_in_place(F):
 
 
 # ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Skv,dh,mb,mh", [
+    (2, 4, 2, 100, 100, 64, True, True),      # mask per batch and head
+    (3, 4, 4, 128, 128, 128, True, False),    # padded sequences: per batch, all heads
+    (1, 8, 2, 300, 333, 128, False, False),   # one plane for everything, odd kv_len
+    (2, 4, 1, 1, 200, 64, True, True),        # single query row
+    (1, 2, 2, 520, 520, 64, False, True),     # several query blocks
+])
+def test_attn_fused_masked(F, bf16, causal, B, Hq, Hkv, Sq, Skv, dh, mb, mh):
+    """Additive mask on the scaled scores: random finite values plus -inf on a padded tail of
+    keys (different per sequence when the mask has a batch axis)."""
+    q = I.normal(66, 0, "q", (B, Hq, Sq, dh), 1.0, bf16=bf16)
+    k = I.normal(66, 0, "k_cache", (B, Hkv, Skv, dh), 1.0, bf16=bf16)
+    v = I.normal(66, 0, "v_cache", (B, Hkv, Skv, dh), 1.0, bf16=bf16)
+    mask = I.normal(66, 0, "misc", (B if mb else 1, Hq if mh else 1, Sq, Skv), 1.5).astype(np.float32)
+    for b in range(mask.shape[0]):
+        pad = (7 * (b + 1)) % max(1, min(Skv - Sq if causal else Skv, 40))     # keep key 0 for every row
+        if pad and not (causal and Skv - pad < Sq):
+            mask[b, :, :, Skv - pad:] = -np.inf
+    scale = 1 / math.sqrt(dh)
+    ref = O.attention(q, k, v, scale, causal, mask)
+    out = torch.empty(B, Sq, Hq * dh, dtype=tdtype(bf16), device="cuda")
+    F.forge_attn_fused_masked(dev(q, bf16), dev(k, bf16), dev(v, bf16), torch.from_numpy(mask).cuda(), out,
+                              scale=scale, causal=causal)
+    torch.cuda.synchronize()
+    check(out, ref, bf16, "masked attention")
+
+
+# ---------------------------------------------------------------------------------------------
 ATTN_SHAPES = [  # B, Hq, Hkv, Sq, Skv, cap, dh
     (1, 12, 12, 128, 128, 128, 64),
     (2, 8, 2, 100, 100, 100, 128),

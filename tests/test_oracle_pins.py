@@ -531,3 +531,41 @@ def test_generators_are_reproducible_and_distinct():
     assert abs(big.std() - 0.02) < 2e-4 and abs(big.mean()) < 1e-4
     ids = I.token_ids(2, 8, 1024, 50257)
     assert ids.min() >= 0 and ids.max() < 50257 and ids.dtype == np.int32
+
+
+# ---------------------------------------------------------------------------
+# the optional additive mask of the attention chain
+# ---------------------------------------------------------------------------
+
+
+def test_attention_additive_mask():
+    B, Hq, Hkv, Sq, Skv, dh = 2, 4, 2, 5, 7, 8
+    q, k, v = rnd(B, Hq, Sq, dh), rnd(B, Hkv, Skv, dh), rnd(B, Hkv, Skv, dh)
+    scale = 1 / math.sqrt(dh)
+    base = O.attention(q, k, v, scale, False)
+    # a zero mask, and a mask that is constant along the keys, change nothing
+    assert np.array_equal(O.attention(q, k, v, scale, False, np.zeros((1, 1, Sq, Skv))), base)
+    shift = rnd(B, Hq, Sq, 1) * np.ones((1, 1, 1, Skv))
+    assert np.abs(O.attention(q, k, v, scale, False, shift) - base).max() < 1e-13
+    # -inf above the (bottom-right aligned) diagonal is the causal flag
+    i = np.arange(Sq)[:, None]; j = np.arange(Skv)[None, :]
+    tri = np.where(j > i + (Skv - Sq), -np.inf, 0.0)[None, None]
+    assert np.abs(O.attention(q, k, v, scale, False, tri) - O.attention(q, k, v, scale, True)).max() < 1e-14
+    # -inf on the last keys of one sequence (padding) is attention over the shorter sequence
+    pad = np.zeros((B, 1, Sq, Skv)); pad[1, :, :, 4:] = -np.inf
+    got = O.attention(q, k, v, scale, False, pad)
+    assert np.abs(got[0] - base[0]).max() < 1e-14
+    assert np.abs(got[1:] - O.attention(q[1:], k[1:, :, :4], v[1:, :, :4], scale, False)).max() < 1e-13
+    # a finite random mask, per batch and head, against the library routine the paper's fused op calls
+    m = rnd(B, Hq, Sq, Skv)
+    kk = np.repeat(k, Hq // Hkv, axis=1); vv = np.repeat(v, Hq // Hkv, axis=1)
+    ref = F.scaled_dot_product_attention(torch.from_numpy(q), torch.from_numpy(kk), torch.from_numpy(vv),
+                                         attn_mask=torch.from_numpy(m), scale=scale)
+    ref = ref.permute(0, 2, 1, 3).reshape(B, Sq, Hq * dh).numpy()
+    assert np.abs(O.attention(q, k, v, scale, False, m) - ref).max() < 1e-13
+    # two keys, closed form: p_0 = sigmoid((s_0 + m_0) - (s_1 + m_1))
+    q1, k1, v1 = rnd(1, 1, 1, dh), rnd(1, 1, 2, dh), rnd(1, 1, 2, dh)
+    m1 = np.array([[[[0.3, -1.1]]]])
+    s0, s1 = (q1[0, 0, 0] @ k1[0, 0, 0]) * scale + 0.3, (q1[0, 0, 0] @ k1[0, 0, 1]) * scale - 1.1
+    p0 = 1 / (1 + math.exp(s1 - s0))
+    assert np.abs(O.attention(q1, k1, v1, scale, False, m1)[0, 0] - (p0 * v1[0, 0, 0] + (1 - p0) * v1[0, 0, 1])).max() < 1e-14
