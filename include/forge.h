@@ -120,10 +120,11 @@ forge_status forge_attn_fused_masked(const void* q, const void* k, const void* v
  * 8 elements keeps every output row 16-byte aligned, which the fast store path needs; a
  * vocabulary-sized N such as 50257 is best given a padded stride (50264).
  * Requirements: M,N,K >= 1; K % 8 == 0 for bf16, K % 4 == 0 for fp32; ldy == 0 or ldy >= N.
- * Workspace: problems that are split along K (bf16 with M <= 64; fp32 with fewer output tiles
- * than CUs) need forge_gemm_workspace_bytes() bytes of device memory for the fp32 partial sums
- * (0 otherwise; FORGE_ERR_WORKSPACE if too little is given); the partial sums are added in a
- * fixed order, so results stay bitwise reproducible.
+ * Workspace: problems with fewer output tiles than the chip has room for are split along K and
+ * keep fp32 partial sums in forge_gemm_workspace_bytes() bytes of device memory (0 when the
+ * problem is not split); the partial sums are added in a fixed order, so results stay bitwise
+ * reproducible.  bf16 problems with M <= 64 (a decode step) cannot run without it
+ * (FORGE_ERR_WORKSPACE); all others run unsplit, slower, when less is given.
  * ------------------------------------------------------------------------------------ */
 size_t forge_gemm_workspace_bytes(int M, int N, int K, forge_act act, forge_dtype dt);
 

@@ -266,7 +266,8 @@ forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias
   if (act < FORGE_ACT_NONE || act > FORGE_ACT_GELU_ERF) return FORGE_ERR_INVALID_ARG;
   if (K % (dt == FORGE_BF16 ? 8 : 4) != 0) return FORGE_ERR_UNSUPPORTED;
   if (y == x || y == w) return FORGE_ERR_INVALID_ARG;
-  const size_t need = gemm_ws(M, N, K, act, dt);
+  // only the decode-sized bf16 problems cannot run without their partial-sum planes
+  const size_t need = dt == FORGE_BF16 && M <= 64 ? gemm_ws(M, N, K, act, dt) : 0;
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FORGE_ERR_WORKSPACE;
   GemmArgs a = {x, w, bias, residual, y, M, N, K, ldy, act, nullptr, nullptr, workspace, workspace_bytes};
   return gemm_dispatch(a, dt, static_cast<hipStream_t>(stream));

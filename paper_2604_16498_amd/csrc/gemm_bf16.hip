@@ -71,7 +71,9 @@ struct GemmParams {
   int ldy;            // row stride of y and residual (elements)
   int tiles_m, tiles_n;
   int k_per_split;    // split-K: k range of one block (multiple of 64); otherwise >= K
+  int splits;         // split-K in the persistent kernel: number of k ranges
   float* part;        // split-K: fp32 partial sums [splits, M, N]
+  size_t part_bytes;  // bytes behind part
   QkvSplit sp;
   NormTail nt;        // nt.y_norm == nullptr: none
 };
@@ -276,7 +278,8 @@ __device__ inline void lds_barrier() {
 // blocks stride through that run together, so at any time one L2 serves a compact patch of y.
 template <int BM, int BN, int WM, int WN, int ACT, int MODE>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams p) {
-  static_assert(MODE == MODE_PLAIN || MODE == MODE_QKV, "split-K does not use this kernel");
+  constexpr bool SPLITK = MODE == MODE_SPLITK;   // raw fp32 partial tiles over grid-wide k ranges
+  static_assert(!SPLITK || ACT == FORGE_ACT_NONE, "the reduce kernel carries the epilogue");
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr bool SWIGLU = ACT == FORGE_ACT_SWIGLU;
@@ -295,7 +298,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
   constexpr int NIT = NITP * NPASS;                   // 16-byte row pieces per lane and tile
   // a tile staged in one pass is parked in registers; the large tile (two passes, accumulators
   // alone take half the register file) is stored at once, pass by pass
-  constexpr bool PARK = NPASS == 1;
+  constexpr bool PARK = NPASS == 1 && !SPLITK;
   constexpr int NPARK = PARK ? NIT : 1;
   constexpr int STORE_ITS = !PARK ? 1 : (NPARK < 8 ? NPARK : 8);   // k iterations that carry stores
   constexpr int STORES_PER_IT = PARK ? NPARK / STORE_ITS : 0;
@@ -309,16 +312,23 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
   const int wm = wave / WN, wn = wave % WN;
   const int fr = lane & 31, fh = lane >> 5;
   const int M = p.M, N = p.N, K = p.K;
-  const int nk = K / BK;
 
-  // ---- this block's tiles ----------------------------------------------------------------------
+  // ---- this block's work items: tiles, or (k range, tile) pairs when K is split -----------------
+  // (k range major, so that the items resident at one time are neighbouring tiles of one range)
   const int ntiles = p.tiles_m * p.tiles_n;
+  const int nitems = SPLITK ? ntiles * p.splits : ntiles;
   const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3, bpx = gridDim.x >> 3;
-  const int lo = xcd * (ntiles >> 3) + min(xcd, ntiles & 7);
-  const int cnt = (ntiles >> 3) + (xcd < (ntiles & 7) ? 1 : 0);
+  const int lo = xcd * (nitems >> 3) + min(xcd, nitems & 7);
+  const int cnt = (nitems >> 3) + (xcd < (nitems & 7) ? 1 : 0);
   if (idx >= cnt) return;                             // uniform over the block
+  auto k_range = [&](int item, int& k_begin, int& n_slabs) {
+    const int z = SPLITK ? item / ntiles : 0;
+    k_begin = z * p.k_per_split;
+    n_slabs = (min(K, k_begin + p.k_per_split) - k_begin) / BK;
+  };
   constexpr int GROUP_M = 8;
-  auto tile_origin = [&](int tile, int& m0, int& n0) {
+  auto tile_origin = [&](int item, int& m0, int& n0) {
+    const int tile = SPLITK ? item % ntiles : item;
     const int in_group = GROUP_M * p.tiles_n;
     const int group = tile / in_group;
     const int first_m = group * GROUP_M;
@@ -438,10 +448,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
   };
   const bool has_res = MODE == MODE_PLAIN && p.residual != nullptr;
 
-  int tt = idx, m0, n0;
+  int tt = idx, m0, n0, kb0, nk;
   tile_origin(lo + tt, m0, n0);
+  k_range(lo + tt, kb0, nk);
   set_sources(m0, n0);
-  if (nk > 0) issue(0, 0);
+  if (nk > 0) issue(kb0, 0);
   for (;;) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -457,7 +468,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
       else if (!PARK && kt == 0 && flushed) __builtin_amdgcn_s_waitcnt(0x0f70 | (NIT & 0xf) | ((NIT >> 4) << 14));
       else __builtin_amdgcn_s_waitcnt(0x0f70);
       __builtin_amdgcn_s_barrier();   // slab kt is in LDS for everyone; buffer (kt+1)&1 is free
-      if (kt + 1 < nk) issue((kt + 1) * BK, (kt + 1) & 1);
+      if (kt + 1 < nk) issue(kb0 + (kt + 1) * BK, (kt + 1) & 1);
       __builtin_amdgcn_sched_barrier(0);   // the wait above counts on loads first, stores second
       if (PARK && pending && kt < STORE_ITS) {
 #pragma unroll
@@ -477,12 +488,35 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
     // ---- next tile's first slab, then the epilogue of this one ------------------------------------
     const int next = tt + bpx;
     const bool has_next = next < cnt;
-    int nm0 = 0, nn0 = 0;
+    int nm0 = 0, nn0 = 0, nkb0 = 0, nnk = 0;
     lds_barrier();                    // every wave is done with the operand slabs
     if (has_next) {
       tile_origin(lo + next, nm0, nn0);
+      k_range(lo + next, nkb0, nnk);
       set_sources(nm0, nn0);
-      if (nk > 0) issue(0, 0);
+      if (nnk > 0) issue(nkb0, 0);
+    }
+    if (SPLITK) {
+      // raw partial sums of this k range: lane = row m, two runs of 8 columns per accumulator
+      const int z = (lo + tt) / ntiles;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int m = m0 + (wm * TM + i) * 32 + fr;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          float run[2][8];
+          runs_of(acc[i][j], run);
+#pragma unroll
+          for (int gp = 0; gp < 2; ++gp) {
+            const int n = n0 + (wn * TN + j) * 32 + 16 * fh + 8 * gp;
+            if (m >= M || n >= N) continue;       // N % 8 == 0 (host): a run is all in or all out
+            Vec8<float>::store(p.part + ((int64_t)z * M + m) * N + n, run[gp]);
+          }
+        }
+      }
+      if (!has_next) break;
+      tt = next; m0 = nm0; n0 = nn0; kb0 = nkb0; nk = nnk;
+      continue;
     }
     const bool interior = m0 + BM <= M && n0 + BN_OUT <= N;
     int tb = 0, ts = 0;
@@ -591,6 +625,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
     tt = next;
     m0 = nm0;
     n0 = nn0;
+    kb0 = nkb0;
+    nk = nnk;
   }
   if (PARK && pending) store_parked(0, NPARK);
 }
@@ -964,8 +1000,8 @@ forge_status launch_pers(const GemmParams& p0, hipStream_t s) {
     configured = true;
   }
   const int slots = compute_units() * per_cu / 8 * 8;
-  const int ntiles = p.tiles_m * p.tiles_n;
-  const int blocks = min(slots, (ntiles + 7) / 8 * 8);
+  const int nitems = p.tiles_m * p.tiles_n * (MODE == MODE_SPLITK ? p.splits : 1);
+  const int blocks = min(slots, (nitems + 7) / 8 * 8);
   kern<<<dim3(blocks), dim3(WM * WN * 64), smem, s>>>(p);
   return launch_status();
 }
@@ -989,6 +1025,23 @@ inline Variant choose_variant(int M, int N, int K, int ldy, forge_act act, bool 
   const bool use_256 = big >= 4 * cus || (big * 10 >= cus * 9 && big * 100 >= rounds * cus * 85);
   if (use_256) return fast ? V_FAST_256 : V_GEN_256;
   return fast ? V_FAST_128 : V_GEN_128;
+}
+
+// Few 128-tiles and a long reduction (a 128-token prompt against the 8B-shaped weights: 32 tiles
+// of 224 slabs): the persistent kernel then walks (k range, tile) items instead of tiles and a
+// reduce kernel adds the fp32 partial tiles in range order.  Only with workspace from the caller.
+struct PersSplit {
+  int splits, k_per_split;
+};
+inline PersSplit plan_pers_split(int M, int ncols, int K) {
+  const int tiles = ceil_div(M, 128) * ceil_div(ncols, 128);
+  const int slots = compute_units() * 2;
+  const int slabs = K / BK;
+  if (K % BK != 0 || ncols % 8 != 0 || tiles * 2 > slots || slabs < 16) return PersSplit{1, K};
+  const int want = min(min(slots / tiles, slabs / 8), 16);
+  if (want < 2) return PersSplit{1, K};
+  const int per = ceil_div(slabs, want);
+  return PersSplit{ceil_div(slabs, per), per * BK};
 }
 
 struct SkinnyPlan {
@@ -1036,12 +1089,27 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
                                    p.bias != nullptr || p.residual != nullptr);
   switch (v) {
     case V_FAST_256: return launch_pers<256, 256, 2, 4, ACT, MODE>(p, s);
-    case V_FAST_128:
+    case V_FAST_128: {
+      const int ncols = ACT == FORGE_ACT_SWIGLU ? 2 * p.N : p.N;
+      const PersSplit ps = plan_pers_split(p.M, ncols, p.K);
+      if (ps.splits > 1 && p.part != nullptr &&
+          p.part_bytes >= (size_t)ps.splits * p.M * ncols * sizeof(float)) {
+        GemmParams q = p;       // the gated weight is a plain [2N, K] matrix here: gate columns, then up
+        q.N = ncols;
+        q.splits = ps.splits;
+        q.k_per_split = ps.k_per_split;
+        const forge_status st = launch_pers<128, 128, 2, 4, FORGE_ACT_NONE, MODE_SPLITK>(q, s);
+        if (st != FORGE_OK) return st;
+        const int64_t threads = (int64_t)p.M * ceil_div(p.N, 4);
+        splitk_reduce_kernel<ACT, MODE == MODE_QKV><<<(unsigned)ceil_div64(threads, 256), 256, 0, s>>>(p, ps.splits, ncols);
+        return launch_status();
+      }
       // 8 waves of 64 x 32 (16 waves per CU) hide the L2 latency of the small tile better than 4
       // waves of 64 x 64 (measured 7-13 % on the d_model = 768 shapes); the gated epilogue pairs
       // two accumulator columns per wave and keeps the 2 x 2 layout
       if constexpr (ACT == FORGE_ACT_SWIGLU) return launch_pers<128, 128, 2, 2, ACT, MODE>(p, s);
       else return launch_pers<128, 128, 2, 4, ACT, MODE>(p, s);
+    }
     case V_GEN_256: return launch_generic<256, 256, 2, 4, ACT, MODE>(p, 1, s);
     case V_GEN_128: return launch_generic<128, 128, 2, 2, ACT, MODE>(p, 1, s);
     default: break;
@@ -1075,7 +1143,11 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
 }  // namespace
 
 size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act) {
-  if (M > 64) return 0;
+  if (M > 64) {     // optional: without it the problem runs unsplit
+    const int ncols = act == FORGE_ACT_SWIGLU ? 2 * N : N;
+    const PersSplit ps = plan_pers_split(M, ncols, K);
+    return ps.splits > 1 ? (size_t)ps.splits * M * ncols * sizeof(float) : 0;
+  }
   const SkinnyPlan sk = plan_skinny(N, K, act);
   return (size_t)sk.splits * M * sk.ncols * sizeof(float);
 }
@@ -1108,7 +1180,10 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   p.ldy = a.ldy > 0 ? a.ldy : a.N;
   p.k_per_split = a.K;
   p.part = (float*)a.workspace;
-  const size_t need = gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act);
+  p.part_bytes = a.workspace != nullptr ? a.workspace_bytes : 0;
+  p.splits = 1;
+  // the decode path needs its partial-sum planes; the k split of larger problems is optional
+  const size_t need = a.M <= 64 ? gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act) : 0;
   if (need > a.workspace_bytes || (need > 0 && a.workspace == nullptr)) return FORGE_ERR_WORKSPACE;
   const bool tails = gemm_fuses_tail(a.M, a.N, FORGE_BF16);
   if (a.norm != nullptr && tails && a.split == nullptr && a.act == FORGE_ACT_NONE) {

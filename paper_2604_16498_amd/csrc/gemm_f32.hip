@@ -181,9 +181,9 @@ size_t gemm_f32_workspace_bytes(int M, int N, int K, forge_act act) {
 }
 
 forge_status launch_gemm_f32(const GemmArgs& a, hipStream_t s) {
-  const SplitPlan pl = plan_split(a.M, a.N, a.K);
+  SplitPlan pl = plan_split(a.M, a.N, a.K);
   const size_t need = gemm_f32_workspace_bytes(a.M, a.N, a.K, a.act);
-  if (need > a.workspace_bytes || (need > 0 && a.workspace == nullptr)) return FORGE_ERR_WORKSPACE;
+  if (need > a.workspace_bytes || (need > 0 && a.workspace == nullptr)) pl = SplitPlan{1, a.K};   // unsplit
   float* part = pl.splits > 1 ? (float*)a.workspace : nullptr;
   dim3 grid(ceil_div(a.N, BN), ceil_div(a.M, BM), pl.splits), block(256);
   const unsigned rblocks = (unsigned)ceil_div64((int64_t)a.M * a.N, 256);

@@ -180,6 +180,22 @@ def test_model_forward_hidden_llama(F):
     assert l2 < 2e-2 and mx < 6e-2
 
 
+def test_block_wide_model_short_prompt(F):
+    """A 100-token prompt through a wide layer (d_model 1024, MLP 4096): every projection has few
+    output tiles and a long reduction, i.e. the k-split path of the tile kernel, including the
+    head split of the QKV projection."""
+    sh = I.BlockShape(1024, 4, 2, 64, 4096, norm="rmsnorm", mlp_act="swiglu", use_rope=True,
+                      rope_base=500000.0, has_bias=False)
+    B, S = 1, 100
+    w = I.block_weights(sh, 78, 0, bf16=True, random_affine=True, weight_std=0.03)
+    x = I.normal(78, 0, "x", (B, S, sh.d_model), 1.0, bf16=True)
+    kc = np.zeros((B, sh.kv_heads, S, sh.head_dim)); vc = np.zeros_like(kc)
+    ref = O.decoder_block(sh, w, x, kc, vc, pos0=0)
+    out, tk, tv = run_block(F, sh, w, x, True, S)
+    check(tk, kc, True, "k cache"); check(tv, vc, True, "v cache")
+    check(out, ref, True, "wide block, short prompt", chain=True)
+
+
 def test_model_generation_loop(F):
     """Prefill of 24 tokens, then 8 single-token steps on the growing KV cache (teacher-forced
     ids): the logits of step i equal row 24 + i of one causal forward over all 32 tokens, which

@@ -122,6 +122,35 @@ def test_gemm_many_tiles_per_block(F, M, N, K, act, use_b, use_r, ld):
     assert torch.equal(again, ty)
 
 
+@pytest.mark.parametrize("M,N,K,act", [
+    (128, 512, 2048, "none"), (130, 520, 4096, "gelu_tanh"), (257, 256, 14336, "none"),
+    (100, 384, 2048, "swiglu"), (512, 128, 8192, "silu"),
+])
+def test_gemm_few_tiles_long_k(F, M, N, K, act):
+    """A prompt-sized M against a long reduction: few output tiles, so the k loop is split over
+    the chip when the caller provides the workspace; without it the same problem runs unsplit."""
+    wn = 2 * N if act == "swiglu" else N
+    x = I.normal(69, 0, "x", (M, K), 1.0, bf16=True)
+    w = I.normal(69, 0, "w_up", (wn, K), 1.0 / math.sqrt(K), bf16=True)
+    b = I.normal(69, 0, "b_up", (wn,), 0.5, bf16=True)
+    r = I.normal(69, 0, "residual", (M, N), 1.0, bf16=True)
+    ref = O.gemm_bias_act(x, w, b, r, act)
+    need = F.forge_gemm_workspace_bytes(M, N, K, act, torch.bfloat16)
+    assert need > 0
+    tx, tw, tb, tr = (dev(a, True) for a in (x, w, b, r))
+    y1 = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    F.forge_gemm_bias_gelu(tx, tw, tb, tr, y1, act, F.workspace(need))
+    y2 = torch.empty_like(y1)
+    F.forge_gemm_bias_gelu(tx, tw, tb, tr, y2, act)          # no workspace: unsplit
+    torch.cuda.synchronize()
+    check(y1, ref, True, "split-k gemm %s" % act)
+    check(y2, ref, True, "unsplit gemm %s" % act)
+    y3 = torch.empty_like(y1)
+    F.forge_gemm_bias_gelu(tx, tw, tb, tr, y3, act, F.workspace(need))
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y3)
+
+
 def test_gemm_residual_in_place(F):
     M, N, K = 200, 256, 128
     x = I.normal(62, 0, "x", (M, K), 1.0, bf16=True)
