@@ -74,12 +74,13 @@ __device__ inline float xchg32_sum(float x) {
 // (not hidden behind anything: this variant trades speed for generality).
 template <int DH, bool MASKED>
 __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
-  constexpr int BQ = 256, BKV = 64, NT = 512;
+  constexpr int BQ = 256, BKV = 64;
   constexpr int CPR = DH / 8;                 // 16-byte chunks per row
   constexpr int KS = DH * 2 + 16;             // K row stride in LDS (bytes)
   constexpr int VS = DH * 2 + 64;             // V row stride in LDS (bytes)
   constexpr int K_BYTES = BKV * KS, V_BYTES = BKV * VS;
-  constexpr int LPT = BKV * CPR / NT;         // chunks per thread per tensor per tile
+  constexpr int NLOAD = 256;                  // threads that move tiles: waves 0-3 (see below)
+  constexpr int LPT = BKV * CPR / NLOAD;      // chunks per loading thread per tensor per tile
   constexpr int NKS = DH / 16;                // MFMA k-steps over dh
   constexpr int NDT = DH / 32;                // 32-row tiles of O^T
   extern __shared__ __attribute__((aligned(16))) char smem[];   // [K0 | K1 | V0 | V1]
@@ -123,15 +124,20 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   const int wave_min_limit = p.causal ? q0w + off : p.kv_len - 1;
 
   // ---- global -> registers -> LDS copy plan ----------------------------------------------------
+  // Only waves 0-3 move tiles: their phase order leaves them ~2000 cycles of slack at the barrier
+  // of every tile, while waves 4-7 are the critical path (measured), so the copies cost nothing
+  // there and shorten the slow group.
+  const bool loader = scores_first;
   int ld_row[LPT], ld_c[LPT];
 #pragma unroll
   for (int i = 0; i < LPT; ++i) {
-    const int idx = tid + i * NT;
+    const int idx = (tid & (NLOAD - 1)) + i * NLOAD;
     ld_row[i] = idx / CPR;
     ld_c[i] = idx % CPR;
   }
   u32x4 rk[LPT], rv[LPT];
   auto load_rows = [&](const bf16* base, int t, u32x4 (&r)[LPT]) {
+    if (!loader) return;
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int key = min(t * BKV + ld_row[i], p.kv_len - 1);   // rows past the end re-read the last key
@@ -139,11 +145,13 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
     }
   };
   auto store_k = [&](int buf) {
+    if (!loader) return;
 #pragma unroll
     for (int i = 0; i < LPT; ++i)
       *reinterpret_cast<u32x4*>(kbuf + buf * K_BYTES + ld_row[i] * KS + ld_c[i] * 16) = rk[i];
   };
   auto store_v = [&](int buf) {
+    if (!loader) return;
 #pragma unroll
     for (int i = 0; i < LPT; ++i)
       *reinterpret_cast<u32x4*>(vbuf + buf * V_BYTES + ld_row[i] * VS + ld_c[i] * 16) = rv[i];
