@@ -151,6 +151,39 @@ def test_gemm_few_tiles_long_k(F, M, N, K, act):
     assert torch.equal(y1, y3)
 
 
+def _random_gemm_cases():
+    rng = np.random.default_rng(20260416)
+    cases = []
+    for _ in range(36):
+        M = int(rng.choice([1, 7, 63, 64, 65, 127, 128, 129, 200, 255, 256, 257, 511, 640, 1000, 2049]))
+        N = int(rng.choice([8, 40, 64, 120, 128, 136, 248, 256, 264, 392, 513, 1000, 1031, 2056]))
+        K = int(rng.choice([8, 64, 72, 128, 192, 200, 512, 1024, 1088, 2048]))
+        act = str(rng.choice(["none", "gelu_tanh", "gelu_erf", "relu", "silu", "swiglu"]))
+        cases.append((M, N, K, act, bool(rng.integers(2)), bool(rng.integers(2)), bool(rng.integers(2))))
+    return cases
+
+
+@pytest.mark.parametrize("M,N,K,act,use_b,use_r,pad", _random_gemm_cases())
+def test_gemm_random_shapes(F, M, N, K, act, use_b, use_r, pad):
+    """Seeded sweep over shapes around the tile, slab and alignment boundaries of every GEMM
+    variant (decode-sized, tile kernels with and without k split, generic fallback), with and
+    without bias / residual / padded output rows, workspace always provided."""
+    wn = 2 * N if act == "swiglu" else N
+    ldy = (N + 15) // 8 * 8 if pad else N
+    x = I.normal(79, 0, "x", (M, K), 1.0, bf16=True)
+    w = I.normal(79, 0, "w_up", (wn, K), 1.0 / math.sqrt(K), bf16=True)
+    b = I.normal(79, 0, "b_up", (wn,), 0.5, bf16=True) if use_b else None
+    r = I.normal(79, 0, "residual", (M, ldy), 1.0, bf16=True) if use_r else None
+    ref = O.gemm_bias_act(x, w, b, None if r is None else r[:, :N], act)
+    ty = torch.full((M, ldy), 7.0, dtype=torch.bfloat16, device="cuda")
+    ws = F.workspace(max(256, F.forge_gemm_workspace_bytes(M, N, K, act, torch.bfloat16)))
+    F.forge_gemm_bias_gelu(dev(x, True), dev(w, True), None if b is None else dev(b, True),
+                           None if r is None else dev(r, True), ty, act, ws, n=N)
+    torch.cuda.synchronize()
+    check(ty[:, :N], ref, True, "gemm %s %dx%dx%d via %s" % (act, M, N, K, F.forge_gemm_variant(M, N, K, act, torch.bfloat16, ldy=ldy)))
+    assert torch.all(ty[:, N:] == 7.0)
+
+
 def test_gemm_residual_in_place(F):
     M, N, K = 200, 256, 128
     x = I.normal(62, 0, "x", (M, K), 1.0, bf16=True)
