@@ -196,6 +196,46 @@ def test_block_wide_model_short_prompt(F):
     check(out, ref, True, "wide block, short prompt", chain=True)
 
 
+def _random_block_cases():
+    rng = np.random.default_rng(16498)
+    cases = []
+    for _ in range(12):
+        dh = int(rng.choice([64, 128]))
+        hkv = int(rng.choice([1, 2, 4]))
+        hq = hkv * int(rng.choice([1, 2, 4]))
+        d = int(rng.choice([128, 192, 256, 512]))
+        ff = int(rng.choice([128, 264, 512, 1032]))
+        llama = bool(rng.integers(2))
+        B = int(rng.integers(1, 6)); S = int(rng.choice([1, 5, 31, 64, 100, 129, 257]))
+        pos0 = int(rng.choice([0, 0, 3, 70]))
+        cases.append((d, hq, hkv, dh, ff, llama, B, S, pos0))
+    return cases
+
+
+@pytest.mark.parametrize("d,hq,hkv,dh,ff,llama,B,S,pos0", _random_block_cases())
+def test_block_random_shapes(F, d, hq, hkv, dh, ff, llama, B, S, pos0):
+    """Seeded sweep over layer shapes: head counts and grouping, head_dim, widths that are not
+    tile multiples, sequence lengths around the tile sizes, with and without cached positions."""
+    if llama:
+        sh = I.BlockShape(d, hq, hkv, dh, ff, norm="rmsnorm", mlp_act="swiglu", use_rope=True,
+                          rope_base=10000.0, has_bias=False)
+    else:
+        sh = I.BlockShape(d, hq, hkv, dh, ff)
+    cap = pos0 + S + 3
+    w = I.block_weights(sh, 80, 0, bf16=True, bias_std=0.05, random_affine=True, weight_std=0.05)
+    x = I.normal(80, 0, "x", (B, S, sh.d_model), 1.0, bf16=True)
+    kc = np.zeros((B, sh.kv_heads, cap, sh.head_dim)); vc = np.zeros_like(kc)
+    if pos0:
+        kc[:, :, :pos0] = I.normal(80, 0, "k_cache", (B, sh.kv_heads, pos0, sh.head_dim), 1.0, bf16=True)
+        vc[:, :, :pos0] = I.normal(80, 0, "v_cache", (B, sh.kv_heads, pos0, sh.head_dim), 1.0, bf16=True)
+    tk, tv = dev(kc.astype(np.float32), True), dev(vc.astype(np.float32), True)
+    ref = O.decoder_block(sh, w, x, kc, vc, pos0=pos0)
+    out, tk, tv = run_block(F, sh, w, x, True, cap, pos0=pos0, kc=tk, vc=tv)
+    check(out, ref, True, "block", chain=True)
+    check(tk[:, :, :pos0 + S], kc[:, :, :pos0 + S], True, "k cache")
+    check(tv[:, :, :pos0 + S], vc[:, :, :pos0 + S], True, "v cache")
+
+
 def test_model_generation_loop(F):
     """Prefill of 24 tokens, then 8 single-token steps on the growing KV cache (teacher-forced
     ids): the logits of step i equal row 24 + i of one causal forward over all 32 tokens, which
