@@ -34,8 +34,10 @@
 // column-major inside a group, so that the tiles resident in one XCD at a time share x and w
 // panels in that L2.
 //
-// M <= 64 (decode): the weight is streamed once; 64 x 64 tiles, K split over grid.y so that at
-// least 512 blocks run, fp32 partials, and a fixed-order reduce kernel that carries the epilogue.
+// M <= 64 (decode): the weight is streamed once by gemm_bf16_wstream_kernel (128 or 256 weight
+// rows per block, K split over grid.y to about one block per CU), fp32 partials, and fixed-order
+// reduce kernels that carry the epilogue (and, inside a decoder layer, RoPE or the following norm).
+// Prompt-sized M with few tiles and a long K: the tile kernel itself walks (k range, tile) items.
 #include "common.hpp"
 
 namespace forge {
@@ -267,7 +269,7 @@ __device__ inline void lds_barrier() {
 //    ring buffer 0; the tile is staged through buffer 1, in row halves if it is larger than a
 //    buffer), so its latency hides behind the epilogue;
 //  * a tile that is staged in one pass (128 x 128, and the SwiGLU 256 x 128) is then parked in
-//    registers (32 per lane) and the next tile's k loop issues a few of these row stores per slab
+//    registers (16 or 32 per lane) and the next tile's k loop issues a few of these row stores per slab
 //    instead of all blocks of the chip storing at once.  The vector-memory counter retires in
 //    order, so the wait for slab k tolerates exactly the stores issued after its loads
 //    (STORES_PER_IT).  Stores of tiles that touch the matrix edge are predicated, hence not
