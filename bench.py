@@ -306,6 +306,55 @@ def main():
         latency = {"steps": len(ds), "mean": round(sum(ds) / len(ds), 4), "p50": round(ds[len(ds) // 2], 4),
                    "p90": round(ds[int(len(ds) * 0.9)], 4), "p99": round(ds[min(len(ds) - 1, int(len(ds) * 0.99))], 4)}
 
+    # ---- the same step through the compiled executor (static buffer plan + HIP graph replay),
+    # outside the timed region: reported beside the plain launch list, never as `value`
+    compiled = None
+    if not args.traffic_probe:
+        cm = F.CompiledModel(m["model"], wl.batch, wl.seq, pos0, m["cap"])
+        cws = F.workspace(cm.workspace_bytes())
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        cm.bind(m["inp"], m["out"], m["kc"], m["vc"], cws, side)
+        for _ in range(args.warmup):
+            cm.run(side)
+        side.synchronize()
+        c0 = time.perf_counter()
+        for _ in range(args.steps):
+            cm.run(side)
+        side.synchronize()
+        c_ms = (time.perf_counter() - c0) * 1e3 / args.steps
+        evs = []
+        with torch.cuda.stream(side):
+            for _ in range(50):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                cm.run(side)
+                e1.record()
+                evs.append((e0, e1))
+        side.synchronize()
+        ds = sorted(a.elapsed_time(b) for a, b in evs)
+        # host time to enqueue one step (the calls return before the GPU is done)
+        torch.cuda.synchronize()
+        h0 = time.perf_counter()
+        for _ in range(10):
+            step()
+        h_plain = (time.perf_counter() - h0) / 10
+        torch.cuda.synchronize()
+        h0 = time.perf_counter()
+        for _ in range(10):
+            cm.run(side)
+        h_comp = (time.perf_counter() - h0) / 10
+        side.synchronize()
+        ni, nr, _, nb = cm.counts()
+        compiled = {"ms_per_step": round(c_ms, 4), "p50": round(ds[len(ds) // 2], 4),
+                    "host_enqueue_us": round(h_comp * 1e6, 1), "plain_host_enqueue_us": round(h_plain * 1e6, 1),
+                    "p99": round(ds[min(len(ds) - 1, int(len(ds) * 0.99))], 4),
+                    "instructions": ni, "registers": nr, "buffers": nb, "rho_buf": round(1 - nb / nr, 3),
+                    "workspace_bytes": cm.workspace_bytes(), "plain_workspace_bytes": m["ws"].numel()}
+        cm.close()
+        del cws
+        torch.cuda.synchronize()
+
     # ---- roofline of the dominant kernel: HIP events on the launch stream around every launch
     # of each plain GEMM of one step (same shapes, same weights), repeated; the group with the
     # largest total time is reported.
@@ -408,6 +457,7 @@ def main():
         "step_tflops": round((gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12, 1),
         "step_frac_of_bf16_peak": round((gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "latency_ms": latency,
+        "compiled": compiled,
         "attention": attn,
         "roofline": roofline,
         "cpu_baseline": cpu,

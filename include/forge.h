@@ -228,6 +228,90 @@ forge_status forge_model_forward(const forge_model_desc* model, const void* inpu
                                  void* k_cache, void* v_cache, int batch, int q_len, int pos0,
                                  int kv_cap, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------
+ * Static buffer plan of a flat instruction list (Sec. "Phase 4: IR Analysis & Optimization").
+ * HOST functions on HOST arrays; they never touch the GPU.
+ * A program has n_instr instructions over registers 0..n_regs-1: instruction j writes
+ * out_reg[j] (-1: none) and reads in_regs[in_begin[j] .. in_begin[j+1]) (in_begin has
+ * n_instr+1 entries, in_begin[0] = 0).  Malformed input -> FORGE_ERR_INVALID_ARG, outputs
+ * untouched.
+ *
+ * forge_plan_liveness (Eq. "liveness"): start[r] = index of the instruction that writes r,
+ *   end[r] = index of the last one that reads it.  A register that is only read (a scratch
+ *   area) starts at its first mention, one that is never read ends where it starts, one that
+ *   is never mentioned gets start = end = -1.
+ * forge_plan_dead_after: the dead-after map in CSR form: dead_regs[dead_begin[j] ..
+ *   dead_begin[j+1]) = registers (ascending) whose last use is instruction j.  dead_begin has
+ *   n_instr+1 entries, dead_regs one per register with end >= 0.
+ * forge_plan_linear_scan (Alg. "Linear-Scan Buffer Allocation"): intervals in order of start
+ *   (ties: register number); before each, active intervals that ended strictly before its
+ *   start release their buffers (first released, first reused); *n_bufs = M.  reg_to_buf[r] =
+ *   -1 where start[r] < 0.  The buffer reduction ratio of Eq. "buf_reduction" is 1 - M/N.
+ * forge_plan_workspace: byte offsets in one workspace.  Registers of equal nbytes share
+ *   buffers through a linear scan of their own; registers that live within one instruction
+ *   (start == end, e.g. scratch areas) form one further group sized to its largest member; the
+ *   groups follow each other in the order of their first register; each buffer spans its
+ *   group's size rounded up to 256.  offset[r] = (size_t)-1 where start[r] < 0.
+ * ------------------------------------------------------------------------------------ */
+forge_status forge_plan_liveness(int n_instr, const int* out_reg, const int* in_begin,
+                                 const int* in_regs, int n_regs, int* start, int* end);
+forge_status forge_plan_dead_after(int n_regs, const int* end, int n_instr, int* dead_begin,
+                                   int* dead_regs);
+forge_status forge_plan_linear_scan(int n_regs, const int* start, const int* end, int* reg_to_buf,
+                                    int* n_bufs);
+forge_status forge_plan_workspace(int n_regs, const int* start, const int* end,
+                                  const size_t* nbytes, size_t* offset, size_t* total_bytes,
+                                  int* n_bufs);
+
+/* ---------------------------------------------------------------------------------------
+ * Compiled executor (Sec. "Code Generation: CompiledNPUExecutor"): the launch list of
+ * forge_model_forward for ONE fixed (batch, q_len, pos0, kv_cap), lowered to a flat
+ * instruction list over virtual registers (Alg. "FX -> NPUIR Lowering"), placed in one
+ * workspace by forge_plan_liveness + forge_plan_workspace, and recorded into a HIP graph.
+ * Same kernels, same order, same results as forge_model_forward, bit for bit.
+ *
+ * Registers are the intermediate tensors and per-launch scratch areas; tensors the caller owns
+ * (input, output, KV cache, weights) are constants.  Register numbering: in program order, per
+ * instruction its output, then its second result, then its scratch area (size 0 where the
+ * launch needs none).
+ *
+ * forge_compile_model   builds the handle (host memory only; copies the descriptors, keeps the
+ *                       weight POINTERS: the weights must outlive the handle).
+ * forge_compiled_counts / forge_compiled_program   report the program and its plan: op[j]
+ *                       (forge_op), out_reg / in_begin / in_regs as for forge_plan_liveness,
+ *                       reg_bytes and reg_offset per register.  Any output pointer may be NULL.
+ * forge_compiled_bind   fixes input / output / caches / workspace (device pointers as for
+ *                       forge_model_forward, workspace >= forge_compiled_workspace_bytes) and
+ *                       records the graph on `stream`, which must not be the NULL stream.  It
+ *                       runs the launch list once on `stream` before recording (so output and
+ *                       cache rows are already written when it returns) and creates the graph
+ *                       objects: the only call besides compile/destroy that allocates.  May be
+ *                       called again with other pointers.
+ * forge_compiled_run    replays the graph on `stream`: one launch call, no allocation, no
+ *                       synchronisation.  FORGE_ERR_INVALID_ARG before a successful bind.
+ * A handle is not thread-safe; replays of one handle must not overlap (they share the workspace).
+ * ------------------------------------------------------------------------------------ */
+typedef enum {
+  FORGE_OP_EMBED = 0, FORGE_OP_NORM = 1, FORGE_OP_GEMM_QKV = 2, FORGE_OP_ROPE_Q = 3,
+  FORGE_OP_ROPE_K = 4, FORGE_OP_ATTN = 5, FORGE_OP_GEMM_RES = 6, FORGE_OP_GEMM_ACT = 7,
+  FORGE_OP_GEMM = 8
+} forge_op;
+
+typedef struct forge_compiled forge_compiled;
+
+forge_status forge_compile_model(const forge_model_desc* model, int batch, int q_len, int pos0,
+                                 int kv_cap, forge_compiled** out);
+void forge_compiled_destroy(forge_compiled* c);
+size_t forge_compiled_workspace_bytes(const forge_compiled* c);
+forge_status forge_compiled_counts(const forge_compiled* c, int* n_instr, int* n_regs, int* n_reads,
+                                   int* n_bufs);
+forge_status forge_compiled_program(const forge_compiled* c, int* op, int* out_reg, int* in_begin,
+                                    int* in_regs, size_t* reg_bytes, size_t* reg_offset);
+forge_status forge_compiled_bind(forge_compiled* c, const void* input, void* output, void* k_cache,
+                                 void* v_cache, void* workspace, size_t workspace_bytes,
+                                 void* stream);
+forge_status forge_compiled_run(forge_compiled* c, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

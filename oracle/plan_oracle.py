@@ -18,9 +18,10 @@ What it computes (Sec. "Phase 4: IR Analysis & Optimization"):
 
 The paper's slots have no byte size.  `workspace_plan` is the one extension
 used to turn slots into byte offsets of one workspace: registers are grouped
-by their byte size, each group is assigned by its own linear scan, and the
-groups are laid out one after the other (so a buffer never has to hold a
-register larger than the one it was created for).
+by their byte size (registers that live within one instruction only, such as
+scratch areas, form a single group sized to the largest of them), each group
+is assigned by its own linear scan, and the groups are laid out one after the
+other (so a buffer never has to hold a register larger than its group's).
 
 Readings where the paper leaves the choice open:
 * a register that no instruction writes (a scratch area an instruction uses
@@ -105,17 +106,21 @@ def buffer_reduction(n_bufs: int, n_regs: int) -> float:
 def workspace_plan(intervals: Sequence[Interval], nbytes: Sequence[int],
                    align: int = 256) -> Tuple[List[int], int, int]:
     """Byte offset of every register inside one workspace, the workspace size and the
-    number of buffers.  Registers of equal byte size form a group; each group gets its own
-    linear scan; groups follow each other in the order of their first register."""
-    groups: Dict[int, List[int]] = {}
+    number of buffers.  Registers of equal byte size form a group, except that all registers
+    living within a single instruction (start == end: scratch areas, results nobody reads)
+    form one group of their own whose buffers span the largest of them.  Each group gets its
+    own linear scan; groups follow each other in the order of their first register."""
+    groups: Dict[object, List[int]] = {}
     for r, iv in enumerate(intervals):
         if iv is not None:
-            groups.setdefault(nbytes[r], []).append(r)
+            key = "single" if iv[0] == iv[1] else nbytes[r]
+            groups.setdefault(key, []).append(r)
     offset = [-1] * len(intervals)
     base, total_bufs = 0, 0
-    for size, regs in groups.items():          # dicts keep insertion order
+    for _, regs in groups.items():             # dicts keep insertion order
         sub = [intervals[r] for r in regs]
         buf, m = linear_scan(sub)
+        size = max(nbytes[r] for r in regs)
         stride = (size + align - 1) // align * align
         for r, b in zip(regs, buf):
             offset[r] = base + b * stride
@@ -136,13 +141,12 @@ OPS = {"embed": 0, "norm": 1, "gemm_qkv": 2, "rope_q": 3, "rope_k": 4, "attn": 5
        "gemm_res": 6, "gemm_act": 7, "gemm": 8}
 
 
-def decoder_program(n_layers: int, tokens: bool, rope_separate: bool, norm2_separate: bool,
-                    gemm_scratch: Sequence[bool], attn_scratch: bool, head_scratch: bool):
+def decoder_program(n_layers: int, tokens: bool, rope_separate: bool, norm2_separate: bool):
     """Returns (program, kinds): program = [(op, output_reg, input_regs)], kinds[r] names what
     register r holds ('h', 'y', 'q', 'o', 'u', 'ws_qkv', 'ws_o', 'ws_up', 'ws_down',
     'ws_attn', 'ws_head').
 
-    `gemm_scratch` = which of the four projections (qkv, out, up, down) use a scratch area;
+    Every projection and the attention carry a scratch register (its byte size may be zero).
     `rope_separate` = q and k are rotated by launches of their own; `norm2_separate` = the
     second norm is a launch of its own (else the output projection produces it as a second
     result next to the new residual stream; an instruction has one output register, so the
@@ -162,8 +166,8 @@ def decoder_program(n_layers: int, tokens: bool, rope_separate: bool, norm2_sepa
     def emit(op, out, ins):
         program.append((OPS[op], out, list(ins)))
 
-    def scratch(flag, kind):
-        return [new(kind)] if flag else []
+    def scratch(kind):
+        return [new(kind)]
 
     h = -1                                   # -1: the caller's input tensor
     if tokens:
@@ -174,29 +178,29 @@ def decoder_program(n_layers: int, tokens: bool, rope_separate: bool, norm2_sepa
         y = new("y")
         emit("norm", y, res)
         q = new("q")
-        emit("gemm_qkv", q, [y] + scratch(gemm_scratch[0], "ws_qkv"))
+        emit("gemm_qkv", q, [y] + scratch("ws_qkv"))
         if rope_separate:
             emit("rope_q", -1, [q])
             emit("rope_k", -1, [])
         o = new("o")
-        emit("attn", o, [q] + scratch(attn_scratch, "ws_attn"))
+        emit("attn", o, [q] + scratch("ws_attn"))
         h_mid = new("h")
         if norm2_separate:
-            emit("gemm_res", h_mid, [o] + res + scratch(gemm_scratch[1], "ws_o"))
+            emit("gemm_res", h_mid, [o] + res + scratch("ws_o"))
             y2 = new("y")
             emit("norm", y2, [h_mid])
         else:
             y2 = new("y")
-            emit("gemm_res", h_mid, [o] + res + [y2] + scratch(gemm_scratch[1], "ws_o"))
+            emit("gemm_res", h_mid, [o] + res + [y2] + scratch("ws_o"))
         u = new("u")
-        emit("gemm_act", u, [y2] + scratch(gemm_scratch[2], "ws_up"))
+        emit("gemm_act", u, [y2] + scratch("ws_up"))
         h_out = new("h")
-        emit("gemm_res", h_out, [u, h_mid] + scratch(gemm_scratch[3], "ws_down"))
+        emit("gemm_res", h_out, [u, h_mid] + scratch("ws_down"))
         h = h_out
     if tokens:
         yf = new("y")
         emit("norm", yf, [h])
-        emit("gemm", -1, [yf] + scratch(head_scratch, "ws_head"))
+        emit("gemm", -1, [yf] + scratch("ws_head"))
     else:
         emit("norm", -1, [h])
     return program, kinds

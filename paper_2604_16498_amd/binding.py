@@ -50,6 +50,7 @@ class ModelDesc(C.Structure):
 _lib = None
 
 _vp, _i, _f, _sz, _i64 = C.c_void_p, C.c_int, C.c_float, C.c_size_t, C.c_int64
+_ip, _szp = C.POINTER(C.c_int), C.POINTER(C.c_size_t)
 
 # name -> (restype, argtypes); the single list of what include/forge.h declares
 SIGNATURES = {
@@ -69,6 +70,17 @@ SIGNATURES = {
     "forge_decoder_block": (_i, [C.POINTER(BlockDesc), _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]),
     "forge_model_workspace_bytes": (_sz, [C.POINTER(ModelDesc), _i, _i, _i]),
     "forge_model_forward": (_i, [C.POINTER(ModelDesc), _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]),
+    "forge_plan_liveness": (_i, [_i, _ip, _ip, _ip, _i, _ip, _ip]),
+    "forge_plan_dead_after": (_i, [_i, _ip, _i, _ip, _ip]),
+    "forge_plan_linear_scan": (_i, [_i, _ip, _ip, _ip, _ip]),
+    "forge_plan_workspace": (_i, [_i, _ip, _ip, _szp, _szp, _szp, _ip]),
+    "forge_compile_model": (_i, [C.POINTER(ModelDesc), _i, _i, _i, _i, C.POINTER(_vp)]),
+    "forge_compiled_destroy": (None, [_vp]),
+    "forge_compiled_workspace_bytes": (_sz, [_vp]),
+    "forge_compiled_counts": (_i, [_vp, _ip, _ip, _ip, _ip]),
+    "forge_compiled_program": (_i, [_vp, _ip, _ip, _ip, _ip, _szp, _szp]),
+    "forge_compiled_bind": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "forge_compiled_run": (_i, [_vp, _vp]),
 }
 
 
@@ -277,3 +289,104 @@ def forge_model_forward(model: ModelDesc, inp, out, k_cache, v_cache, pos0, work
     _check(lib().forge_model_forward(C.byref(model), _p(inp), _p(out), _p(k_cache), _p(v_cache), B,
                                      q_len, pos0, kv_cap, wp, wb, _stream()), "forge_model_forward")
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# Static buffer plan (host arrays in, host arrays out) and the compiled executor.
+
+
+def _ints(values):
+    return (C.c_int * max(1, len(values)))(*values)
+
+
+def forge_plan_liveness(out_reg: Sequence[int], in_lists: Sequence[Sequence[int]], n_regs: int):
+    """Program = per instruction an output register (-1: none) and the registers it reads.
+    Returns (start, end) lists, -1 for registers never mentioned."""
+    n = len(out_reg)
+    begin, flat = [0], []
+    for ins in in_lists:
+        flat.extend(ins)
+        begin.append(len(flat))
+    start, end = _ints([0] * n_regs), _ints([0] * n_regs)
+    _check(lib().forge_plan_liveness(n, _ints(out_reg), _ints(begin), _ints(flat), n_regs, start, end),
+           "forge_plan_liveness")
+    return list(start)[:n_regs], list(end)[:n_regs]
+
+
+def forge_plan_dead_after(end: Sequence[int], n_instr: int) -> Dict[int, list]:
+    live = sum(1 for e in end if e >= 0)
+    begin, regs = _ints([0] * (n_instr + 1)), _ints([0] * live)
+    _check(lib().forge_plan_dead_after(len(end), _ints(end), n_instr, begin, regs), "forge_plan_dead_after")
+    return {j: list(regs[begin[j]:begin[j + 1]]) for j in range(n_instr) if begin[j + 1] > begin[j]}
+
+
+def forge_plan_linear_scan(start: Sequence[int], end: Sequence[int]):
+    n = len(start)
+    buf, m = _ints([0] * n), C.c_int(0)
+    _check(lib().forge_plan_linear_scan(n, _ints(start), _ints(end), buf, C.byref(m)), "forge_plan_linear_scan")
+    return list(buf)[:n], m.value
+
+
+def forge_plan_workspace(start: Sequence[int], end: Sequence[int], nbytes: Sequence[int]):
+    """Returns (offset per register, total bytes, number of buffers); offset -1 where start < 0."""
+    n = len(start)
+    sizes = (C.c_size_t * max(1, n))(*nbytes)
+    off = (C.c_size_t * max(1, n))()
+    total, m = C.c_size_t(0), C.c_int(0)
+    _check(lib().forge_plan_workspace(n, _ints(start), _ints(end), sizes, off, C.byref(total), C.byref(m)),
+           "forge_plan_workspace")
+    none = C.c_size_t(-1).value
+    return [-1 if o == none else o for o in list(off)[:n]], total.value, m.value
+
+
+class CompiledModel:
+    """Handle of forge_compile_model for one fixed (batch, q_len, pos0, kv_cap).  `bind` records
+    the HIP graph on a non-default stream, `run` replays it.  Keeps the descriptor (and through
+    it nothing else) alive: the caller keeps the weight tensors alive."""
+
+    def __init__(self, model: ModelDesc, batch: int, q_len: int, pos0: int, kv_cap: int):
+        self._h = C.c_void_p(None)
+        self._model = model
+        _check(lib().forge_compile_model(C.byref(model), batch, q_len, pos0, kv_cap, C.byref(self._h)),
+               "forge_compile_model")
+        self._bound = None
+
+    def close(self):
+        if self._h:
+            lib().forge_compiled_destroy(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace_bytes(self) -> int:
+        return lib().forge_compiled_workspace_bytes(self._h)
+
+    def counts(self):
+        """(instructions, registers, register reads, buffers)"""
+        a, b, c, d = C.c_int(0), C.c_int(0), C.c_int(0), C.c_int(0)
+        _check(lib().forge_compiled_counts(self._h, C.byref(a), C.byref(b), C.byref(c), C.byref(d)),
+               "forge_compiled_counts")
+        return a.value, b.value, c.value, d.value
+
+    def program(self):
+        """(ops, out_reg, in_lists, reg_bytes, reg_offset)"""
+        ni, nr, nreads, _ = self.counts()
+        op, out, begin, regs = _ints([0] * ni), _ints([0] * ni), _ints([0] * (ni + 1)), _ints([0] * nreads)
+        nb, off = (C.c_size_t * max(1, nr))(), (C.c_size_t * max(1, nr))()
+        _check(lib().forge_compiled_program(self._h, op, out, begin, regs, nb, off), "forge_compiled_program")
+        ins = [list(regs[begin[j]:begin[j + 1]]) for j in range(ni)]
+        return list(op)[:ni], list(out)[:ni], ins, list(nb)[:nr], list(off)[:nr]
+
+    def bind(self, inp, out, k_cache, v_cache, workspace, stream: "torch.cuda.Stream"):
+        wp, wb = _ws(workspace)
+        _check(lib().forge_compiled_bind(self._h, _p(inp), _p(out), _p(k_cache), _p(v_cache), wp, wb,
+                                         C.c_void_p(stream.cuda_stream)), "forge_compiled_bind")
+        self._bound = (inp, out, k_cache, v_cache, workspace)     # keep the tensors alive
+        return self
+
+    def run(self, stream: "torch.cuda.Stream"):
+        _check(lib().forge_compiled_run(self._h, C.c_void_p(stream.cuda_stream)), "forge_compiled_run")

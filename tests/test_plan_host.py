@@ -1,0 +1,206 @@
+"""Host logic of the static buffer plan, through the C ABI, against the plan oracle: exact
+integer equality on random programs and on the launch lists of compiled decoder stacks.
+No GPU: the plan functions are host code, and compiling a model launches nothing (the weight
+pointers below are made-up aligned addresses that are never dereferenced).
+
+Sec. "Phase 4: IR Analysis & Optimization" (Eq. "liveness", Alg. "Linear-Scan Buffer
+Allocation"), Alg. "FX -> NPUIR Lowering".
+"""
+import ctypes as C
+import random
+
+import pytest
+
+from oracle import plan_oracle as P
+from paper_2604_16498_amd import binding as B
+from test_plan_oracle_pins import random_program
+
+
+def to_lists(iv):
+    return [(-1 if x is None else x[0]) for x in iv], [(-1 if x is None else x[1]) for x in iv]
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_plan_functions_match_the_oracle_on_random_programs(seed):
+    rng = random.Random(300 + seed)
+    prog, n = random_program(rng, rng.randint(1, 80), fan_in=rng.randint(1, 5))
+    n += rng.randint(0, 2)                     # trailing registers nobody mentions
+    iv = P.live_intervals(prog, n)
+    start, end = B.forge_plan_liveness([o for o, _ in prog], [i for _, i in prog], n)
+    assert (start, end) == to_lists(iv)
+    assert B.forge_plan_dead_after(end, len(prog)) == P.dead_after(iv)
+    buf, m = B.forge_plan_linear_scan(start, end)
+    assert (buf, m) == P.linear_scan(iv)
+    sizes = [rng.choice([0, 100, 256, 4096, 5000, 1 << 20]) for _ in range(n)]
+    off, total, nb = B.forge_plan_workspace(start, end, sizes)
+    assert (off, total, nb) == P.workspace_plan(iv, sizes)
+
+
+def test_hand_worked_chain_through_the_abi():
+    n = 7
+    start, end = B.forge_plan_liveness(list(range(n)), [[]] + [[j - 1] for j in range(1, n)], n)
+    assert start == list(range(n)) and end == [j + 1 for j in range(n - 1)] + [n - 1]
+    buf, m = B.forge_plan_linear_scan(start, end)
+    assert m == 2 and buf == [j % 2 for j in range(n)]
+
+
+def test_empty_program():
+    assert B.forge_plan_liveness([], [], 0) == ([], [])
+    assert B.forge_plan_linear_scan([], []) == ([], 0)
+    assert B.forge_plan_workspace([], [], []) == ([], 0, 0)
+    start, end = B.forge_plan_liveness([], [], 3)
+    assert start == [-1] * 3 and end == [-1] * 3
+    assert B.forge_plan_workspace(start, end, [8, 8, 8]) == ([-1] * 3, 0, 0)
+
+
+def test_malformed_programs_are_rejected():
+    l = B.lib()
+    ints = lambda v: (C.c_int * max(1, len(v)))(*v)
+    s, e = ints([0, 0]), ints([0, 0])
+    # register out of range, as output and as input
+    assert l.forge_plan_liveness(1, ints([5]), ints([0, 0]), ints([]), 2, s, e) == 1
+    assert l.forge_plan_liveness(1, ints([0]), ints([0, 1]), ints([2]), 2, s, e) == 1
+    # in_begin not starting at zero / decreasing
+    assert l.forge_plan_liveness(1, ints([0]), ints([1, 1]), ints([0]), 2, s, e) == 1
+    assert l.forge_plan_liveness(2, ints([0, 1]), ints([0, 1, 0]), ints([0]), 2, s, e) == 1
+    # NULL outputs
+    assert l.forge_plan_liveness(1, ints([0]), ints([0, 0]), ints([]), 2, None, e) == 1
+    # an interval that ends before it starts, or starts at -1 but has an end
+    m = C.c_int(0)
+    assert l.forge_plan_linear_scan(1, ints([3]), ints([2]), ints([0]), C.byref(m)) == 1
+    assert l.forge_plan_linear_scan(1, ints([-1]), ints([2]), ints([0]), C.byref(m)) == 1
+    with pytest.raises(B.ForgeError):
+        B.forge_plan_dead_after([4], 2)
+
+
+# ------------------------------------------------------------------ compiled decoder stacks
+
+class Shape:
+    def __init__(self, **kw):
+        self.__dict__.update(kw)
+
+
+def fake_model(shape, n_layers, tokens, dt, vocab=1000, n_pos=512):
+    """Descriptors whose pointers are distinct aligned made-up addresses."""
+    addr = [0x10000]
+
+    def ptr():
+        addr[0] += 0x1000
+        return addr[0]
+
+    layers = []
+    for _ in range(n_layers):
+        d = B.BlockDesc()
+        d.d_model, d.q_heads, d.kv_heads, d.head_dim, d.d_ff = (shape.d_model, shape.q_heads, shape.kv_heads,
+                                                                shape.head_dim, shape.d_ff)
+        d.norm, d.eps, d.mlp_act = B.NORM[shape.norm], 1e-5, B.ACT[shape.mlp_act]
+        d.use_rope, d.rope_base, d.dt = int(shape.use_rope), 10000.0, dt
+        for name in ("norm1_g", "w_qkv", "w_o", "norm2_g", "w_up", "w_down"):
+            setattr(d, name, ptr())
+        layers.append(d)
+    m = B.ModelDesc()
+    arr = (B.BlockDesc * n_layers)(*layers)
+    m._layer_array = arr
+    m.n_layers, m.layers = n_layers, C.cast(arr, C.POINTER(B.BlockDesc))
+    m.vocab, m.n_pos, m.logits_ld = (vocab, n_pos, 0) if tokens else (0, 0, 0)
+    m.wte, m.wpe = (ptr(), ptr()) if tokens else (None, None)
+    m.normf_g, m.normf_b = ptr(), None
+    return m
+
+
+GPT = Shape(d_model=256, q_heads=4, kv_heads=4, head_dim=64, d_ff=1024, norm="layernorm",
+            mlp_act="gelu_tanh", use_rope=False)
+LLAMA = Shape(d_model=512, q_heads=4, kv_heads=2, head_dim=128, d_ff=1408, norm="rmsnorm",
+              mlp_act="swiglu", use_rope=True)
+
+CASES = [
+    # name, shape, layers, tokens, dtype, batch, q_len, pos0, kv_cap
+    ("gpt_prefill_bf16", GPT, 3, True, B.FORGE_BF16, 2, 128, 0, 128),
+    ("gpt_prefill_f32", GPT, 2, True, B.FORGE_F32, 1, 128, 0, 128),
+    ("llama_prefill_bf16", LLAMA, 4, False, B.FORGE_BF16, 1, 256, 0, 256),
+    ("llama_decode_bf16", LLAMA, 4, False, B.FORGE_BF16, 8, 1, 300, 301),
+    ("llama_decode_f32", LLAMA, 2, False, B.FORGE_F32, 8, 1, 40, 64),
+    ("gpt_decode_bf16", GPT, 12, True, B.FORGE_BF16, 4, 1, 100, 128),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_compiled_program_and_plan_match_the_oracle(case):
+    _, shape, L, tokens, dt, batch, q_len, pos0, kv_cap = case
+    model = fake_model(shape, L, tokens, dt)
+    cm = B.CompiledModel(model, batch, q_len, pos0, kv_cap)
+    ops, out_reg, ins, reg_bytes, reg_offset = cm.program()
+    ni, nr, _, nb = cm.counts()
+
+    # which operators the small-row split-K projections absorb (bf16, at most 64 rows)
+    T = batch * q_len
+    small = dt == B.FORGE_BF16 and T <= 64
+    prog, kinds = P.decoder_program(L, tokens, rope_separate=shape.use_rope and not small,
+                                    norm2_separate=not small)
+    assert (ni, nr) == (len(prog), len(kinds))
+    assert ops == [p[0] for p in prog]
+    assert out_reg == [p[1] for p in prog]
+    assert ins == [p[2] for p in prog]
+
+    # byte sizes of the tensor registers, from the shapes
+    es = 2 if dt == B.FORGE_BF16 else 4
+    want = {"h": T * shape.d_model * es, "y": T * shape.d_model * es,
+            "q": T * shape.q_heads * shape.head_dim * es, "o": T * shape.q_heads * shape.head_dim * es,
+            "u": T * shape.d_ff * es}
+    for r, k in enumerate(kinds):
+        if k in want:
+            assert reg_bytes[r] == want[k], (r, k)
+    # scratch registers: what the library's own workspace queries report for that launch
+    act = B.ACT[shape.mlp_act]
+    nqkv = (shape.q_heads + 2 * shape.kv_heads) * shape.head_dim
+    hd = shape.q_heads * shape.head_dim
+    l = B.lib()
+    scratch = {"ws_qkv": l.forge_gemm_workspace_bytes(T, nqkv, shape.d_model, 0, dt),
+               "ws_o": l.forge_gemm_workspace_bytes(T, shape.d_model, hd, 0, dt),
+               "ws_up": l.forge_gemm_workspace_bytes(T, shape.d_ff, shape.d_model, act, dt),
+               "ws_down": l.forge_gemm_workspace_bytes(T, shape.d_model, shape.d_ff, 0, dt),
+               "ws_attn": l.forge_attn_fused_workspace_bytes(batch, shape.q_heads, shape.kv_heads, q_len,
+                                                             pos0 + q_len, shape.head_dim, dt),
+               "ws_head": l.forge_gemm_workspace_bytes(T, 1000, shape.d_model, 0, dt)}
+    for r, k in enumerate(kinds):
+        if k in scratch:
+            assert reg_bytes[r] == scratch[k], (r, k)
+
+    # the plan: oracle's liveness + byte plan over the oracle's program and these sizes
+    iv = P.live_intervals([(o, i) for _, o, i in prog], len(kinds))
+    off, total, bufs = P.workspace_plan(iv, reg_bytes)
+    assert reg_offset == off
+    assert cm.workspace_bytes() == total
+    assert nb == bufs
+    # fewer buffers than registers, and the count does not depend on the depth
+    assert nb < nr
+    cm.close()
+
+
+def test_buffer_count_is_independent_of_depth_and_reduction_grows():
+    rho = []
+    for L in (2, 8, 32):
+        cm = B.CompiledModel(fake_model(GPT, L, True, B.FORGE_BF16), 2, 128, 0, 128)
+        ni, nr, _, nb = cm.counts()
+        rho.append((nb, 1 - nb / nr))
+        cm.close()
+    assert rho[0][0] == rho[1][0] == rho[2][0]
+    assert rho[0][1] < rho[1][1] < rho[2][1]
+
+
+def test_compile_rejects_bad_arguments():
+    l = B.lib()
+    model = fake_model(GPT, 2, True, B.FORGE_BF16)
+    h = C.c_void_p(None)
+    assert l.forge_compile_model(C.byref(model), 0, 128, 0, 128, C.byref(h)) == 1
+    assert l.forge_compile_model(C.byref(model), 1, 128, 8, 128, C.byref(h)) == 1      # past the cache
+    assert l.forge_compile_model(C.byref(model), 1, 128, 0, 1024, None) == 1
+    assert l.forge_compile_model(C.byref(model), 1, 600, 0, 1024, C.byref(h)) == 1     # past n_pos = 512
+    assert not h.value
+    assert l.forge_compiled_run(None, None) == 1
+    cm = B.CompiledModel(model, 1, 128, 0, 128)
+    assert l.forge_compiled_run(cm._h, None) == 1                                        # not bound yet
+    good = C.c_void_p(0x100000)
+    assert l.forge_compiled_bind(cm._h, good, good, good, good, good, 0, good) == 3      # workspace too small
+    assert l.forge_compiled_bind(cm._h, good, good, good, good, good, 1 << 40, None) == 1  # NULL stream
+    cm.close()

@@ -178,14 +178,29 @@ def test_workspace_plan_regions_of_live_registers_never_overlap(seed):
         for b in live:
             if a < b and overlaps(iv[a], iv[b]):
                 assert off[a] + sizes[a] <= off[b] or off[b] + sizes[b] <= off[a], (a, b)
-    # each size group is an independent linear scan: its buffer count is its own max overlap
-    expect = 0
-    for size in set(sizes[r] for r in live):
-        expect += max_alive([iv[r] if sizes[r] == size else None for r in live])
-    assert nb == expect
-    assert total == sum(((size + 255) // 256 * 256) *
-                        max_alive([iv[r] if sizes[r] == size else None for r in live])
-                        for size in set(sizes[r] for r in live))
+    # each group is an independent linear scan: its buffer count is its own max overlap; the
+    # registers living within one instruction form one group sized to the largest of them
+    single = [r for r in live if iv[r][0] == iv[r][1]]
+    multi = [r for r in live if iv[r][0] != iv[r][1]]
+    pad = lambda b: (b + 255) // 256 * 256
+    expect_bufs = max_alive([iv[r] for r in single])
+    expect_total = pad(max([sizes[r] for r in single] or [0])) * expect_bufs
+    for size in set(sizes[r] for r in multi):
+        k = max_alive([iv[r] for r in multi if sizes[r] == size])
+        expect_bufs += k
+        expect_total += pad(size) * k
+    assert nb == expect_bufs
+    assert total == expect_total
+
+
+def test_workspace_plan_hand_worked():
+    # r0 [0,2] 1000 B, r1 [1,1] 64 B (scratch), r2 [2,3] 1000 B, r3 [3,3] 4096 B (scratch), r4 [3,4] 1000 B
+    iv = [(0, 2), (1, 1), (2, 3), (3, 3), (3, 4)]
+    off, total, nb = P.workspace_plan(iv, [1000, 64, 1000, 4096, 1000])
+    # group "1000 B": r0 -> buffer 0, r2 overlaps r0 at index 2 -> buffer 1, r4 starts at 3 after r0
+    # ended at 2 -> buffer 0; stride 1024.  group "single": one buffer of 4096 B after it.
+    assert off == [0, 2048, 1024, 2048, 0]
+    assert (total, nb) == (2048 + 4096, 3)
 
 
 # ------------------------------------------------------------------ the decoder launch list
@@ -193,7 +208,7 @@ def test_workspace_plan_regions_of_live_registers_never_overlap(seed):
 @pytest.mark.parametrize("tokens,rope,norm2", [(True, False, True), (False, True, True), (False, False, False)])
 def test_decoder_program_shape(tokens, rope, norm2):
     L = 3
-    prog, kinds = P.decoder_program(L, tokens, rope, norm2, [False, False, False, False], False, False)
+    prog, kinds = P.decoder_program(L, tokens, rope, norm2)
     per_layer = 6 + (2 if rope else 0) + (1 if norm2 else 0)
     assert len(prog) == L * per_layer + (3 if tokens else 1)
     # every register is written or first mentioned before any later use, numbering is dense
@@ -201,6 +216,8 @@ def test_decoder_program_shape(tokens, rope, norm2):
     assert all(x is not None for x in iv)
     starts = [s for s, _ in iv]
     assert starts == sorted(starts)
+    # scratch areas live inside one instruction only
+    assert all(iv[r][0] == iv[r][1] for r, k in enumerate(kinds) if k.startswith("ws_"))
     # the residual stream of a layer is read twice after it is written: by the next norm and by
     # the next output projection
     buf, m = P.linear_scan(iv)
@@ -212,7 +229,7 @@ def test_decoder_program_shape(tokens, rope, norm2):
 def test_decoder_program_buffer_count_does_not_grow_with_depth():
     counts = []
     for L in (1, 2, 12, 32):
-        prog, kinds = P.decoder_program(L, True, False, True, [False] * 4, False, False)
+        prog, kinds = P.decoder_program(L, True, False, True)
         iv = P.live_intervals([(o, i) for _, o, i in prog], len(kinds))
         counts.append(P.linear_scan(iv)[1])
     assert counts[1] == counts[2] == counts[3]
