@@ -31,6 +31,9 @@ identities; identity-weight and zero-weight special cases; pure-Python brute
 force of every operator and of a whole block on tiny shapes, written in fused
 (online-softmax, epilogue) order; decode step == last row of a longer prefill;
 torch CPU fp64 library routines as special cases.
+Weight-only int8: quantize_int8 / dequantize_int8 (pins: half-step error bound, grid
+weights returned exactly, sign symmetry, idempotence, pure-Python loops); a quantised linear is
+`linear` on the dequantised weight.
 Parity unpinned: the RoPE pairing convention (rotate-half) and the GQA grouping
 order (contiguous groups) are conventions, fixed only by the docstrings below.
 """
@@ -111,6 +114,28 @@ def linear(x, w, b=None):
     if b is not None:
         z = z + _f64(b)
     return z
+
+
+def quantize_int8(w):
+    """Symmetric int8 weights, one scale per output channel (Sec. "Precision Strategy for
+    Llama-3.1-8B": symmetric int8 weight quantisation with 16-bit activations; the paper gives no
+    granularity or rounding, so: per row of the [out, in] weight, no zero point, range -127..127).
+
+    The integer decision is taken in fp32, the precision the kernel takes it in:
+    scale[n] = max_k |w[n, k]| / 127 and q[n, k] = rint(w[n, k] / scale[n]) (ties to even), both
+    as IEEE fp32 divisions.  A row of zeros gets scale 1 and q = 0.  Returns (q int8, scale fp32).
+    """
+    w32 = np.asarray(w, dtype=np.float32)
+    amax = np.max(np.abs(w32), axis=1)
+    scale = np.where(amax > 0, amax / np.float32(127.0), np.float32(1.0)).astype(np.float32)
+    q = np.rint(w32 / scale[:, None])
+    q = np.clip(q, -127, 127).astype(np.int8)
+    return q, scale
+
+
+def dequantize_int8(q, scale):
+    """The weight the quantised linear multiplies by: q[n, k] * scale[n], in fp64."""
+    return q.astype(np.float64) * scale.astype(np.float64)[:, None]
 
 
 def gelu_tanh(x):

@@ -569,3 +569,82 @@ def test_attention_additive_mask():
     s0, s1 = (q1[0, 0, 0] @ k1[0, 0, 0]) * scale + 0.3, (q1[0, 0, 0] @ k1[0, 0, 1]) * scale - 1.1
     p0 = 1 / (1 + math.exp(s1 - s0))
     assert np.abs(O.attention(q1, k1, v1, scale, False, m1)[0, 0] - (p0 * v1[0, 0, 0] + (1 - p0) * v1[0, 0, 1])).max() < 1e-14
+
+
+# ---------------------------------------------------------------------------------------------
+# symmetric per-channel int8 weights (Sec. "Precision Strategy for Llama-3.1-8B")
+
+def test_int8_quantisation_error_is_at_most_half_a_step():
+    rng = np.random.default_rng(8)
+    w = (rng.standard_normal((37, 200)) * 0.02).astype(np.float32)
+    q, s = O.quantize_int8(w)
+    assert q.dtype == np.int8 and s.dtype == np.float32 and s.shape == (37,)
+    assert q.min() >= -127 and q.max() <= 127
+    # every row uses the full range: its largest magnitude maps to +-127
+    assert np.all(np.max(np.abs(q.astype(np.int32)), axis=1) == 127)
+    err = np.abs(O.dequantize_int8(q, s) - w.astype(np.float64))
+    assert np.all(err <= 0.5 * s[:, None].astype(np.float64) * (1 + 1e-6))
+    np.testing.assert_allclose(s, np.max(np.abs(w), axis=1) / 127.0, rtol=1e-7)
+
+
+def test_int8_weights_on_the_grid_come_back_exactly():
+    rng = np.random.default_rng(9)
+    q0 = rng.integers(-127, 128, size=(16, 64)).astype(np.int8)
+    q0[:, 0] = 127                                   # the row maximum defines the scale
+    s0 = (2.0 ** rng.integers(-12, -4, size=16)).astype(np.float32)     # powers of two: exact products
+    w = q0.astype(np.float32) * s0[:, None]
+    q, s = O.quantize_int8(w)
+    np.testing.assert_array_equal(q, q0)
+    np.testing.assert_array_equal(s, s0)
+    # idempotent: quantising the dequantised weight changes nothing
+    q2, s2 = O.quantize_int8(O.dequantize_int8(q, s).astype(np.float32))
+    np.testing.assert_array_equal(q2, q); np.testing.assert_array_equal(s2, s)
+
+
+def test_int8_sign_symmetry_zero_rows_and_ties():
+    rng = np.random.default_rng(10)
+    w = (rng.standard_normal((5, 33))).astype(np.float32)
+    w[2] = 0.0
+    q, s = O.quantize_int8(w)
+    qn, sn = O.quantize_int8(-w)
+    np.testing.assert_array_equal(qn, -q); np.testing.assert_array_equal(sn, s)
+    assert np.all(q[2] == 0) and s[2] == 1.0
+    # ties go to the even integer: with scale 1 (row maximum 127) the values k + 0.5 are exact ties
+    t = np.array([[127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5]], dtype=np.float32)
+    q, s = O.quantize_int8(t)
+    assert s[0] == 1.0
+    np.testing.assert_array_equal(q[0], [127, 0, 2, 2, 0, -2, -2, 126])
+
+
+def test_int8_matches_plain_python_loops():
+    import struct
+    rng = np.random.default_rng(11)
+    w = (rng.standard_normal((4, 9)) * 0.3).astype(np.float32)
+    q, s = O.quantize_int8(w)
+
+    def f32(v):                         # round a Python float to fp32
+        return struct.unpack("f", struct.pack("f", v))[0]
+
+    for n in range(4):
+        amax = max(abs(float(v)) for v in w[n])
+        sc = f32(amax / 127.0)
+        assert sc == float(s[n])
+        for k in range(9):
+            r = f32(float(w[n, k]) / sc)
+            assert int(q[n, k]) == max(-127, min(127, round(r)))      # Python's round: ties to even
+
+
+def test_int8_linear_is_linear_on_the_dequantised_weight_and_close_to_the_original():
+    rng = np.random.default_rng(12)
+    w = (rng.standard_normal((24, 512)) * 0.02).astype(np.float32)
+    x = rng.standard_normal((6, 512)).astype(np.float32)
+    q, s = O.quantize_int8(w)
+    z8 = O.linear(x, O.dequantize_int8(q, s))
+    # factoring the scale out of the sum is the same thing: s[n] * sum_k x q
+    z8b = (x.astype(np.float64) @ q.astype(np.float64).T) * s.astype(np.float64)[None, :]
+    np.testing.assert_allclose(z8, z8b, rtol=1e-12, atol=1e-12)
+    # quantisation noise: uniform in +-s/2 per weight => rms error of a dot product ~ |x| s / sqrt(12)
+    z = O.linear(x, w)
+    bound = np.linalg.norm(x, axis=1)[:, None] * s[None, :] / np.sqrt(12.0)
+    assert np.sqrt(np.mean(((z8 - z) / bound) ** 2)) < 1.3
+    assert np.max(np.abs(z8 - z) / bound) < 5.0
