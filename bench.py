@@ -355,6 +355,42 @@ def main():
         del cws
         torch.cuda.synchronize()
 
+    # ---- the decode step on int8 weights (quantised here by the library's own kernel), outside
+    # the timed region: reported beside the bf16 step, never as `value`
+    w8 = None
+    if args.workload == "c5" and not args.traffic_probe:
+        layers8 = []
+        for w in m["layers"]:
+            d = dict(w)
+            for wn, sn in (("w_qkv", "s_qkv"), ("w_o", "s_o"), ("w_up", "s_up"), ("w_down", "s_down")):
+                d[wn], d[sn] = F.forge_quantize_int8(w[wn])
+            layers8.append(d)
+        descs8 = [F.make_block_desc(wl.block, d) for d in layers8]
+        model8 = F.make_model_desc(descs8, m["mw"], logits_ld=m["logits_ld"])
+        ws8 = F.workspace(F.forge_model_workspace_bytes(model8, wl.batch, wl.seq, m["cap"]))
+
+        def step8():
+            F.forge_model_forward(model8, m["inp"], m["out"], m["kc"], m["vc"], pos0, ws8)
+
+        for _ in range(args.warmup):
+            step8()
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for _ in range(args.steps):
+            step8()
+        torch.cuda.synchronize()
+        ms8 = (time.perf_counter() - c0) * 1e3 / args.steps
+        shb = wl.block
+        wbytes8 = (shb.qkv_out * shb.d_model + shb.d_model * shb.q_heads * shb.head_dim + shb.up_out * shb.d_model
+                   + shb.d_model * shb.d_ff) * wl.layers
+        kvbytes = 2 * wl.batch * shb.kv_heads * (wl.pos0 + wl.seq) * shb.head_dim * 2 * wl.layers
+        w8 = {"ms_per_step": round(ms8, 4), "tokens_per_s": round(wl.batch * wl.seq / (ms8 * 1e-3), 1),
+              "weights": "int8 per-row symmetric, bf16 activations",
+              "algorithmic_gb_per_step": round((wbytes8 + kvbytes) / 1e9, 2),
+              "hbm_gbs": round((wbytes8 + kvbytes) / (ms8 * 1e-3) / 1e9, 1)}
+        del layers8, descs8, model8, ws8
+        torch.cuda.synchronize()
+
     # ---- roofline of the dominant kernel: HIP events on the launch stream around every launch
     # of each plain GEMM of one step (same shapes, same weights), repeated; the group with the
     # largest total time is reported.
@@ -458,6 +494,7 @@ def main():
         "step_frac_of_bf16_peak": round((gemm_fl + attn_fl) / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "latency_ms": latency,
         "compiled": compiled,
+        "int8_weights": w8,
         "attention": attn,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -139,6 +139,29 @@ forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias
                                   void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Weight-only int8 (Sec. "Precision Strategy for Llama-3.1-8B": symmetric int8 weights with
+ * 16-bit activations).  The paper gives no granularity or rounding; taken here: one fp32 scale
+ * per weight row (output channel), no zero point, q in [-127, 127].
+ *
+ * forge_quantize_int8: scale[n] = max_k |w[n,k]| / 127, q[n,k] = rint(w[n,k] / scale[n]) (ties
+ *   to even), both correctly rounded fp32 divisions; a row of zeros gets scale 1.  w [N,K] in
+ *   `dt`, q [N,K] int8, scale [N] fp32, all device pointers (w 16-byte aligned).
+ * forge_gemm_w8: y[M,N] = act(x[M,K] . (wq[N,K] * wscale[N])^T + bias) (+ residual), x, bias,
+ *   residual, y in bf16, fp32 accumulation; the scale multiplies the finished sum (the same
+ *   value as multiplying every weight, one rounding fewer).  Arguments as forge_gemm_bias_gelu
+ *   (SWIGLU: wq [2N,K], wscale [2N]).  K % 128 != 0 -> FORGE_ERR_UNSUPPORTED.  The workspace of
+ *   forge_gemm_w8_workspace_bytes is REQUIRED for every M.  M <= 64 is the tuned case (a decode
+ *   step: the int8 weight is streamed once at half the bytes of bf16); larger M runs 64 rows at
+ *   a time, re-reading the weight for each group.
+ * ------------------------------------------------------------------------------------ */
+forge_status forge_quantize_int8(const void* w, int8_t* q, float* scale, int N, int K,
+                                 forge_dtype dt, void* stream);
+size_t forge_gemm_w8_workspace_bytes(int M, int N, int K, forge_act act);
+forge_status forge_gemm_w8(const void* x, const int8_t* wq, const float* wscale, const void* bias,
+                           const void* residual, void* y, int M, int N, int K, int ldy,
+                           forge_act act, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Fused residual add + normalisation:  h = x (+ delta);  y = Norm(h).
  *
  * x, delta (may be NULL), h_out (may be NULL, may alias x), y: [rows,d].  gamma: [d];
@@ -192,6 +215,11 @@ typedef struct {
   forge_dtype dt;
   const void *norm1_g, *norm1_b, *w_qkv, *b_qkv, *w_o, *b_o;
   const void *norm2_g, *norm2_b, *w_up, *b_up, *w_down, *b_down;
+  /* Weight-only int8 (Sec. "Precision Strategy for Llama-3.1-8B"): all four NULL = weights in
+   * `dt`; all four set = w_qkv, w_o, w_up, w_down are int8 [out, in] with these fp32 per-row
+   * scales (as forge_quantize_int8 writes them); dt must be FORGE_BF16 and d_model, d_ff and
+   * q_heads*head_dim multiples of 128, else FORGE_ERR_UNSUPPORTED. */
+  const float *s_qkv, *s_o, *s_up, *s_down;
 } forge_block_desc;
 
 size_t forge_decoder_block_workspace_bytes(const forge_block_desc* desc, int batch, int q_len,

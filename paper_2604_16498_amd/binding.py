@@ -36,6 +36,7 @@ class BlockDesc(C.Structure):
         ("norm1_g", C.c_void_p), ("norm1_b", C.c_void_p), ("w_qkv", C.c_void_p), ("b_qkv", C.c_void_p),
         ("w_o", C.c_void_p), ("b_o", C.c_void_p), ("norm2_g", C.c_void_p), ("norm2_b", C.c_void_p),
         ("w_up", C.c_void_p), ("b_up", C.c_void_p), ("w_down", C.c_void_p), ("b_down", C.c_void_p),
+        ("s_qkv", C.c_void_p), ("s_o", C.c_void_p), ("s_up", C.c_void_p), ("s_down", C.c_void_p),
     ]
 
 
@@ -63,6 +64,9 @@ SIGNATURES = {
     "forge_gemm_workspace_bytes": (_sz, [_i, _i, _i, _i, _i]),
     "forge_gemm_variant": (C.c_char_p, [_i, _i, _i, _i, _i, _i]),
     "forge_gemm_bias_gelu": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
+    "forge_quantize_int8": (_i, [_vp, _vp, _vp, _i, _i, _i, _vp]),
+    "forge_gemm_w8_workspace_bytes": (_sz, [_i, _i, _i, _i]),
+    "forge_gemm_w8": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
     "forge_residual_norm": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _f, _i, _i, _vp]),
     "forge_rope": (_i, [_vp, _i, _i, _i, _i, _i64, _i64, _i, _i, _f, _i, _vp]),
     "forge_embed": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp]),
@@ -201,6 +205,30 @@ def forge_gemm_bias_gelu(x, w, bias, residual, y, act="gelu_tanh", workspace=Non
     return y
 
 
+def forge_quantize_int8(w):
+    """w [N,K] (bf16 or fp32, GPU) -> (q int8 [N,K], scale fp32 [N])."""
+    N, K = w.shape
+    q = torch.empty(N, K, dtype=torch.int8, device=w.device)
+    scale = torch.empty(N, dtype=torch.float32, device=w.device)
+    _check(lib().forge_quantize_int8(_p(w), _p(q), _p(scale), N, K, _dt(w), _stream()), "forge_quantize_int8")
+    return q, scale
+
+
+def forge_gemm_w8_workspace_bytes(M, N, K, act) -> int:
+    return lib().forge_gemm_w8_workspace_bytes(M, N, K, ACT[act])
+
+
+def forge_gemm_w8(x, wq, wscale, bias, residual, y, act="none", workspace=None, n=None):
+    """y[M,:N] = act(x[M,K] (wq * wscale[:,None])^T + bias) (+ residual); x, y bf16, wq int8."""
+    M, K = x.shape
+    ldy = y.shape[1]
+    N = ldy if n is None else n
+    wp, wb = _ws(workspace)
+    _check(lib().forge_gemm_w8(_p(x), _p(wq), _p(wscale), _p(bias), _p(residual), _p(y), M, N, K, ldy,
+                               ACT[act], wp, wb, _stream()), "forge_gemm_w8")
+    return y
+
+
 def forge_residual_norm(x, delta, gamma, beta, h_out, y, eps=1e-5, kind="layernorm"):
     rows, d = x.shape[0] if x.dim() == 2 else x.numel() // x.shape[-1], x.shape[-1]
     _check(lib().forge_residual_norm(_p(x), _p(delta), _p(gamma), _p(beta), _p(h_out), _p(y), rows, d,
@@ -235,9 +263,10 @@ def make_block_desc(shape, w: Dict[str, Optional[torch.Tensor]]) -> BlockDesc:
     d.mlp_act = ACT[shape.mlp_act]
     d.use_rope = int(shape.use_rope)
     d.rope_base = shape.rope_base
-    d.dt = _dt(w["w_qkv"])
+    # int8 weights (with "s_*" scale vectors in w): the activation dtype is that of the norm gain
+    d.dt = _dt(w["norm1_g"] if w.get("s_qkv") is not None else w["w_qkv"])
     for name in ("norm1_g", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o", "norm2_g", "norm2_b",
-                 "w_up", "b_up", "w_down", "b_down"):
+                 "w_up", "b_up", "w_down", "b_down", "s_qkv", "s_o", "s_up", "s_down"):
         t = w.get(name)
         if t is not None and (not t.is_cuda or not t.is_contiguous()):
             raise ValueError("weight %s must be a contiguous GPU tensor" % name)

@@ -21,10 +21,13 @@ BlockPlan plan_block(const forge_block_desc* d, int batch, int q_len, int kv_cap
   p.o = align_up(T * hd * es, 256);
   p.u = align_up(T * d->d_ff * es, 256);
   p.attn = align_up(attn_ws(batch, d->q_heads, d->kv_heads, q_len, kv_cap, d->head_dim, d->dt), 256);
-  size_t g = gemm_ws((int)T, nqkv, d->d_model, FORGE_ACT_NONE, d->dt);
-  g = g > gemm_ws((int)T, d->d_model, hd, FORGE_ACT_NONE, d->dt) ? g : gemm_ws((int)T, d->d_model, hd, FORGE_ACT_NONE, d->dt);
-  g = g > gemm_ws((int)T, d->d_ff, d->d_model, d->mlp_act, d->dt) ? g : gemm_ws((int)T, d->d_ff, d->d_model, d->mlp_act, d->dt);
-  g = g > gemm_ws((int)T, d->d_model, d->d_ff, FORGE_ACT_NONE, d->dt) ? g : gemm_ws((int)T, d->d_model, d->d_ff, FORGE_ACT_NONE, d->dt);
+  const bool w8 = block_w8(d);
+  size_t g = 0;
+  for (size_t v : {gemm_ws((int)T, nqkv, d->d_model, FORGE_ACT_NONE, d->dt, w8),
+                   gemm_ws((int)T, d->d_model, hd, FORGE_ACT_NONE, d->dt, w8),
+                   gemm_ws((int)T, d->d_ff, d->d_model, d->mlp_act, d->dt, w8),
+                   gemm_ws((int)T, d->d_model, d->d_ff, FORGE_ACT_NONE, d->dt, w8)})
+    g = v > g ? v : g;
   p.gemm = align_up(g, 256);
   p.total = p.y + p.q + p.o + p.u + p.attn + p.gemm;
   return p;
@@ -56,7 +59,7 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
   const bool rope_in_gemm = d->use_rope && gemm_fuses_tail(T, nqkv, d->dt);
   QkvSplit sp = {q, k_cache, v_cache, d->q_heads, d->kv_heads, dh, q_len, kv_cap, pos0,
                  rope_in_gemm ? 1 : 0, d->rope_base};
-  GemmArgs g = {y, d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, 0, FORGE_ACT_NONE, &sp, nullptr, gws, pl.gemm};
+  GemmArgs g = {y, d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, 0, FORGE_ACT_NONE, &sp, nullptr, gws, pl.gemm, d->s_qkv};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
   // 3. rotary embedding of the new q and k rows
@@ -77,7 +80,7 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
   const bool norm_in_gemm = gemm_fuses_tail(T, dm, d->dt);
   NormTail nt = {d->norm2_g, d->norm2_b, y, d->eps, d->norm};
   g = GemmArgs{o, d->w_o, d->b_o, x_in, x_out, T, dm, hd, 0, FORGE_ACT_NONE, nullptr,
-               norm_in_gemm ? &nt : nullptr, gws, pl.gemm};
+               norm_in_gemm ? &nt : nullptr, gws, pl.gemm, d->s_o};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
   // 6. second norm
@@ -86,11 +89,11 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
     if (st != FORGE_OK) return st;
   }
   // 7. MLP up projection + bias + activation (SwiGLU: gate and up in one pass)
-  g = GemmArgs{y, d->w_up, d->b_up, nullptr, u, T, d->d_ff, dm, 0, d->mlp_act, nullptr, nullptr, gws, pl.gemm};
+  g = GemmArgs{y, d->w_up, d->b_up, nullptr, u, T, d->d_ff, dm, 0, d->mlp_act, nullptr, nullptr, gws, pl.gemm, d->s_up};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
   // 8. MLP down projection + bias + residual
-  g = GemmArgs{u, d->w_down, d->b_down, x_out, x_out, T, dm, d->d_ff, 0, FORGE_ACT_NONE, nullptr, nullptr, gws, pl.gemm};
+  g = GemmArgs{u, d->w_down, d->b_down, x_out, x_out, T, dm, d->d_ff, 0, FORGE_ACT_NONE, nullptr, nullptr, gws, pl.gemm, d->s_down};
   return gemm_dispatch(g, d->dt, s);
 }
 
@@ -110,7 +113,7 @@ ModelPlan plan_model(const forge_model_desc* m, int batch, int q_len, int kv_cap
     const size_t b = plan_block(&m->layers[l], batch, q_len, kv_cap).total;
     p.block = b > p.block ? b : p.block;
   }
-  const size_t head = m->wte != nullptr ? align_up(gemm_ws((int)T, m->vocab, d0->d_model, FORGE_ACT_NONE, d0->dt), 256) : 0;
+  const size_t head = m->wte != nullptr ? align_up(gemm_ws((int)T, m->vocab, d0->d_model, FORGE_ACT_NONE, d0->dt, false), 256) : 0;
   p.block = head > p.block ? head : p.block;
   p.total = p.h + p.yf + p.block;
   return p;
@@ -190,7 +193,7 @@ forge_status forge_attn_fused_masked(const void* q, const void* k, const void* v
 
 size_t forge_gemm_workspace_bytes(int M, int N, int K, forge_act act, forge_dtype dt) {
   if (M < 1 || N < 1 || K < 1) return 0;
-  return gemm_ws(M, N, K, act, dt);
+  return gemm_ws(M, N, K, act, dt, false);
 }
 
 const char* forge_gemm_variant(int M, int N, int K, int ldy, forge_act act, forge_dtype dt) {
@@ -209,10 +212,37 @@ forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias
   if (K % (dt == FORGE_BF16 ? 8 : 4) != 0) return FORGE_ERR_UNSUPPORTED;
   if (y == x || y == w) return FORGE_ERR_INVALID_ARG;
   // only the decode-sized bf16 problems cannot run without their partial-sum planes
-  const size_t need = dt == FORGE_BF16 && M <= 64 ? gemm_ws(M, N, K, act, dt) : 0;
+  const size_t need = dt == FORGE_BF16 && M <= 64 ? gemm_ws(M, N, K, act, dt, false) : 0;
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FORGE_ERR_WORKSPACE;
   GemmArgs a = {x, w, bias, residual, y, M, N, K, ldy, act, nullptr, nullptr, workspace, workspace_bytes};
   return gemm_dispatch(a, dt, static_cast<hipStream_t>(stream));
+}
+
+size_t forge_gemm_w8_workspace_bytes(int M, int N, int K, forge_act act) {
+  if (M < 1 || N < 1 || K < 1) return 0;
+  return gemm_ws(M, N, K, act, FORGE_BF16, true);
+}
+
+forge_status forge_gemm_w8(const void* x, const int8_t* wq, const float* wscale, const void* bias,
+                           const void* residual, void* y, int M, int N, int K, int ldy,
+                           forge_act act, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!req(x) || !req(wq) || !req(wscale) || !req(y) || !opt(bias) || !opt(residual) || !req(workspace))
+    return FORGE_ERR_INVALID_ARG;
+  if (M < 1 || N < 1 || K < 1 || ldy < 0 || (ldy > 0 && ldy < N)) return FORGE_ERR_INVALID_ARG;
+  if (act < FORGE_ACT_NONE || act > FORGE_ACT_GELU_ERF) return FORGE_ERR_INVALID_ARG;
+  if (K % 128 != 0) return FORGE_ERR_UNSUPPORTED;
+  if (y == x) return FORGE_ERR_INVALID_ARG;
+  if (workspace_bytes < gemm_ws(M, N, K, act, FORGE_BF16, true)) return FORGE_ERR_WORKSPACE;
+  GemmArgs a = {x, wq, bias, residual, y, M, N, K, ldy, act, nullptr, nullptr, workspace, workspace_bytes, wscale};
+  return gemm_dispatch(a, FORGE_BF16, static_cast<hipStream_t>(stream));
+}
+
+forge_status forge_quantize_int8(const void* w, int8_t* q, float* scale, int N, int K, forge_dtype dt,
+                                 void* stream) {
+  if (!dtype_ok(dt) || !req(w) || q == nullptr || scale == nullptr || (reinterpret_cast<uintptr_t>(scale) & 3u) != 0)
+    return FORGE_ERR_INVALID_ARG;
+  if (N < 1 || K < 1) return FORGE_ERR_INVALID_ARG;
+  return launch_quantize_int8(w, q, scale, N, K, dt, static_cast<hipStream_t>(stream));
 }
 
 forge_status forge_residual_norm(const void* x, const void* delta, const void* gamma,

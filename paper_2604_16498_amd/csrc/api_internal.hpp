@@ -35,9 +35,13 @@ inline size_t attn_ws(int batch, int q_heads, int kv_heads, int q_len, int kv_le
   return 0;
 }
 
-inline size_t gemm_ws(int M, int N, int K, forge_act act, forge_dtype dt) {
+inline size_t gemm_ws(int M, int N, int K, forge_act act, forge_dtype dt, bool w8) {
+  if (w8) return gemm_w8_workspace_bytes(M, N, K, act);
   return dt == FORGE_BF16 ? gemm_bf16_workspace_bytes(M, N, K, act) : gemm_f32_workspace_bytes(M, N, K, act);
 }
+
+// int8 weights: all four scale vectors given (checked by check_block_desc: all or none)
+inline bool block_w8(const forge_block_desc* d) { return d->s_qkv != nullptr; }
 
 inline forge_status gemm_dispatch(const GemmArgs& a, forge_dtype dt, hipStream_t s) {
   return dt == FORGE_BF16 ? launch_gemm_bf16(a, s) : launch_gemm_f32(a, s);
@@ -60,6 +64,15 @@ inline forge_status check_block_desc(const forge_block_desc* d) {
       !opt(d->b_down))
     return FORGE_ERR_INVALID_ARG;
   if (d->use_rope && !(d->rope_base > 1.0f)) return FORGE_ERR_INVALID_ARG;
+  const int n_scales = (d->s_qkv != nullptr) + (d->s_o != nullptr) + (d->s_up != nullptr) + (d->s_down != nullptr);
+  if (n_scales != 0 && n_scales != 4) return FORGE_ERR_INVALID_ARG;
+  if (n_scales == 4) {
+    if (!req(d->s_qkv) || !req(d->s_o) || !req(d->s_up) || !req(d->s_down)) return FORGE_ERR_INVALID_ARG;
+    // int8 weights go with bf16 activations and whole 128-element slabs of every reduction
+    if (d->dt != FORGE_BF16 || d->d_model % 128 != 0 || d->d_ff % 128 != 0 ||
+        (d->q_heads * d->head_dim) % 128 != 0)
+      return FORGE_ERR_UNSUPPORTED;
+  }
   return FORGE_OK;
 }
 

@@ -154,6 +154,7 @@ struct GemmArgs {
   const NormTail* norm;   // NULL: none; honoured only where gemm_fuses_tail() says so
   void* workspace;
   size_t workspace_bytes;
+  const float* w_scale;   // non-NULL: w is int8 [N, K] (bf16 activations only), one scale per weight row
 };
 
 forge_status launch_gemm_f32(const GemmArgs& a, hipStream_t s);
@@ -163,6 +164,10 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
 // (GemmArgs::norm).  Otherwise both fields are ignored and the caller launches those operators.
 bool gemm_fuses_tail(int M, int N, forge_dtype dt);
 size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act);
+size_t gemm_w8_workspace_bytes(int M, int N, int K, forge_act act);   // required, any M
+// Symmetric int8 quantisation of a weight, one scale per row.
+forge_status launch_quantize_int8(const void* w, int8_t* q, float* scale, int N, int K, forge_dtype dt,
+                                  hipStream_t s);
 const char* gemm_bf16_variant(int M, int N, int K, int ldy, forge_act act);
 size_t gemm_f32_workspace_bytes(int M, int N, int K, forge_act act);
 

@@ -95,11 +95,12 @@ void lower(forge_compiled* c) {
     const int hd = d.q_heads * d.head_dim, nqkv = (d.q_heads + 2 * d.kv_heads) * d.head_dim;
     const bool rope_in_gemm = d.use_rope && gemm_fuses_tail(Ti, nqkv, dt);
     const bool norm_in_gemm = gemm_fuses_tail(Ti, dm, dt);
+    const bool w8 = block_w8(&d);
 
     const int y = lo.new_reg(h_bytes);
     lo.emit({FORGE_OP_NORM, l, 0, y, h, REG_NONE, REG_NONE, REG_NONE}, {h});
     const int q = lo.new_reg(T * hd * es);
-    int ws = lo.new_reg(gemm_ws(Ti, nqkv, dm, FORGE_ACT_NONE, dt));
+    int ws = lo.new_reg(gemm_ws(Ti, nqkv, dm, FORGE_ACT_NONE, dt, w8));
     lo.emit({FORGE_OP_GEMM_QKV, l, rope_in_gemm ? 1 : 0, q, y, REG_NONE, REG_NONE, ws}, {y, ws});
     if (d.use_rope && !rope_in_gemm) {
       lo.emit({FORGE_OP_ROPE_Q, l, 0, REG_NONE, q, REG_NONE, REG_NONE, REG_NONE}, {q});
@@ -112,26 +113,26 @@ void lower(forge_compiled* c) {
     int y2;
     if (norm_in_gemm) {
       y2 = lo.new_reg(h_bytes);
-      ws = lo.new_reg(gemm_ws(Ti, dm, hd, FORGE_ACT_NONE, dt));
+      ws = lo.new_reg(gemm_ws(Ti, dm, hd, FORGE_ACT_NONE, dt, w8));
       lo.emit({FORGE_OP_GEMM_RES, l, 0, h_mid, o, h, y2, ws}, {o, h, y2, ws});
     } else {
-      ws = lo.new_reg(gemm_ws(Ti, dm, hd, FORGE_ACT_NONE, dt));
+      ws = lo.new_reg(gemm_ws(Ti, dm, hd, FORGE_ACT_NONE, dt, w8));
       lo.emit({FORGE_OP_GEMM_RES, l, 0, h_mid, o, h, REG_NONE, ws}, {o, h, ws});
       y2 = lo.new_reg(h_bytes);
       lo.emit({FORGE_OP_NORM, l, 1, y2, h_mid, REG_NONE, REG_NONE, REG_NONE}, {h_mid});
     }
     const int u = lo.new_reg(T * d.d_ff * es);
-    ws = lo.new_reg(gemm_ws(Ti, d.d_ff, dm, d.mlp_act, dt));
+    ws = lo.new_reg(gemm_ws(Ti, d.d_ff, dm, d.mlp_act, dt, w8));
     lo.emit({FORGE_OP_GEMM_ACT, l, 0, u, y2, REG_NONE, REG_NONE, ws}, {y2, ws});
     const int h_out = lo.new_reg(h_bytes);
-    ws = lo.new_reg(gemm_ws(Ti, dm, d.d_ff, FORGE_ACT_NONE, dt));
+    ws = lo.new_reg(gemm_ws(Ti, dm, d.d_ff, FORGE_ACT_NONE, dt, w8));
     lo.emit({FORGE_OP_GEMM_RES, l, 1, h_out, u, h_mid, REG_NONE, ws}, {u, h_mid, ws});
     h = h_out;
   }
   if (tokens) {
     const int yf = lo.new_reg(h_bytes);
     lo.emit({FORGE_OP_NORM, -1, 2, yf, h, REG_NONE, REG_NONE, REG_NONE}, {h});
-    const int ws = lo.new_reg(gemm_ws(Ti, m.vocab, dm, FORGE_ACT_NONE, dt));
+    const int ws = lo.new_reg(gemm_ws(Ti, m.vocab, dm, FORGE_ACT_NONE, dt, false));
     lo.emit({FORGE_OP_GEMM, -1, 0, REG_EXT, yf, REG_NONE, REG_NONE, ws}, {yf, ws});
   } else {
     lo.emit({FORGE_OP_NORM, -1, 2, REG_EXT, h, REG_NONE, REG_NONE, REG_NONE}, {h});
@@ -184,7 +185,7 @@ forge_status run_program(const forge_compiled* c, hipStream_t s) {
         QkvSplit sp = {out(I.out), kc, vc, d->q_heads, d->kv_heads, dh, c->q_len, c->kv_cap, c->pos0,
                        I.which, d->rope_base};
         GemmArgs g = {in(I.x), d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, 0, FORGE_ACT_NONE,
-                      &sp, nullptr, out(I.ws), bytes(I.ws)};
+                      &sp, nullptr, out(I.ws), bytes(I.ws), d->s_qkv};
         st = gemm_dispatch(g, dt, s);
         break;
       }
@@ -208,13 +209,13 @@ forge_status run_program(const forge_compiled* c, hipStream_t s) {
         const bool o_proj = I.which == 0;
         GemmArgs g = {in(I.x), o_proj ? d->w_o : d->w_down, o_proj ? d->b_o : d->b_down, in(I.res),
                       out(I.out), T, dm, o_proj ? hd : d->d_ff, 0, FORGE_ACT_NONE, nullptr,
-                      I.aux >= 0 ? &nt : nullptr, out(I.ws), bytes(I.ws)};
+                      I.aux >= 0 ? &nt : nullptr, out(I.ws), bytes(I.ws), o_proj ? d->s_o : d->s_down};
         st = gemm_dispatch(g, dt, s);
         break;
       }
       case FORGE_OP_GEMM_ACT: {
         GemmArgs g = {in(I.x), d->w_up, d->b_up, nullptr, out(I.out), T, d->d_ff, dm, 0, d->mlp_act,
-                      nullptr, nullptr, out(I.ws), bytes(I.ws)};
+                      nullptr, nullptr, out(I.ws), bytes(I.ws), d->s_up};
         st = gemm_dispatch(g, dt, s);
         break;
       }

@@ -78,6 +78,9 @@ struct GemmParams {
   size_t part_bytes;  // bytes behind part
   QkvSplit sp;
   NormTail nt;        // nt.y_norm == nullptr: none
+  const int8_t* w8;     // weight-only int8 (M <= 64 streaming path): [N, K] bytes; w is NULL then
+  const float* wscale;  // one scale per weight row, applied to the reduced sum before the bias
+  int row0;             // row of the whole problem that row 0 of this launch is (head split only)
 };
 
 enum Mode { MODE_PLAIN = 0, MODE_QKV = 1, MODE_SPLITK = 2 };
@@ -233,7 +236,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_generic_kernel(GemmPara
         if (SWIGLU) val = silu_f(val) * (acc[i][SWIGLU ? j + TN / 2 : j][v] + bv2);
         else val = apply_act<ACT>(val);
         if (MODE == MODE_QKV) {
-          *split_dst_bf16(p.sp, m, n) = (bf16)val;
+          *split_dst_bf16(p.sp, p.row0 + m, n) = (bf16)val;
         } else {
           if (p.residual != nullptr) val += (float)p.residual[(int64_t)m * p.ldy + n];
           p.y[(int64_t)m * p.ldy + n] = (bf16)val;
@@ -647,24 +650,40 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
 // (1 : 2 at BN = 128, 1 : 4 at BN = 256); the launcher picks the widest block that still gives
 // every CU work.  All waves multiply: a wave owns 32 weight rows and both halves of the
 // activation rows.  Output: fp32 partial sums D[n, m] for the fixed-order split-K reduce.
-template <int BN>
+template <int BN, bool W8>
 struct WStream {
   static constexpr int NWV = BN >= 256 ? 8 : 4;            // waves per block
   static constexpr int NG = BN / 32;                       // 32-row groups of weight rows
   static constexpr int TMW = NG >= NWV ? 2 : 1;            // activation halves per wave
   static constexpr int NWL = NWV / 2, NXL = NWV - NWL;     // loader waves per stream
+  // A weight row of a slab is 128 bytes either way: 64 bf16 or 128 int8 elements.  What an
+  // iteration costs is mostly fixed (barrier, issue of the loads), so the int8 variant keeps the
+  // weight bytes per iteration and doubles the k extent instead of halving the bytes.
+  static constexpr int BKS = W8 ? 2 * BK : BK;             // k elements per slab
   static constexpr int LPW_W = BN / 8 / NWL;               // wave-wide 1 KB loads per loader and slab
-  static constexpr int LPW_X = 8 / NXL;
-  static constexpr int WS_W = BN == 128 ? 3 : 4;           // weight ring depth
-  static constexpr int WS_X = 3;                           // activation ring depth
-  static constexpr int SLAB_W = BN * BK * 2, SLAB_X = 64 * BK * 2;
+  static constexpr int SLAB_W = BN * 128, SLAB_X = 64 * BKS * 2;
+  static constexpr int LPW_X = SLAB_X / 1024 / NXL;
+  static constexpr int WS_W = (BN == 128 || W8) ? 3 : 4;   // weight ring depth
+  static constexpr int WS_X = W8 ? 2 : 3;                  // activation ring depth
   static constexpr int SMEM = WS_W * SLAB_W + WS_X * SLAB_X;
   static_assert(NG * (2 / TMW) == NWV, "waves cover the block tile");
+  static_assert(SMEM <= 160 * 1024, "fits the LDS of a CU");
 };
 
-template <int BN>
-__global__ __launch_bounds__(WStream<BN>::NWV * 64) void gemm_bf16_wstream_kernel(GemmParams p) {
-  using C = WStream<BN>;
+// 8 signed bytes -> 8 bf16 (exact: |q| <= 127 has 7 significant bits)
+__device__ inline bf16x8 cvt_i8x8_bf16(u32x2 v) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int b = (int)(int8_t)((v[e >> 2] >> (8 * (e & 3))) & 0xff);
+    r[e] = (bf16)(float)b;
+  }
+  return r;
+}
+
+template <int BN, bool W8>
+__global__ __launch_bounds__((WStream<BN, W8>::NWV * 64)) void gemm_bf16_wstream_kernel(GemmParams p) {
+  using C = WStream<BN, W8>;
   extern __shared__ __attribute__((aligned(16))) char smem[];   // [W ring | x ring]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -677,17 +696,20 @@ __global__ __launch_bounds__(WStream<BN>::NWV * 64) void gemm_bf16_wstream_kerne
 
   // loader plan: wave-wide load i of loader lw fills slab rows (i * loaders + lw)*8 .. +8
   constexpr int LPW_MAX = C::LPW_W > C::LPW_X ? C::LPW_W : C::LPW_X;
-  const bf16* src[LPW_MAX];
+  // (the activation slab of the int8 variant is two 64 x 64 sub-slabs, 8 loads each)
+  constexpr int WESZ = W8 ? 1 : 2;     // bytes per weight element
+  const char* src[LPW_MAX];
 #pragma unroll
   for (int i = 0; i < LPW_MAX; ++i) {
-    const int r = (i * (w_loader ? C::NWL : C::NXL) + lw) * 8 + (lane >> 3);
+    const int j = i * (w_loader ? C::NWL : C::NXL) + lw;     // which 1 KB piece of the slab
+    const int r = (w_loader ? j : j % 8) * 8 + (lane >> 3);
     const int c = (lane & 7) ^ ((r >> 1) & 7);
-    src[i] = w_loader ? p.w + (int64_t)min(n0 + r, N - 1) * K + c * 8
-                      : p.x + (int64_t)min(r, M - 1) * K + c * 8;
+    src[i] = w_loader ? (W8 ? (const char*)p.w8 : (const char*)p.w) + ((int64_t)min(n0 + r, N - 1) * K * WESZ + c * 16)
+                      : (const char*)(p.x + (int64_t)min(r, M - 1) * K + (j / 8) * BK + c * 8);
   }
   const int k_begin = blockIdx.y * p.k_per_split;
   const int k_end = min(K, k_begin + p.k_per_split);
-  const int nk = (k_end - k_begin) / BK;
+  const int nk = (k_end - k_begin) / C::BKS;
   char* const xring = smem + C::WS_W * C::SLAB_W;
 
   // slab kt of this wave's stream; past the end the last slab is re-loaded into its own buffer
@@ -699,13 +721,13 @@ __global__ __launch_bounds__(WStream<BN>::NWV * 64) void gemm_bf16_wstream_kerne
       char* dst = smem + (k % C::WS_W) * C::SLAB_W;
 #pragma unroll
       for (int i = 0; i < C::LPW_W; ++i)
-        __builtin_amdgcn_global_load_lds((const void*)(src[i] + k_begin + k * BK),
+        __builtin_amdgcn_global_load_lds((const void*)(src[i] + (int64_t)(k_begin + k * C::BKS) * WESZ),
                                          (lds_void*)(dst + (i * C::NWL + lw) * 1024), 16, 0, 0);
     } else {
       char* dst = xring + (k % C::WS_X) * C::SLAB_X;
 #pragma unroll
       for (int i = 0; i < C::LPW_X; ++i)
-        __builtin_amdgcn_global_load_lds((const void*)(src[i] + k_begin + k * BK),
+        __builtin_amdgcn_global_load_lds((const void*)(src[i] + (int64_t)(k_begin + k * C::BKS) * 2),
                                          (lds_void*)(dst + (i * C::NXL + lw) * 1024), 16, 0, 0);
     }
   };
@@ -733,12 +755,18 @@ __global__ __launch_bounds__(WStream<BN>::NWV * 64) void gemm_bf16_wstream_kerne
     const char* sw = smem + (kt % C::WS_W) * C::SLAB_W;
     const char* sx = xring + (kt % C::WS_X) * C::SLAB_X;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const bf16x8 wf = *reinterpret_cast<const bf16x8*>(sw + lds_chunk_off(wn * 32 + fr, 2 * ks + fh));
+    for (int ks = 0; ks < C::BKS / 16; ++ks) {
+      // 16 k of a weight row: one 32-byte run (bf16) or one 16-byte chunk (int8), halves by fh
+      bf16x8 wf;
+      if constexpr (W8)
+        wf = cvt_i8x8_bf16(*reinterpret_cast<const u32x2*>(sw + lds_chunk_off(wn * 32 + fr, ks) + fh * 8));
+      else
+        wf = *reinterpret_cast<const bf16x8*>(sw + lds_chunk_off(wn * 32 + fr, 2 * ks + fh));
+      const char* sxs = sx + (ks / 4) * (64 * BK * 2);      // 64-k sub-slab of the activations
 #pragma unroll
       for (int t = 0; t < C::TMW; ++t) {
         const int mh = C::TMW == 2 ? t : wm0;
-        const bf16x8 xf = *reinterpret_cast<const bf16x8*>(sx + lds_chunk_off(mh * 32 + fr, 2 * ks + fh));
+        const bf16x8 xf = *reinterpret_cast<const bf16x8*>(sxs + lds_chunk_off(mh * 32 + fr, 2 * (ks % 4) + fh));
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[t], 0, 0, 0);
       }
     }
@@ -816,13 +844,17 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p, int sp
     const int n = n0 + e;
     if (n >= N) break;
     float av = a[e], uv = u[e];
+    if (p.wscale != nullptr) {
+      av *= p.wscale[n];
+      if (SWIGLU) uv *= p.wscale[n + N];
+    }
     if (p.bias != nullptr) {
       av += (float)p.bias[n];
       if (SWIGLU) uv += (float)p.bias[n + N];
     }
     float val = SWIGLU ? silu_f(av) * uv : apply_act<ACT>(av);
     if (QKV) {
-      *split_dst_bf16(p.sp, m, n) = (bf16)val;
+      *split_dst_bf16(p.sp, p.row0 + m, n) = (bf16)val;
     } else {
       if (p.residual != nullptr) val += (float)p.residual[(int64_t)m * p.ldy + n];
       p.y[(int64_t)m * p.ldy + n] = (bf16)val;
@@ -865,6 +897,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_qkv_rope_kernel(GemmParams 
   for (int z = 0; z < splits; ++z) {       // split order, independent 128-bit loads
     lo += *reinterpret_cast<const floatx4*>(src + z * plane + n_lo);
     hi += *reinterpret_cast<const floatx4*>(src + z * plane + n_hi);
+  }
+  if (p.wscale != nullptr) {
+    lo *= *reinterpret_cast<const floatx4*>(p.wscale + n_lo);
+    hi *= *reinterpret_cast<const floatx4*>(p.wscale + n_hi);
   }
   if (p.bias != nullptr) {
 #pragma unroll
@@ -923,6 +959,7 @@ __global__ __launch_bounds__(NORM_TAIL_THREADS) void splitk_reduce_norm_kernel(G
     floatx4 a = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 8
     for (int z = 0; z < splits; ++z) a += *reinterpret_cast<const floatx4*>(src + z * plane + n);
+    if (p.wscale != nullptr) a *= *reinterpret_cast<const floatx4*>(p.wscale + n);
     const int64_t at = (int64_t)m * p.ldy + n;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -1052,10 +1089,10 @@ struct SkinnyPlan {
   int splits;
   int k_per_split;
 };
-inline SkinnyPlan plan_skinny(int N, int K, forge_act act) {
+inline SkinnyPlan plan_skinny(int N, int K, forge_act act, int bk = BK) {
   SkinnyPlan sp;
   sp.ncols = act == FORGE_ACT_SWIGLU ? 2 * N : N;
-  const int slabs = ceil_div(K, BK);
+  const int slabs = ceil_div(K, bk);
   const int cus = compute_units();
   // About one block per CU measured best on the decode shapes: more blocks mean more k ranges,
   // i.e. more partial-sum traffic and a longer reduce.  256-row blocks (fewest activation re-reads
@@ -1063,17 +1100,17 @@ inline SkinnyPlan plan_skinny(int N, int K, forge_act act) {
   sp.bn = ceil_div(sp.ncols, 256) * 8 >= cus * 3 ? 256 : 128;
   const int tiles = ceil_div(sp.ncols, sp.bn);
   int want = (cus + tiles / 2) / tiles;              // k ranges for ~ one block per CU
-  want = max(1, min(want, min(8, slabs / 8)));       // at least 8 slabs of work per block
+  want = max(1, min(want, min(8, slabs * bk / 512)));   // at least 512 k of work per block
   const int per = ceil_div(slabs, want);
   sp.splits = ceil_div(slabs, per);
-  sp.k_per_split = per * BK;
+  sp.k_per_split = per * bk;
   return sp;
 }
 
-template <int BN>
+template <int BN, bool W8>
 forge_status launch_wstream(const GemmParams& q, int splits, hipStream_t s) {
-  using C = WStream<BN>;
-  auto kern = gemm_bf16_wstream_kernel<BN>;
+  using C = WStream<BN, W8>;
+  auto kern = gemm_bf16_wstream_kernel<BN, W8>;
   static bool configured = false;
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1117,13 +1154,14 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
     default: break;
   }
   // skinny: raw split-K GEMM over all weight rows into fp32 partials, then reduce + epilogue
-  const SkinnyPlan sk = plan_skinny(p.N, p.K, (forge_act)ACT);
+  const SkinnyPlan sk = plan_skinny(p.N, p.K, (forge_act)ACT, p.w8 != nullptr ? 2 * BK : BK);
   GemmParams q = p;
   q.N = sk.ncols;
   q.k_per_split = sk.k_per_split;
   forge_status st;
   if (v == V_SKINNY_FAST) {
-    st = sk.bn == 256 ? launch_wstream<256>(q, sk.splits, s) : launch_wstream<128>(q, sk.splits, s);
+    if (q.w8 != nullptr) st = sk.bn == 256 ? launch_wstream<256, true>(q, sk.splits, s) : launch_wstream<128, true>(q, sk.splits, s);
+    else st = sk.bn == 256 ? launch_wstream<256, false>(q, sk.splits, s) : launch_wstream<128, false>(q, sk.splits, s);
   } else {
     st = launch_generic<64, 64, 2, 2, FORGE_ACT_NONE, MODE_SPLITK>(q, sk.splits, s);
   }
@@ -1152,6 +1190,11 @@ size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act) {
   }
   const SkinnyPlan sk = plan_skinny(N, K, act);
   return (size_t)sk.splits * M * sk.ncols * sizeof(float);
+}
+
+size_t gemm_w8_workspace_bytes(int M, int N, int K, forge_act act) {
+  const SkinnyPlan sk = plan_skinny(N, K, act, 2 * BK);
+  return (size_t)sk.splits * (M < 64 ? M : 64) * sk.ncols * sizeof(float);
 }
 
 bool gemm_fuses_tail(int M, int N, forge_dtype dt) {
@@ -1184,8 +1227,10 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   p.part = (float*)a.workspace;
   p.part_bytes = a.workspace != nullptr ? a.workspace_bytes : 0;
   p.splits = 1;
+  const bool w8 = a.w_scale != nullptr;
   // the decode path needs its partial-sum planes; the k split of larger problems is optional
-  const size_t need = a.M <= 64 ? gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act) : 0;
+  const size_t need = w8 ? gemm_w8_workspace_bytes(a.M, a.N, a.K, a.act)
+                         : (a.M <= 64 ? gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act) : 0);
   if (need > a.workspace_bytes || (need > 0 && a.workspace == nullptr)) return FORGE_ERR_WORKSPACE;
   const bool tails = gemm_fuses_tail(a.M, a.N, FORGE_BF16);
   if (a.norm != nullptr && tails && a.split == nullptr && a.act == FORGE_ACT_NONE) {
@@ -1196,17 +1241,40 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
     if (a.act != FORGE_ACT_NONE || a.residual != nullptr) return FORGE_ERR_UNSUPPORTED;
     p.sp = *a.split;
     if (!tails) p.sp.rope = 0;
-    return launch_act<FORGE_ACT_NONE, MODE_QKV>(p, s);
   }
-  switch (a.act) {
-    case FORGE_ACT_NONE: return launch_act<FORGE_ACT_NONE, MODE_PLAIN>(p, s);
-    case FORGE_ACT_GELU_TANH: return launch_act<FORGE_ACT_GELU_TANH, MODE_PLAIN>(p, s);
-    case FORGE_ACT_RELU: return launch_act<FORGE_ACT_RELU, MODE_PLAIN>(p, s);
-    case FORGE_ACT_SILU: return launch_act<FORGE_ACT_SILU, MODE_PLAIN>(p, s);
-    case FORGE_ACT_SWIGLU: return launch_act<FORGE_ACT_SWIGLU, MODE_PLAIN>(p, s);
-    case FORGE_ACT_GELU_ERF: return launch_act<FORGE_ACT_GELU_ERF, MODE_PLAIN>(p, s);
-    default: return FORGE_ERR_INVALID_ARG;
+  auto dispatch = [&](const GemmParams& q) -> forge_status {
+    if (a.split != nullptr) return launch_act<FORGE_ACT_NONE, MODE_QKV>(q, s);
+    switch (a.act) {
+      case FORGE_ACT_NONE: return launch_act<FORGE_ACT_NONE, MODE_PLAIN>(q, s);
+      case FORGE_ACT_GELU_TANH: return launch_act<FORGE_ACT_GELU_TANH, MODE_PLAIN>(q, s);
+      case FORGE_ACT_RELU: return launch_act<FORGE_ACT_RELU, MODE_PLAIN>(q, s);
+      case FORGE_ACT_SILU: return launch_act<FORGE_ACT_SILU, MODE_PLAIN>(q, s);
+      case FORGE_ACT_SWIGLU: return launch_act<FORGE_ACT_SWIGLU, MODE_PLAIN>(q, s);
+      case FORGE_ACT_GELU_ERF: return launch_act<FORGE_ACT_GELU_ERF, MODE_PLAIN>(q, s);
+      default: return FORGE_ERR_INVALID_ARG;
+    }
+  };
+  if (!w8) return dispatch(p);
+
+  // Weight-only int8: only the streaming kernel reads such weights.  At most 64 rows go through
+  // it as they are; more rows go 64 at a time (the weight is streamed once per 64 rows: correct,
+  // not tuned - int8 weights are meant for the decode step).
+  if (a.K % (2 * BK) != 0) return FORGE_ERR_UNSUPPORTED;
+  p.w = nullptr;
+  p.w8 = (const int8_t*)a.w;
+  p.wscale = a.w_scale;
+  if (a.M <= 64) return dispatch(p);
+  for (int m0 = 0; m0 < a.M; m0 += 64) {
+    GemmParams q = p;
+    q.M = min(64, a.M - m0);
+    q.row0 = m0;
+    q.x = p.x + (int64_t)m0 * p.K;
+    if (p.y != nullptr) q.y = p.y + (int64_t)m0 * p.ldy;
+    if (p.residual != nullptr) q.residual = p.residual + (int64_t)m0 * p.ldy;
+    const forge_status st = dispatch(q);
+    if (st != FORGE_OK) return st;
   }
+  return FORGE_OK;
 }
 
 }  // namespace forge

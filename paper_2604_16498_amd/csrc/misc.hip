@@ -1,5 +1,5 @@
-// Rotary position embedding (in place) and token + position embedding.  Both are HBM-bound
-// elementwise kernels with 128-bit accesses.
+// Rotary position embedding (in place), token + position embedding, and the one-time int8
+// quantisation of a weight.  HBM-bound elementwise kernels.
 #include "common.hpp"
 
 namespace forge {
@@ -76,7 +76,42 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
   Vec8<T>::store(h + t * d + c * 8, a);
 }
 
+// Symmetric int8 quantisation with one scale per weight row (Sec. "Precision Strategy for
+// Llama-3.1-8B": symmetric int8 weights, 16-bit activations).  One block per row: the row maximum
+// of |w|, scale = max / 127 and q = rint(w / scale), both as correctly rounded fp32 divisions
+// (the precision the integer decision is defined in), clipped to [-127, 127].  A row of zeros
+// gets scale 1.
+template <typename T>
+__global__ __launch_bounds__(256) void quantize_int8_kernel(const T* __restrict__ w, int8_t* __restrict__ q,
+                                                            float* __restrict__ scale, int K) {
+  __shared__ float red[4];
+  const int n = blockIdx.x;
+  const T* row = w + (int64_t)n * K;
+  float amax = 0.f;
+  for (int k = threadIdx.x; k < K; k += 256) amax = fmaxf(amax, fabsf((float)row[k]));
+  amax = wave_max(amax);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = amax;
+  __syncthreads();
+  amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  const float sc = amax > 0.f ? __fdiv_rn(amax, 127.0f) : 1.0f;
+  if (threadIdx.x == 0) scale[n] = sc;
+  int8_t* out = q + (int64_t)n * K;
+  for (int k = threadIdx.x; k < K; k += 256) {
+    const float r = rintf(__fdiv_rn((float)row[k], sc));
+    out[k] = (int8_t)(int)fminf(fmaxf(r, -127.f), 127.f);
+  }
+}
+
 }  // namespace
+
+forge_status launch_quantize_int8(const void* w, int8_t* q, float* scale, int N, int K, forge_dtype dt,
+                                  hipStream_t s) {
+  if (dt == FORGE_BF16)
+    quantize_int8_kernel<bf16><<<N, 256, 0, s>>>((const bf16*)w, q, scale, K);
+  else
+    quantize_int8_kernel<float><<<N, 256, 0, s>>>((const float*)w, q, scale, K);
+  return launch_status();
+}
 
 forge_status launch_rope(void* x, int batch, int heads, int n_rows, int head_dim,
                          int64_t batch_stride, int64_t head_stride, int row0, int pos0, float base,
