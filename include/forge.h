@@ -257,6 +257,37 @@ forge_status forge_model_forward(const forge_model_desc* model, const void* inpu
                                  int kv_cap, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Decode step with per-sequence lengths (the generation loop of the paper's language-modelling
+ * workload, Sec. "Datasets": a prompt, then one token at a time; here for a batch whose sequences
+ * have different lengths).  q_len is 1.  seq_pos: DEVICE int32 [batch]; sequence b has seq_pos[b]
+ * cached positions and its new token sits at position seq_pos[b]: its k and v go to cache row
+ * seq_pos[b], RoPE / the learned position embedding use seq_pos[b], and its query attends to
+ * rows [0, seq_pos[b]].  max_pos: HOST upper bound of seq_pos (max_pos < kv_cap; it sizes
+ * launches and workspace, as pos0 does in the calls above).  The kernels clamp every entry to
+ * [0, max_pos], so a bad entry gives a wrong result for that sequence, never an access outside
+ * the cache.  Because the positions live in device memory the same launch list serves every
+ * step: advance seq_pos on the device and launch again (forge_compiled_bind_decode records it
+ * once for a whole generation, for positions up to the max_pos the handle was compiled with as
+ * pos0).  Workspace: forge_attn_fused_workspace_bytes(.., q_len 1, kv_len max_pos + 1, ..),
+ * forge_decoder_block_workspace_bytes / forge_model_workspace_bytes(.., q_len 1, kv_cap).
+ * Other arguments, layouts and errors as forge_attn_fused (causal), forge_decoder_block and
+ * forge_model_forward.
+ * ------------------------------------------------------------------------------------ */
+forge_status forge_attn_decode_varlen(const void* q, const void* k, const void* v, void* out,
+                                      const int32_t* seq_pos, int batch, int q_heads, int kv_heads,
+                                      int max_pos, int head_dim, int64_t kv_batch_stride,
+                                      int64_t kv_head_stride, float scale, forge_dtype dt,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+forge_status forge_decoder_block_decode(const forge_block_desc* desc, const void* x_in, void* x_out,
+                                        void* k_cache, void* v_cache, const int32_t* seq_pos,
+                                        int batch, int max_pos, int kv_cap, void* workspace,
+                                        size_t workspace_bytes, void* stream);
+forge_status forge_model_decode(const forge_model_desc* model, const void* input, void* output,
+                                void* k_cache, void* v_cache, const int32_t* seq_pos, int batch,
+                                int max_pos, int kv_cap, void* workspace, size_t workspace_bytes,
+                                void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Static buffer plan of a flat instruction list (Sec. "Phase 4: IR Analysis & Optimization").
  * HOST functions on HOST arrays; they never touch the GPU.
  * A program has n_instr instructions over registers 0..n_regs-1: instruction j writes
@@ -338,6 +369,11 @@ forge_status forge_compiled_program(const forge_compiled* c, int* op, int* out_r
 forge_status forge_compiled_bind(forge_compiled* c, const void* input, void* output, void* k_cache,
                                  void* v_cache, void* workspace, size_t workspace_bytes,
                                  void* stream);
+/* as forge_compiled_bind for a handle compiled with q_len 1, with per-sequence positions: the
+ * handle's pos0 is the max_pos of forge_model_decode */
+forge_status forge_compiled_bind_decode(forge_compiled* c, const void* input, void* output,
+                                        void* k_cache, void* v_cache, const int32_t* seq_pos,
+                                        void* workspace, size_t workspace_bytes, void* stream);
 forge_status forge_compiled_run(forge_compiled* c, void* stream);
 
 #ifdef __cplusplus

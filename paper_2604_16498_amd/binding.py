@@ -74,6 +74,10 @@ SIGNATURES = {
     "forge_decoder_block": (_i, [C.POINTER(BlockDesc), _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]),
     "forge_model_workspace_bytes": (_sz, [C.POINTER(ModelDesc), _i, _i, _i]),
     "forge_model_forward": (_i, [C.POINTER(ModelDesc), _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]),
+    "forge_attn_decode_varlen": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _vp, _sz, _vp]),
+    "forge_decoder_block_decode": (_i, [C.POINTER(BlockDesc), _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _sz, _vp]),
+    "forge_model_decode": (_i, [C.POINTER(ModelDesc), _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _sz, _vp]),
+    "forge_compiled_bind_decode": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "forge_plan_liveness": (_i, [_i, _ip, _ip, _ip, _i, _ip, _ip]),
     "forge_plan_dead_after": (_i, [_i, _ip, _i, _ip, _ip]),
     "forge_plan_linear_scan": (_i, [_i, _ip, _ip, _ip, _ip]),
@@ -321,6 +325,44 @@ def forge_model_forward(model: ModelDesc, inp, out, k_cache, v_cache, pos0, work
 
 
 # ---------------------------------------------------------------------------------------------
+# Decode step with per-sequence positions (seq_pos: int32 GPU tensor [B]).
+
+
+def forge_attn_decode_varlen(q, k, v, out, seq_pos, max_pos, scale=None, workspace=None):
+    """q [B,Hq,1,dh]; k, v [B,Hkv,cap,dh]; out [B,1,Hq*dh]; sequence b attends rows [0, seq_pos[b]]."""
+    B, Hq, _, dh = q.shape
+    Hkv, cap = k.shape[1], k.shape[2]
+    scale = dh ** -0.5 if scale is None else scale
+    wp, wb = _ws(workspace)
+    assert seq_pos.dtype == torch.int32 and seq_pos.numel() == B
+    _check(lib().forge_attn_decode_varlen(_p(q), _p(k), _p(v), _p(out), _p(seq_pos), B, Hq, Hkv, max_pos, dh,
+                                          Hkv * cap * dh, cap * dh, scale, _dt(q), wp, wb, _stream()),
+           "forge_attn_decode_varlen")
+    return out
+
+
+def forge_decoder_block_decode(desc: BlockDesc, x_in, x_out, k_cache, v_cache, seq_pos, max_pos, workspace):
+    B = x_in.shape[0]
+    kv_cap = k_cache.shape[2]
+    wp, wb = _ws(workspace)
+    assert seq_pos.dtype == torch.int32 and seq_pos.numel() == B
+    _check(lib().forge_decoder_block_decode(C.byref(desc), _p(x_in), _p(x_out), _p(k_cache), _p(v_cache),
+                                            _p(seq_pos), B, max_pos, kv_cap, wp, wb, _stream()),
+           "forge_decoder_block_decode")
+    return x_out
+
+
+def forge_model_decode(model: ModelDesc, inp, out, k_cache, v_cache, seq_pos, max_pos, workspace):
+    B = inp.shape[0]
+    kv_cap = k_cache.shape[3]
+    wp, wb = _ws(workspace)
+    assert seq_pos.dtype == torch.int32 and seq_pos.numel() == B
+    _check(lib().forge_model_decode(C.byref(model), _p(inp), _p(out), _p(k_cache), _p(v_cache), _p(seq_pos), B,
+                                    max_pos, kv_cap, wp, wb, _stream()), "forge_model_decode")
+    return out
+
+
+# ---------------------------------------------------------------------------------------------
 # Static buffer plan (host arrays in, host arrays out) and the compiled executor.
 
 
@@ -415,6 +457,13 @@ class CompiledModel:
         _check(lib().forge_compiled_bind(self._h, _p(inp), _p(out), _p(k_cache), _p(v_cache), wp, wb,
                                          C.c_void_p(stream.cuda_stream)), "forge_compiled_bind")
         self._bound = (inp, out, k_cache, v_cache, workspace)     # keep the tensors alive
+        return self
+
+    def bind_decode(self, inp, out, k_cache, v_cache, seq_pos, workspace, stream: "torch.cuda.Stream"):
+        wp, wb = _ws(workspace)
+        _check(lib().forge_compiled_bind_decode(self._h, _p(inp), _p(out), _p(k_cache), _p(v_cache), _p(seq_pos),
+                                                wp, wb, C.c_void_p(stream.cuda_stream)), "forge_compiled_bind_decode")
+        self._bound = (inp, out, k_cache, v_cache, seq_pos, workspace)
         return self
 
     def run(self, stream: "torch.cuda.Stream"):

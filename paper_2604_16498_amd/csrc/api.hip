@@ -34,9 +34,11 @@ BlockPlan plan_block(const forge_block_desc* d, int batch, int q_len, int kv_cap
 }
 
 // the launch list of one layer; all arguments already validated
+// seq_pos (device, [batch], or NULL): per-sequence positions of a decode step (q_len == 1); pos0 is
+// then the largest position the caller vouches for
 forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out, void* k_cache,
                        void* v_cache, int batch, int q_len, int pos0, int kv_cap, void* workspace,
-                       hipStream_t s) {
+                       hipStream_t s, const int* seq_pos = nullptr) {
   const BlockPlan pl = plan_block(d, batch, q_len, kv_cap);
   Carver cv(workspace);
   void* y = cv.take(pl.y);
@@ -58,21 +60,22 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
   // (a decode-sized QKV projection rotates q and k in its own reduce step)
   const bool rope_in_gemm = d->use_rope && gemm_fuses_tail(T, nqkv, d->dt);
   QkvSplit sp = {q, k_cache, v_cache, d->q_heads, d->kv_heads, dh, q_len, kv_cap, pos0,
-                 rope_in_gemm ? 1 : 0, d->rope_base};
+                 rope_in_gemm ? 1 : 0, d->rope_base, seq_pos};
   GemmArgs g = {y, d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, 0, FORGE_ACT_NONE, &sp, nullptr, gws, pl.gemm, d->s_qkv};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
   // 3. rotary embedding of the new q and k rows
   if (d->use_rope && !rope_in_gemm) {
     st = launch_rope(q, batch, d->q_heads, q_len, dh, (int64_t)d->q_heads * q_len * dh,
-                     (int64_t)q_len * dh, 0, pos0, d->rope_base, d->dt, s);
+                     (int64_t)q_len * dh, 0, pos0, d->rope_base, d->dt, s, seq_pos, false);
     if (st != FORGE_OK) return st;
-    st = launch_rope(k_cache, batch, d->kv_heads, q_len, dh, kv_bs, kv_hs, pos0, pos0, d->rope_base, d->dt, s);
+    st = launch_rope(k_cache, batch, d->kv_heads, q_len, dh, kv_bs, kv_hs, pos0, pos0, d->rope_base, d->dt, s,
+                     seq_pos, true);
     if (st != FORGE_OK) return st;
   }
   // 4. fused causal attention over cache rows [0, pos0 + q_len)
   AttnArgs at = {q, k_cache, v_cache, o, batch, d->q_heads, d->kv_heads, q_len, pos0 + q_len, dh,
-                 kv_bs, kv_hs, 1.0f / sqrtf((float)dh), 1, aws, pl.attn, nullptr, 0, 0};
+                 kv_bs, kv_hs, 1.0f / sqrtf((float)dh), 1, aws, pl.attn, nullptr, 0, 0, seq_pos};
   st = attn_dispatch(at, d->dt, s);
   if (st != FORGE_OK) return st;
   // 5. output projection + bias + residual
@@ -307,9 +310,10 @@ size_t forge_model_workspace_bytes(const forge_model_desc* model, int batch, int
   return plan_model(model, batch, q_len, kv_cap).total;
 }
 
-forge_status forge_model_forward(const forge_model_desc* model, const void* input, void* output,
-                                 void* k_cache, void* v_cache, int batch, int q_len, int pos0,
-                                 int kv_cap, void* workspace, size_t workspace_bytes, void* stream) {
+static forge_status model_forward(const forge_model_desc* model, const void* input, void* output,
+                                  void* k_cache, void* v_cache, int batch, int q_len, int pos0,
+                                  int kv_cap, void* workspace, size_t workspace_bytes, void* stream,
+                                  const int* seq_pos) {
   forge_status st = check_model(model);
   if (st != FORGE_OK) return st;
   if (input == nullptr || !req(output) || !req(k_cache) || !req(v_cache) || !req(workspace))
@@ -333,13 +337,14 @@ forge_status forge_model_forward(const forge_model_desc* model, const void* inpu
   const void* x = input;
   if (tokens) {
     st = launch_embed(static_cast<const int32_t*>(input), model->wte, model->wpe, h, batch, q_len,
-                      dm, model->vocab, model->n_pos, pos0, dt, s);
+                      dm, model->vocab, model->n_pos, pos0, dt, s, seq_pos);
     if (st != FORGE_OK) return st;
     x = h;
   }
   for (int l = 0; l < model->n_layers; ++l) {
     st = run_block(&model->layers[l], x, h, static_cast<char*>(k_cache) + l * layer_kv_bytes,
-                   static_cast<char*>(v_cache) + l * layer_kv_bytes, batch, q_len, pos0, kv_cap, bws, s);
+                   static_cast<char*>(v_cache) + l * layer_kv_bytes, batch, q_len, pos0, kv_cap, bws, s,
+                   seq_pos);
     if (st != FORGE_OK) return st;
     x = h;
   }
@@ -350,6 +355,62 @@ forge_status forge_model_forward(const forge_model_desc* model, const void* inpu
   GemmArgs g = {yf, model->wte, nullptr, nullptr, output, T, model->vocab, dm, model->logits_ld, FORGE_ACT_NONE,
                 nullptr, nullptr, bws, pl.block};
   return gemm_dispatch(g, dt, s);
+}
+
+forge_status forge_model_forward(const forge_model_desc* model, const void* input, void* output,
+                                 void* k_cache, void* v_cache, int batch, int q_len, int pos0,
+                                 int kv_cap, void* workspace, size_t workspace_bytes, void* stream) {
+  return model_forward(model, input, output, k_cache, v_cache, batch, q_len, pos0, kv_cap, workspace,
+                       workspace_bytes, stream, nullptr);
+}
+
+static bool seq_pos_ok(const int32_t* seq_pos) {
+  return seq_pos != nullptr && (reinterpret_cast<uintptr_t>(seq_pos) & 3u) == 0;
+}
+
+forge_status forge_attn_decode_varlen(const void* q, const void* k, const void* v, void* out,
+                                      const int32_t* seq_pos, int batch, int q_heads, int kv_heads,
+                                      int max_pos, int head_dim, int64_t kv_batch_stride,
+                                      int64_t kv_head_stride, float scale, forge_dtype dt,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+  if (!dtype_ok(dt) || !req(q) || !req(k) || !req(v) || !req(out) || !opt(workspace) || !seq_pos_ok(seq_pos))
+    return FORGE_ERR_INVALID_ARG;
+  if (batch < 1 || q_heads < 1 || kv_heads < 1 || max_pos < 0 || max_pos == INT32_MAX) return FORGE_ERR_INVALID_ARG;
+  if (q_heads % kv_heads != 0) return FORGE_ERR_INVALID_ARG;
+  if (head_dim != 64 && head_dim != 128) return FORGE_ERR_UNSUPPORTED;
+  const int kv_len = max_pos + 1;
+  if (kv_head_stride < (int64_t)kv_len * head_dim || kv_batch_stride < kv_head_stride * kv_heads)
+    return FORGE_ERR_INVALID_ARG;
+  if (kv_head_stride % 8 != 0 || kv_batch_stride % 8 != 0) return FORGE_ERR_INVALID_ARG;
+  if (out == q || out == k || out == v) return FORGE_ERR_INVALID_ARG;
+  const size_t need = attn_ws(batch, q_heads, kv_heads, 1, kv_len, head_dim, dt);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FORGE_ERR_WORKSPACE;
+  AttnArgs a = {q, k, v, out, batch, q_heads, kv_heads, 1, kv_len, head_dim,
+                kv_batch_stride, kv_head_stride, scale, 1, workspace, workspace_bytes, nullptr, 0, 0, seq_pos};
+  return attn_dispatch(a, dt, static_cast<hipStream_t>(stream));
+}
+
+forge_status forge_decoder_block_decode(const forge_block_desc* desc, const void* x_in, void* x_out,
+                                        void* k_cache, void* v_cache, const int32_t* seq_pos,
+                                        int batch, int max_pos, int kv_cap, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+  forge_status st = check_block_desc(desc);
+  if (st != FORGE_OK) return st;
+  if (!req(x_in) || !req(x_out) || !req(k_cache) || !req(v_cache) || !req(workspace) || !seq_pos_ok(seq_pos))
+    return FORGE_ERR_INVALID_ARG;
+  if (batch < 1 || max_pos < 0 || max_pos >= kv_cap) return FORGE_ERR_INVALID_ARG;
+  if (workspace_bytes < plan_block(desc, batch, 1, kv_cap).total) return FORGE_ERR_WORKSPACE;
+  return run_block(desc, x_in, x_out, k_cache, v_cache, batch, 1, max_pos, kv_cap, workspace,
+                   static_cast<hipStream_t>(stream), seq_pos);
+}
+
+forge_status forge_model_decode(const forge_model_desc* model, const void* input, void* output,
+                                void* k_cache, void* v_cache, const int32_t* seq_pos, int batch,
+                                int max_pos, int kv_cap, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  if (!seq_pos_ok(seq_pos)) return FORGE_ERR_INVALID_ARG;
+  return model_forward(model, input, output, k_cache, v_cache, batch, 1, max_pos, kv_cap, workspace,
+                       workspace_bytes, stream, seq_pos);
 }
 
 }  // extern "C"

@@ -41,6 +41,7 @@ struct DecParams {
   int q_heads, kv_heads, kv_len, splits;
   int64_t kv_bs, kv_hs;
   float scale_log2e;
+  const int* kv_pos;   // per-sequence: rows [0, kv_pos[b]] (clamped to kv_len - 1); NULL: kv_len rows
 };
 
 // Lanes of one wave exchange data through LDS: the hardware runs a wave's LDS instructions in
@@ -74,8 +75,11 @@ __global__ __launch_bounds__(NWAVES * 64, 3) void attn_decode_kernel(DecParams p
   const bf16* kb = p.k + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
   const bf16* vb = p.v + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
   const int row0 = split * CHUNK + wave * WROWS;
-  const int row_end = min(p.kv_len, (split + 1) * CHUNK);
-  const int last = p.kv_len - 1;
+  // a split that lies wholly past the end of a short sequence writes a neutral partial
+  // (maximum -1e30, sum 0), which the combine weighs with exactly 0
+  const int kv_len = p.kv_pos != nullptr ? min(max(p.kv_pos[b], 0), p.kv_len - 1) + 1 : p.kv_len;
+  const int row_end = min(kv_len, (split + 1) * CHUNK);
+  const int last = kv_len - 1;
 
   // q as the MFMA B operand: lane = (head, chunk 4j + kg); heads >= G are zero columns
   bf16x8 qf[NJ];
@@ -268,6 +272,7 @@ forge_status launch_dg(const AttnArgs& a, hipStream_t s) {
   p.kv_bs = a.kv_batch_stride;
   p.kv_hs = a.kv_head_stride;
   p.scale_log2e = a.scale * 1.4426950408889634f;
+  p.kv_pos = a.kv_pos;
   if (p.splits > 64) return FORGE_ERR_UNSUPPORTED;   // the combine holds one split per lane
   attn_decode_kernel<DH, G><<<dim3(p.splits, a.kv_heads, a.batch), NWAVES * 64, 0, s>>>(p);
   if (hipGetLastError() != hipSuccess) return FORGE_ERR_HIP;

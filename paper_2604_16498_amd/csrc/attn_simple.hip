@@ -14,7 +14,7 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(
     const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
     T* __restrict__ out, int batch, int q_heads, int kv_heads, int q_len, int kv_len,
     int64_t kv_bs, int64_t kv_hs, float scale, int causal, const float* __restrict__ mask,
-    int64_t mask_bs, int64_t mask_hs) {
+    int64_t mask_bs, int64_t mask_hs, const int* __restrict__ kv_pos) {
   constexpr int NO = DH / 64;
   __shared__ __attribute__((aligned(16))) float qs[4][DH];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -33,6 +33,8 @@ __global__ __launch_bounds__(256) void attn_simple_kernel(
   for (int t = 0; t < NO; ++t) qs[wave][lane + 64 * t] = to_f32<T>(qrow[lane + 64 * t]);
   __syncthreads();
 
+  // per-sequence length (decode step of a generation loop): rows [0, kv_pos[b]] plus the new ones
+  if (kv_pos != nullptr) kv_len = min(max(kv_pos[b], 0) + q_len, kv_len);
   const int limit = causal ? i + (kv_len - q_len) + 1 : kv_len;   // keys [0, limit)
   const float* mrow = mask == nullptr ? nullptr : mask + b * mask_bs + h * mask_hs + (int64_t)i * kv_len;
   float m = -1e30f, l = 0.f, acc[NO];      // finite start: a chunk that is masked out entirely stays 0
@@ -85,12 +87,12 @@ forge_status launch_t(const AttnArgs& a, hipStream_t s) {
     attn_simple_kernel<T, 64><<<grid, block, 0, s>>>(
         (const T*)a.q, (const T*)a.k, (const T*)a.v, (T*)a.out, a.batch, a.q_heads, a.kv_heads,
         a.q_len, a.kv_len, a.kv_batch_stride, a.kv_head_stride, a.scale, a.causal, a.mask,
-        a.mask_batch_stride, a.mask_head_stride);
+        a.mask_batch_stride, a.mask_head_stride, a.kv_pos);
   else if (a.head_dim == 128)
     attn_simple_kernel<T, 128><<<grid, block, 0, s>>>(
         (const T*)a.q, (const T*)a.k, (const T*)a.v, (T*)a.out, a.batch, a.q_heads, a.kv_heads,
         a.q_len, a.kv_len, a.kv_batch_stride, a.kv_head_stride, a.scale, a.causal, a.mask,
-        a.mask_batch_stride, a.mask_head_stride);
+        a.mask_batch_stride, a.mask_head_stride, a.kv_pos);
   else
     return FORGE_ERR_UNSUPPORTED;
   return launch_status();

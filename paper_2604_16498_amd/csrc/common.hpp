@@ -129,7 +129,15 @@ struct QkvSplit {
   int q_heads, kv_heads, head_dim, q_len, kv_cap, pos0;
   int rope;         // the GEMM rotates the new q and k rows itself (only where gemm_fuses_tail() says so)
   float rope_base;
+  // Per-sequence positions (decode step of a generation loop, q_len == 1): device array [B];
+  // sequence b writes cache row pos[b] and rotates by pos[b].  pos0 is then the largest position
+  // the caller vouches for: values are clamped to [0, pos0] so a bad entry cannot leave the cache.
+  const int* pos;
 };
+
+__device__ inline int seq_position(const int* pos, int b, int pos0) {
+  return pos != nullptr ? min(max(pos[b], 0), pos0) : pos0;
+}
 
 // Optional tail of a GEMM with a residual: y_norm = Norm(y) of the rows just produced, from the
 // fp32 values before y is rounded (the contract of the residual + norm operator).
@@ -184,6 +192,9 @@ struct AttnArgs {
   size_t workspace_bytes;
   const float* mask;                 // additive fp32 [*, *, q_len, kv_len], NULL: none
   int64_t mask_batch_stride, mask_head_stride;   // elements; 0 broadcasts
+  // Per-sequence lengths (q_len == 1, no mask): device array [B]; sequence b attends to rows
+  // [0, kv_pos[b]] (clamped to kv_len - 1); kv_len is then the upper bound that sizes the launch.
+  const int* kv_pos;
 };
 
 forge_status launch_attn_f32(const AttnArgs& a, hipStream_t s);
@@ -195,11 +206,13 @@ size_t attn_decode_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_
 forge_status launch_residual_norm(const void* x, const void* delta, const void* gamma,
                                   const void* beta, void* h_out, void* y, int rows, int d,
                                   float eps, forge_norm kind, forge_dtype dt, hipStream_t s);
+// pos (device, [batch], or NULL): per-sequence position instead of pos0 (then pos0 is the clamp);
+// rows_at_pos: the rows to rotate start at row pos[b] of each head (a KV cache) instead of row0.
 forge_status launch_rope(void* x, int batch, int heads, int n_rows, int head_dim,
                          int64_t batch_stride, int64_t head_stride, int row0, int pos0, float base,
-                         forge_dtype dt, hipStream_t s);
+                         forge_dtype dt, hipStream_t s, const int* pos = nullptr, bool rows_at_pos = false);
 forge_status launch_embed(const int32_t* ids, const void* wte, const void* wpe, void* h, int batch,
                           int seq, int d, int vocab, int n_pos, int pos0, forge_dtype dt,
-                          hipStream_t s);
+                          hipStream_t s, const int* pos = nullptr);
 
 }  // namespace forge

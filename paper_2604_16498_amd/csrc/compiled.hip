@@ -50,6 +50,7 @@ struct forge_compiled {
   void* k_cache = nullptr;
   void* v_cache = nullptr;
   char* workspace = nullptr;
+  const int* seq_pos = nullptr;   // per-sequence positions of a decode step (device), or NULL
   hipGraph_t graph = nullptr;
   hipGraphExec_t exec = nullptr;
 };
@@ -173,7 +174,7 @@ forge_status run_program(const forge_compiled* c, hipStream_t s) {
     switch (I.op) {
       case FORGE_OP_EMBED:
         st = launch_embed(static_cast<const int32_t*>(c->input), m.wte, m.wpe, out(I.out), c->batch,
-                          c->q_len, dm, m.vocab, m.n_pos, c->pos0, dt, s);
+                          c->q_len, dm, m.vocab, m.n_pos, c->pos0, dt, s, c->seq_pos);
         break;
       case FORGE_OP_NORM: {
         const void* g = I.which == 0 ? d->norm1_g : (I.which == 1 ? d->norm2_g : m.normf_g);
@@ -183,7 +184,7 @@ forge_status run_program(const forge_compiled* c, hipStream_t s) {
       }
       case FORGE_OP_GEMM_QKV: {
         QkvSplit sp = {out(I.out), kc, vc, d->q_heads, d->kv_heads, dh, c->q_len, c->kv_cap, c->pos0,
-                       I.which, d->rope_base};
+                       I.which, d->rope_base, c->seq_pos};
         GemmArgs g = {in(I.x), d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, 0, FORGE_ACT_NONE,
                       &sp, nullptr, out(I.ws), bytes(I.ws), d->s_qkv};
         st = gemm_dispatch(g, dt, s);
@@ -191,16 +192,16 @@ forge_status run_program(const forge_compiled* c, hipStream_t s) {
       }
       case FORGE_OP_ROPE_Q:
         st = launch_rope(out(I.x), c->batch, d->q_heads, c->q_len, dh, (int64_t)d->q_heads * c->q_len * dh,
-                         (int64_t)c->q_len * dh, 0, c->pos0, d->rope_base, dt, s);
+                         (int64_t)c->q_len * dh, 0, c->pos0, d->rope_base, dt, s, c->seq_pos, false);
         break;
       case FORGE_OP_ROPE_K:
         st = launch_rope(kc, c->batch, d->kv_heads, c->q_len, dh, kv_bs, kv_hs, c->pos0, c->pos0,
-                         d->rope_base, dt, s);
+                         d->rope_base, dt, s, c->seq_pos, true);
         break;
       case FORGE_OP_ATTN: {
         AttnArgs at = {in(I.x), kc, vc, out(I.out), c->batch, d->q_heads, d->kv_heads, c->q_len,
                        c->pos0 + c->q_len, dh, kv_bs, kv_hs, 1.0f / sqrtf((float)dh), 1,
-                       out(I.ws), bytes(I.ws), nullptr, 0, 0};
+                       out(I.ws), bytes(I.ws), nullptr, 0, 0, c->seq_pos};
         st = attn_dispatch(at, dt, s);
         break;
       }
@@ -306,9 +307,9 @@ forge_status forge_compiled_program(const forge_compiled* c, int* op, int* out_r
   return FORGE_OK;
 }
 
-forge_status forge_compiled_bind(forge_compiled* c, const void* input, void* output, void* k_cache,
-                                 void* v_cache, void* workspace, size_t workspace_bytes,
-                                 void* stream) {
+static forge_status bind(forge_compiled* c, const void* input, void* output, void* k_cache,
+                         void* v_cache, void* workspace, size_t workspace_bytes, void* stream,
+                         const int* seq_pos) {
   if (c == nullptr) return FORGE_ERR_INVALID_ARG;
   if (input == nullptr || !req(output) || !req(k_cache) || !req(v_cache) || !req(workspace))
     return FORGE_ERR_INVALID_ARG;
@@ -321,6 +322,7 @@ forge_status forge_compiled_bind(forge_compiled* c, const void* input, void* out
   c->k_cache = k_cache;
   c->v_cache = v_cache;
   c->workspace = static_cast<char*>(workspace);
+  c->seq_pos = seq_pos;
   hipStream_t s = static_cast<hipStream_t>(stream);
   // one plain pass first: it settles the one-time kernel attributes outside the recording and
   // reports a launch that cannot run as an ordinary status
@@ -342,6 +344,20 @@ forge_status forge_compiled_bind(forge_compiled* c, const void* input, void* out
     return FORGE_ERR_HIP;
   }
   return FORGE_OK;
+}
+
+forge_status forge_compiled_bind(forge_compiled* c, const void* input, void* output, void* k_cache,
+                                 void* v_cache, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+  return bind(c, input, output, k_cache, v_cache, workspace, workspace_bytes, stream, nullptr);
+}
+
+forge_status forge_compiled_bind_decode(forge_compiled* c, const void* input, void* output,
+                                        void* k_cache, void* v_cache, const int32_t* seq_pos,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  if (c == nullptr || c->q_len != 1) return FORGE_ERR_INVALID_ARG;
+  if (seq_pos == nullptr || (reinterpret_cast<uintptr_t>(seq_pos) & 3u) != 0) return FORGE_ERR_INVALID_ARG;
+  return bind(c, input, output, k_cache, v_cache, workspace, workspace_bytes, stream, seq_pos);
 }
 
 forge_status forge_compiled_run(forge_compiled* c, void* stream) {

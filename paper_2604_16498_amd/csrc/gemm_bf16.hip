@@ -60,7 +60,7 @@ __device__ inline bf16* split_dst_bf16(const QkvSplit& sp, int m, int n) {
   const int nn = is_k ? n - nq : n - nq - nk;
   const int h = nn / dh;
   bf16* basep = (bf16*)(is_k ? sp.k_cache : sp.v_cache);
-  return basep + (((int64_t)b * sp.kv_heads + h) * sp.kv_cap + sp.pos0 + s) * dh + nn % dh;
+  return basep + (((int64_t)b * sp.kv_heads + h) * sp.kv_cap + seq_position(sp.pos, b, sp.pos0) + s) * dh + nn % dh;
 }
 
 struct GemmParams {
@@ -421,7 +421,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
       const int d = nn - h * dh;
       if (is_q) return (bf16*)p.sp.q + (((int64_t)sb_ * p.sp.q_heads + h) * p.sp.q_len + ss_) * dh + d;
       return (bf16*)(is_k ? p.sp.k_cache : p.sp.v_cache) +
-             (((int64_t)sb_ * p.sp.kv_heads + h) * p.sp.kv_cap + p.sp.pos0 + ss_) * dh + d;
+             (((int64_t)sb_ * p.sp.kv_heads + h) * p.sp.kv_cap + seq_position(p.sp.pos, sb_, p.sp.pos0) + ss_) * dh + d;
     }
     return p.y + (int64_t)(m0_ + row) * p.ldy + n;
   };
@@ -907,7 +907,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_qkv_rope_kernel(GemmParams 
     for (int e = 0; e < 4; ++e) { lo[e] += (float)p.bias[n_lo + e]; hi[e] += (float)p.bias[n_hi + e]; }
   }
   if (hg < p.sp.q_heads + p.sp.kv_heads) {   // q and k heads rotate, v heads do not
-    const double pos = (double)(p.sp.pos0 + m % p.sp.q_len);
+    const double pos = (double)(seq_position(p.sp.pos, (p.row0 + m) / p.sp.q_len, p.sp.pos0) + (p.row0 + m) % p.sp.q_len);
     const double l2b = log2((double)p.sp.rope_base);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -922,8 +922,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_qkv_rope_kernel(GemmParams 
   u32x2 plo, phi;
   plo[0] = pack_bf2(lo[0], lo[1]); plo[1] = pack_bf2(lo[2], lo[3]);
   phi[0] = pack_bf2(hi[0], hi[1]); phi[1] = pack_bf2(hi[2], hi[3]);
-  *reinterpret_cast<u32x2*>(split_dst_bf16(p.sp, m, n_lo)) = plo;   // 4 columns stay inside a head half
-  *reinterpret_cast<u32x2*>(split_dst_bf16(p.sp, m, n_hi)) = phi;
+  *reinterpret_cast<u32x2*>(split_dst_bf16(p.sp, p.row0 + m, n_lo)) = plo;   // 4 columns stay inside a head half
+  *reinterpret_cast<u32x2*>(split_dst_bf16(p.sp, p.row0 + m, n_hi)) = phi;
 }
 
 // Split-K second stage of a projection with residual, followed by the normalisation of the

@@ -33,7 +33,7 @@ __device__ inline void* split_dst(const QkvSplit& sp, int m, int n, size_t esz) 
   const int nn = is_k ? n - nq : n - nq - nk;
   const int h = nn / dh;
   char* basep = (char*)(is_k ? sp.k_cache : sp.v_cache);
-  return basep + ((((int64_t)b * sp.kv_heads + h) * sp.kv_cap + sp.pos0 + s) * dh + nn % dh) * esz;
+  return basep + ((((int64_t)b * sp.kv_heads + h) * sp.kv_cap + seq_position(sp.pos, b, sp.pos0) + s) * dh + nn % dh) * esz;
 }
 
 template <int ACT, bool SPLIT>

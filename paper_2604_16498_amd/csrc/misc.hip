@@ -15,7 +15,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ x, int batch, int heads,
                                                    int n_rows, int head_dim, int64_t batch_stride,
                                                    int64_t head_stride, int row0, int pos0,
-                                                   float base, int head_groups) {
+                                                   float base, int head_groups,
+                                                   const int* __restrict__ pos, int rows_at_pos) {
   const int half = head_dim / 2;
   const int chunks = half / 8;
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -27,7 +28,8 @@ __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ x, int batch,
   const int b = (int)(gid / ((int64_t)chunks * head_groups * n_rows));
   const int per = ceil_div(heads, head_groups);
   const int h0 = hg * per, h1 = min(heads, h0 + per);
-  const double p = (double)(pos0 + s);
+  const int pb = seq_position(pos, b, pos0);    // position of this sequence's first new row
+  const double p = (double)(pb + s);
   const double l2b = log2((double)base);
   float cs[8], sn[8];
 #pragma unroll
@@ -38,7 +40,7 @@ __global__ __launch_bounds__(256) void rope_kernel(T* __restrict__ x, int batch,
     cs[i] = (float)cv;
     sn[i] = (float)sv;
   }
-  T* row = x + (int64_t)b * batch_stride + (int64_t)(row0 + s) * head_dim + c * 8;
+  T* row = x + (int64_t)b * batch_stride + (int64_t)((rows_at_pos ? pb : row0) + s) * head_dim + c * 8;
   for (int h = h0; h < h1; ++h) {
     T* p1 = row + (int64_t)h * head_stride;
     T* p2 = p1 + half;
@@ -59,7 +61,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ ids,
                                                     const T* __restrict__ wte,
                                                     const T* __restrict__ wpe, T* __restrict__ h,
-                                                    int batch, int seq, int d, int vocab, int pos0) {
+                                                    int batch, int seq, int d, int vocab, int pos0,
+                                                    const int* __restrict__ pos) {
   const int chunks = d / 8;
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= (int64_t)batch * seq * chunks) return;
@@ -70,7 +73,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
   id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
   float a[8], p[8];
   Vec8<T>::load(wte + (int64_t)id * d + c * 8, a);
-  Vec8<T>::load(wpe + (int64_t)(pos0 + s) * d + c * 8, p);
+  Vec8<T>::load(wpe + (int64_t)(seq_position(pos, (int)(t / seq), pos0) + s) * d + c * 8, p);
 #pragma unroll
   for (int i = 0; i < 8; ++i) a[i] += p[i];
   Vec8<T>::store(h + t * d + c * 8, a);
@@ -115,7 +118,7 @@ forge_status launch_quantize_int8(const void* w, int8_t* q, float* scale, int N,
 
 forge_status launch_rope(void* x, int batch, int heads, int n_rows, int head_dim,
                          int64_t batch_stride, int64_t head_stride, int row0, int pos0, float base,
-                         forge_dtype dt, hipStream_t s) {
+                         forge_dtype dt, hipStream_t s, const int* pos, bool rows_at_pos) {
   const int64_t base_threads = (int64_t)batch * n_rows * (head_dim / 16);
   // enough head groups to reach ~128k threads, at most one group per head
   int head_groups = (int)ceil_div64(131072, base_threads);
@@ -124,25 +127,26 @@ forge_status launch_rope(void* x, int batch, int heads, int n_rows, int head_dim
   dim3 grid((unsigned)ceil_div64(total, 256)), block(256);
   if (dt == FORGE_BF16)
     rope_kernel<bf16><<<grid, block, 0, s>>>((bf16*)x, batch, heads, n_rows, head_dim, batch_stride,
-                                             head_stride, row0, pos0, base, head_groups);
+                                             head_stride, row0, pos0, base, head_groups, pos, rows_at_pos ? 1 : 0);
   else
     rope_kernel<float><<<grid, block, 0, s>>>((float*)x, batch, heads, n_rows, head_dim,
-                                              batch_stride, head_stride, row0, pos0, base, head_groups);
+                                              batch_stride, head_stride, row0, pos0, base, head_groups, pos,
+                                              rows_at_pos ? 1 : 0);
   return launch_status();
 }
 
 forge_status launch_embed(const int32_t* ids, const void* wte, const void* wpe, void* h, int batch,
                           int seq, int d, int vocab, int n_pos, int pos0, forge_dtype dt,
-                          hipStream_t s) {
+                          hipStream_t s, const int* pos) {
   (void)n_pos;
   const int64_t total = (int64_t)batch * seq * (d / 8);
   dim3 grid((unsigned)ceil_div64(total, 256)), block(256);
   if (dt == FORGE_BF16)
     embed_kernel<bf16><<<grid, block, 0, s>>>(ids, (const bf16*)wte, (const bf16*)wpe, (bf16*)h,
-                                              batch, seq, d, vocab, pos0);
+                                              batch, seq, d, vocab, pos0, pos);
   else
     embed_kernel<float><<<grid, block, 0, s>>>(ids, (const float*)wte, (const float*)wpe, (float*)h,
-                                               batch, seq, d, vocab, pos0);
+                                               batch, seq, d, vocab, pos0, pos);
   return launch_status();
 }
 
