@@ -408,25 +408,29 @@ def main():
         y = torch.empty(M, ld, device="cuda", dtype=dt)
         res = torch.randn(M, N, device="cuda", dtype=torch.float32).to(dt) if name in ("out", "mlp_down") else None
         gws = F.workspace(F.forge_gemm_workspace_bytes(M, N, K, act, dt))
+        # one event pair around each sweep over the layers' weights (the launches run back to back,
+        # as they do inside a step); an event pair around every single launch would add the
+        # dispatch latency on both sides to a 40 us kernel
         times = []
-        for r in range(reps):
+        for r in range(reps + 1):                 # the first sweep is a warm-up and is dropped
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
             for l in range(count):
                 if name != "lm_head":
                     w, b = m["layers"][l][key[0]], m["layers"][l][key[1]]
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
                 F.forge_gemm_bias_gelu(x, w, b, res, y, act, gws, n=N)
-                e1.record()
-                times.append((e0, e1))
+            e1.record()
+            times.append((e0, e1))
         torch.cuda.synchronize()
-        durs = [a.elapsed_time(b_) * 1e-3 for a, b_ in times]
+        durs = [a.elapsed_time(b_) * 1e-3 for a, b_ in times[1:]]
+        n_launch = reps * count
         nw = 2 * N if act == "swiglu" else N
         sym = "%s act=%s" % (F.forge_gemm_variant(M, N, K, act, dt, ldy=ld), act)
         gkey = sym
         gr = groups.setdefault(gkey, {"time": 0.0, "flops": 0.0, "launches": 0, "bytes": 0.0})
         gr["time"] += sum(durs)
-        gr["flops"] += 2.0 * M * nw * K * len(durs)
-        gr["launches"] += len(durs)
+        gr["flops"] += 2.0 * M * nw * K * n_launch
+        gr["launches"] += n_launch
         del x, y, res
     if args.traffic_probe:
         return
@@ -440,14 +444,16 @@ def main():
         aws = F.workspace(F.forge_attn_fused_workspace_bytes(wl.batch, sh.q_heads, sh.kv_heads, wl.seq, kvl,
                                                              sh.head_dim, dt))
         evs = []
-        for _ in range(3 + reps * 4):
+        per = 4                                   # calls per event pair, back to back
+        for _ in range(1 + reps):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            F.forge_attn_fused(q, kc0, vc0, o, kv_len=kvl, workspace=aws)
+            for _ in range(per):
+                F.forge_attn_fused(q, kc0, vc0, o, kv_len=kvl, workspace=aws)
             e1.record()
             evs.append((e0, e1))
         torch.cuda.synchronize()
-        ad = [a.elapsed_time(b) * 1e-3 for a, b in evs[3:]]
+        ad = [a.elapsed_time(b) * 1e-3 / per for a, b in evs[1:]]
         at = sum(ad) / len(ad)
         if wl.seq == 1:
             kvb = 2.0 * wl.batch * sh.kv_heads * kvl * sh.head_dim * 2
