@@ -176,3 +176,97 @@ def test_config5_llama8b_decode_layer(F):
         ref = O.attention(q[b:b + 1], host(tk[b:b + 1, :, :pos0 + 1]), host(tv[b:b + 1, :, :pos0 + 1]),
                           1 / math.sqrt(sh.head_dim), True)
         check(o[b:b + 1], ref, True, "config 5 attention seq %d" % b)
+
+
+def test_config5_llama8b_decode_layer_int8_weights(F):
+    """The same decode step on int8 weights (symmetric, one scale per weight row), quantised by the
+    oracle; 4 of the 64 sequences go through the oracle, which multiplies by the dequantised
+    weights."""
+    wl = I.WORKLOADS[5]
+    sh = wl.block
+    B, pos0 = wl.batch, wl.pos0
+    cap = 2112
+    w = I.block_weights(sh, 5, 0, True)
+    x = I.hidden_states(wl)
+    kc = I.kv_cache(wl, 0, "k_cache", B, cap, pos0)
+    vc = I.kv_cache(wl, 0, "v_cache", B, cap, pos0)
+    wo, tw = dict(w), {k: (None if v is None else dev(v, True)) for k, v in w.items()}
+    for wn, sn in (("w_qkv", "s_qkv"), ("w_o", "s_o"), ("w_up", "s_up"), ("w_down", "s_down")):
+        q, s = O.quantize_int8(w[wn])
+        wo[wn] = O.dequantize_int8(q, s)
+        tw[wn], tw[sn] = torch.from_numpy(q).cuda(), torch.from_numpy(s).cuda()
+    desc = F.make_block_desc(sh, tw)
+    out, tk, tv = gpu_block(F, desc, dev(x, True), pos0, cap, sh, dev(kc, True), dev(vc, True))
+    sample = [0, 21, 42, 63]
+    kcs = kc[sample].astype(np.float64); vcs = vc[sample].astype(np.float64)
+    ref = O.decoder_block(sh, wo, x[sample], kcs, vcs, pos0=pos0)
+    e = check(out[sample], ref, True, "config 5 decode layer, int8 weights", chain=True)
+    print("config5 int8 decode layer l2 err %.3e" % e)
+    check(tk[sample, :, pos0], kcs[:, :, pos0], True, "appended K row")
+    check(tv[sample, :, pos0], vcs[:, :, pos0], True, "appended V row")
+
+
+def test_config5_llama8b_decode_layer_ragged(F):
+    """The decode step of the 8B shape with every sequence at its own position (1 ... 2048 cached
+    positions): 5 sequences, among them the shortest and the longest, go through the oracle."""
+    wl = I.WORKLOADS[5]
+    sh = wl.block
+    B = wl.batch
+    cap = 2112
+    rng = np.random.default_rng(505)
+    pos = [int(p) for p in rng.integers(1, 2049, size=B)]
+    pos[0], pos[63] = 1, 2048
+    w = I.block_weights(sh, 5, 0, True)
+    x = I.hidden_states(wl)
+    kc = I.kv_cache(wl, 0, "k_cache", B, cap, 2048)
+    vc = I.kv_cache(wl, 0, "v_cache", B, cap, 2048)
+    tw = dev_dict(w, True)
+    desc = F.make_block_desc(sh, tw)
+    tx, tk, tv = dev(x, True), dev(kc, True), dev(vc, True)
+    out = torch.empty_like(tx)
+    ws = F.workspace(F.forge_decoder_block_workspace_bytes(desc, B, 1, cap))
+    F.forge_decoder_block_decode(desc, tx, out, tk, tv, torch.tensor(pos, dtype=torch.int32, device="cuda"),
+                                 max(pos), ws)
+    torch.cuda.synchronize()
+    for b in (0, 13, 31, 50, 63):
+        p = pos[b]
+        kr, vr = kc[b:b + 1].astype(np.float64), vc[b:b + 1].astype(np.float64)
+        ref = O.decoder_block(sh, w, x[b:b + 1], kr, vr, pos0=p)
+        check(out[b:b + 1], ref, True, "sequence %d at position %d" % (b, p), chain=True)
+        check(tk[b:b + 1, :, p], kr[:, :, p], True, "appended K row of sequence %d" % b)
+
+
+def test_config2_compiled_replay_equals_the_plain_launch_list(F):
+    """The benchmark's default workload through the compiled launcher: the replay of the recorded
+    graph, on the linear-scan workspace plan, gives the logits of forge_model_forward bit for bit."""
+    wl = I.WORKLOADS[2]
+    sh = wl.block
+    B, S = wl.batch, wl.seq
+    layers = [I.block_weights(sh, 2, l, True, wl.bias_std) for l in range(wl.layers)]
+    mw = I.model_weights(wl)
+    tl = [dev_dict(w, True) for w in layers]
+    tm = dev_dict(mw, True)
+    ld = (wl.vocab + 7) // 8 * 8
+    model = F.make_model_desc([F.make_block_desc(sh, w) for w in tl], tm, logits_ld=ld)
+    tids = torch.from_numpy(I.token_ids(2, B, S, wl.vocab)).cuda()
+    shape_kv = (wl.layers, B, sh.kv_heads, S, sh.head_dim)
+    plain = torch.zeros(B, S, ld, dtype=torch.bfloat16, device="cuda")
+    kc0 = torch.zeros(shape_kv, dtype=torch.bfloat16, device="cuda"); vc0 = torch.zeros_like(kc0)
+    F.forge_model_forward(model, tids, plain, kc0, vc0, 0, F.workspace(F.forge_model_workspace_bytes(model, B, S, S)))
+    torch.cuda.synchronize()
+    cm = F.CompiledModel(model, B, S, 0, S)
+    ni, nr, _, nb = cm.counts()
+    assert (ni, nb) == (87, 5) and nr == 147
+    out = torch.zeros_like(plain)
+    kc = torch.zeros_like(kc0); vc = torch.zeros_like(vc0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    cm.bind(tids, out, kc, vc, F.workspace(cm.workspace_bytes()), side)
+    side.synchronize()
+    for _ in range(2):
+        out.zero_(); kc.zero_(); vc.zero_()
+        torch.cuda.synchronize()
+        cm.run(side)
+        side.synchronize()
+        assert torch.equal(out, plain) and torch.equal(kc, kc0) and torch.equal(vc, vc0)
+    cm.close()
