@@ -167,3 +167,36 @@ def test_block_w8_rejects_partial_scales_and_fp32(F):
     with pytest.raises(F.ForgeError) as e:
         F.forge_decoder_block(desc, x, torch.empty_like(x), kc, kc.clone(), 0, F.workspace(1 << 20))
     assert e.value.status == 1
+
+
+def test_compiled_model_on_int8_weights(F):
+    """A decode step of a two-layer int8 stack through the compiled launcher equals the plain
+    launch list bit for bit (same kernels, the scratch areas at their planned places)."""
+    sh, L, B, cap, pos0 = LLAMA, 2, 8, 96, 70
+    gpu_layers = []
+    for l in range(L):
+        _, wg = quantised_weights(I.block_weights(sh, 96, l, bf16=True, random_affine=True, weight_std=0.05))
+        gpu_layers.append(wg)
+    wl = I.scaled(I.WORKLOADS[4], block=sh, layers=L, batch=B, seq=1)
+    tm = dev_dict(I.model_weights(wl, random_affine=True), True)
+    model = F.make_model_desc([F.make_block_desc(sh, w) for w in gpu_layers], tm)
+    x = dev(I.normal(96, 0, "x", (B, 1, sh.d_model), 1.0, bf16=True), True)
+    k_init = dev(I.normal(96, 0, "k_cache", (L, B, sh.kv_heads, cap, sh.head_dim), 1.0, bf16=True), True)
+    v_init = dev(I.normal(96, 0, "v_cache", (L, B, sh.kv_heads, cap, sh.head_dim), 1.0, bf16=True), True)
+    plain = torch.empty(B, 1, sh.d_model, dtype=torch.bfloat16, device="cuda")
+    kc0, vc0 = k_init.clone(), v_init.clone()
+    F.forge_model_forward(model, x, plain, kc0, vc0, pos0, F.workspace(F.forge_model_workspace_bytes(model, B, 1, cap)))
+    torch.cuda.synchronize()
+    cm = F.CompiledModel(model, B, 1, pos0, cap)
+    out = torch.zeros_like(plain)
+    kc, vc = k_init.clone(), v_init.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    cm.bind(x, out, kc, vc, F.workspace(cm.workspace_bytes()), side)
+    for _ in range(2):
+        out.zero_(); kc.copy_(k_init); vc.copy_(v_init)
+        torch.cuda.synchronize()
+        cm.run(side)
+        side.synchronize()
+        assert torch.equal(out, plain) and torch.equal(kc, kc0) and torch.equal(vc, vc0)
+    cm.close()

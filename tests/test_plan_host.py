@@ -80,7 +80,7 @@ class Shape:
         self.__dict__.update(kw)
 
 
-def fake_model(shape, n_layers, tokens, dt, vocab=1000, n_pos=512):
+def fake_model(shape, n_layers, tokens, dt, vocab=1000, n_pos=512, w8=False):
     """Descriptors whose pointers are distinct aligned made-up addresses."""
     addr = [0x10000]
 
@@ -95,7 +95,8 @@ def fake_model(shape, n_layers, tokens, dt, vocab=1000, n_pos=512):
                                                                 shape.head_dim, shape.d_ff)
         d.norm, d.eps, d.mlp_act = B.NORM[shape.norm], 1e-5, B.ACT[shape.mlp_act]
         d.use_rope, d.rope_base, d.dt = int(shape.use_rope), 10000.0, dt
-        for name in ("norm1_g", "w_qkv", "w_o", "norm2_g", "w_up", "w_down"):
+        for name in ("norm1_g", "w_qkv", "w_o", "norm2_g", "w_up", "w_down") + (
+                ("s_qkv", "s_o", "s_up", "s_down") if w8 else ()):
             setattr(d, name, ptr())
         layers.append(d)
     m = B.ModelDesc()
@@ -121,13 +122,16 @@ CASES = [
     ("llama_decode_bf16", LLAMA, 4, False, B.FORGE_BF16, 8, 1, 300, 301),
     ("llama_decode_f32", LLAMA, 2, False, B.FORGE_F32, 8, 1, 40, 64),
     ("gpt_decode_bf16", GPT, 12, True, B.FORGE_BF16, 4, 1, 100, 128),
+    ("llama_decode_int8", LLAMA, 3, False, B.FORGE_BF16, 16, 1, 300, 320),
+    ("llama_prefill_int8", LLAMA, 2, False, B.FORGE_BF16, 1, 96, 0, 96),
 ]
 
 
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
 def test_compiled_program_and_plan_match_the_oracle(case):
-    _, shape, L, tokens, dt, batch, q_len, pos0, kv_cap = case
-    model = fake_model(shape, L, tokens, dt)
+    name, shape, L, tokens, dt, batch, q_len, pos0, kv_cap = case
+    w8 = name.endswith("int8")
+    model = fake_model(shape, L, tokens, dt, w8=w8)
     cm = B.CompiledModel(model, batch, q_len, pos0, kv_cap)
     ops, out_reg, ins, reg_bytes, reg_offset = cm.program()
     ni, nr, _, nb = cm.counts()
@@ -155,10 +159,11 @@ def test_compiled_program_and_plan_match_the_oracle(case):
     nqkv = (shape.q_heads + 2 * shape.kv_heads) * shape.head_dim
     hd = shape.q_heads * shape.head_dim
     l = B.lib()
-    scratch = {"ws_qkv": l.forge_gemm_workspace_bytes(T, nqkv, shape.d_model, 0, dt),
-               "ws_o": l.forge_gemm_workspace_bytes(T, shape.d_model, hd, 0, dt),
-               "ws_up": l.forge_gemm_workspace_bytes(T, shape.d_ff, shape.d_model, act, dt),
-               "ws_down": l.forge_gemm_workspace_bytes(T, shape.d_model, shape.d_ff, 0, dt),
+    gws = (lambda M, N, K, a, _dt: l.forge_gemm_w8_workspace_bytes(M, N, K, a)) if w8 else l.forge_gemm_workspace_bytes
+    scratch = {"ws_qkv": gws(T, nqkv, shape.d_model, 0, dt),
+               "ws_o": gws(T, shape.d_model, hd, 0, dt),
+               "ws_up": gws(T, shape.d_ff, shape.d_model, act, dt),
+               "ws_down": gws(T, shape.d_model, shape.d_ff, 0, dt),
                "ws_attn": l.forge_attn_fused_workspace_bytes(batch, shape.q_heads, shape.kv_heads, q_len,
                                                              pos0 + q_len, shape.head_dim, dt),
                "ws_head": l.forge_gemm_workspace_bytes(T, 1000, shape.d_model, 0, dt)}
