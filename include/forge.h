@@ -338,7 +338,10 @@ forge_status forge_plan_workspace(int n_regs, const int* start, const int* end,
  *                       weight POINTERS: the weights must outlive the handle).
  * forge_compiled_counts / forge_compiled_program   report the program and its plan: op[j]
  *                       (forge_op), out_reg / in_begin / in_regs as for forge_plan_liveness,
- *                       reg_bytes and reg_offset per register.  Any output pointer may be NULL.
+ *                       reg_bytes and reg_offset per register.  HOST arrays sized from the
+ *                       counts: op and out_reg n_instr entries, in_begin n_instr + 1, in_regs
+ *                       n_reads, reg_bytes and reg_offset n_regs.  Any output pointer may be
+ *                       NULL.
  * forge_compiled_bind   fixes input / output / caches / workspace (device pointers as for
  *                       forge_model_forward, workspace >= forge_compiled_workspace_bytes) and
  *                       records the graph on `stream`, which must not be the NULL stream.  It
