@@ -100,7 +100,11 @@ forge_status launch_t(const AttnArgs& a, hipStream_t s) {
 
 }  // namespace
 
-forge_status launch_attn_f32(const AttnArgs& a, hipStream_t s) { return launch_t<float>(a, s); }
+forge_status launch_attn_f32(const AttnArgs& a, hipStream_t s) {
+  // a prompt goes to the matrix-core kernel; single queries, masks and per-sequence lengths stay here
+  if (a.mask == nullptr && a.kv_pos == nullptr && a.q_len >= 16) return launch_attn_f32_mfma(a, s);
+  return launch_t<float>(a, s);
+}
 forge_status launch_attn_simple_bf16(const AttnArgs& a, hipStream_t s) { return launch_t<bf16>(a, s); }
 
 }  // namespace forge

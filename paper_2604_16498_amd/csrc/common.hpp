@@ -198,6 +198,7 @@ struct AttnArgs {
 };
 
 forge_status launch_attn_f32(const AttnArgs& a, hipStream_t s);
+forge_status launch_attn_f32_mfma(const AttnArgs& a, hipStream_t s);   // prompts: no mask, one length
 forge_status launch_attn_simple_bf16(const AttnArgs& a, hipStream_t s);
 forge_status launch_attn_prefill_bf16(const AttnArgs& a, hipStream_t s);
 forge_status launch_attn_decode_bf16(const AttnArgs& a, hipStream_t s);
