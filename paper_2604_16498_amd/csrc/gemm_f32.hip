@@ -8,7 +8,8 @@
 // floats so that eight lanes reading the same column chunk of eight consecutive rows hit
 // disjoint banks.  The MFMA contracts two k per issue (lanes 0-31 supply one, lanes 32-63 the
 // other); lanes 0-31 walk k = 0..15 of the slab and lanes 32-63 walk k = 16..31, so every
-// lane reads four consecutive floats per 128-bit LDS read.
+// lane reads four consecutive floats per 128-bit LDS read.  The slabs are prefetched three
+// ahead in registers.
 //
 // Small problems (fewer tiles than CUs -- the 128-token fp32 layer has 24 to 96 of them, and a
 // block walks K slab by slab with a barrier each) are split along K over grid.z: raw fp32
@@ -61,38 +62,72 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(
 
   const int k_begin = blockIdx.z * k_per_split;           // multiple of BK
   const int k_end = min(K, k_begin + k_per_split);
-  for (int k0 = k_begin; k0 < k_end; k0 += BK) {
-    // global -> LDS (zero fill outside the matrix)
+
+  // Register prefetch, PF slabs ahead: a block of a small problem walks only a few slabs, and
+  // with load -> LDS -> barrier -> multiply in sequence every slab would pay the full memory
+  // latency.  Loads are unconditional from clamped (valid) addresses so that they stay
+  // asynchronous; what lies outside the matrix is zeroed when the slab is written to LDS.
+  constexpr int PF = 3;
+  floatx4 va[PF][2], vb[PF][NB][2];
+  const float* xrow[2];
+  const float* wrow[NB][2];
+  bool rowa_ok[2], rowb_ok[2];
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int row = lrow + 32 * r;
+    rowa_ok[r] = m0 + row < M;
+    rowb_ok[r] = n0 + row < N;
+    xrow[r] = x + (int64_t)min(m0 + row, M - 1) * K;
+#pragma unroll
+    for (int t = 0; t < NB; ++t) wrow[t][r] = w + (int64_t)(min(n0 + row, N - 1) + t * N) * K;
+  }
+  auto gload = [&](int k0, int slot) {
+    const int kk = min(k0 + lcol, K - 4);
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      va[slot][r] = *reinterpret_cast<const floatx4*>(xrow[r] + kk);
+#pragma unroll
+      for (int t = 0; t < NB; ++t) vb[slot][t][r] = *reinterpret_cast<const floatx4*>(wrow[t][r] + kk);
+    }
+  };
+  auto lstore = [&](int k0, int slot) {
+    const bool k_ok = k0 + lcol < K;
+    const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
       const int row = lrow + 32 * r;
-      const int kk = k0 + lcol;
-      floatx4 va = {0.f, 0.f, 0.f, 0.f};
-      if (m0 + row < M && kk < K) va = *reinterpret_cast<const floatx4*>(x + (int64_t)(m0 + row) * K + kk);
-      *reinterpret_cast<floatx4*>(&As[row][lcol]) = va;
+      *reinterpret_cast<floatx4*>(&As[row][lcol]) = rowa_ok[r] && k_ok ? va[slot][r] : zero;
 #pragma unroll
-      for (int t = 0; t < NB; ++t) {
-        floatx4 vb = {0.f, 0.f, 0.f, 0.f};
-        if (n0 + row < N && kk < K)
-          vb = *reinterpret_cast<const floatx4*>(w + (int64_t)(n0 + row + t * N) * K + kk);
-        *reinterpret_cast<floatx4*>(&Bs[t][row][lcol]) = vb;
+      for (int t = 0; t < NB; ++t)
+        *reinterpret_cast<floatx4*>(&Bs[t][row][lcol]) = rowb_ok[r] && k_ok ? vb[slot][t][r] : zero;
+    }
+  };
+#pragma unroll
+  for (int d = 0; d < PF; ++d) gload(k_begin + d * BK, d);
+  for (int kb = k_begin; kb < k_end; kb += PF * BK) {
+#pragma unroll
+    for (int d = 0; d < PF; ++d) {
+      const int k0 = kb + d * BK;
+      if (k0 < k_end) {                       // block-uniform
+        lstore(k0, d);
+        __syncthreads();
+        const int r = lane & 31, hk = (lane >> 5) * 16;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const floatx4 a = *reinterpret_cast<const floatx4*>(&As[wm * 32 + r][hk + 4 * j]);
+          floatx4 b[NB];
+#pragma unroll
+          for (int t = 0; t < NB; ++t) b[t] = *reinterpret_cast<const floatx4*>(&Bs[t][wn * 32 + r][hk + 4 * j]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int t = 0; t < NB; ++t)
+              acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], b[t][e], acc[t], 0, 0, 0);
+        }
+        __syncthreads();
       }
+      gload(k0 + PF * BK, d);                 // slab k0 + PF slabs into the registers just consumed
     }
-    __syncthreads();
-    const int r = lane & 31, hk = (lane >> 5) * 16;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const floatx4 a = *reinterpret_cast<const floatx4*>(&As[wm * 32 + r][hk + 4 * j]);
-      floatx4 b[NB];
-#pragma unroll
-      for (int t = 0; t < NB; ++t) b[t] = *reinterpret_cast<const floatx4*>(&Bs[t][wn * 32 + r][hk + 4 * j]);
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-#pragma unroll
-        for (int t = 0; t < NB; ++t)
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], b[t][e], acc[t], 0, 0, 0);
-    }
-    __syncthreads();
   }
 
   const int n = n0 + wn * 32 + (lane & 31);
@@ -166,7 +201,7 @@ struct SplitPlan { int splits, k_per_split; };
 SplitPlan plan_split(int M, int N, int K) {
   const int tiles = ceil_div(M, BM) * ceil_div(N, BN);
   const int slabs = ceil_div(K, BK);
-  int want = tiles >= 256 ? 1 : min(ceil_div(512, tiles), slabs / 4);
+  int want = tiles >= 256 ? 1 : min(ceil_div(256, tiles), slabs / 4);
   want = max(1, want);
   const int per = ceil_div(slabs, want);
   return SplitPlan{ceil_div(slabs, per), per * BK};
