@@ -2,10 +2,14 @@
 // every cached K and V row is read exactly once, with 128-bit loads, and nothing else of
 // comparable size moves.
 //
-// Split-KV: block (split, kv head, batch) streams CHUNK = 256 consecutive cache rows of ONE kv
+// Split-KV: block (split, kv head, batch) streams one contiguous range of cache rows of ONE kv
 // head for all G = Hq/Hkv query heads that share it (grouped-query attention reads the cache
-// once per group, not once per query head).  Each of the 4 waves owns 64 rows as 4 tiles of 16
-// and keeps two tiles of K and V loads in flight ahead of the one it is working on.
+// once per group, not once per query head).  The 4 waves of a block take the 16-row tiles of the
+// range in turn (wave w: tiles w, w + 4, ...) and each keeps two tiles of K and V loads in flight
+// ahead of the one it is working on.  The number of splits is chosen on the host so that about
+// two blocks per compute unit exist: a large batch needs no split at all (one block per
+// (kv head, sequence) walks the whole cache and writes the final output itself: no partials, no
+// second kernel), a small batch is cut into ranges that are multiples of 128 rows.
 //
 // Per tile of 16 rows:
 //   scores   S[row, head] = K . q^T on the matrix cores (v_mfma_f32_16x16x32_bf16, heads padded
@@ -19,9 +23,9 @@
 //            patch of LDS (the only cross-lane traffic), is packed with its neighbour row to
 //            bf16 pairs, V rows of two steps are interleaved with byte permutes, and the
 //            accumulation runs on v_dot2_f32_bf16: two rows per instruction, fp32 accumulate.
-// Wave and block partials are merged in a fixed order; the block writes (m, l, o) per query head
-// to the workspace and a second kernel merges the splits in split order -- no atomics, so the
-// result is bitwise reproducible.
+// Wave and block partials are merged in a fixed order; with more than one split the block writes
+// (m, l, o) per query head to the workspace and a second kernel merges the splits in split order
+// -- no atomics, so the result is bitwise reproducible.
 #include "common.hpp"
 
 namespace forge {
@@ -29,16 +33,17 @@ namespace {
 
 constexpr int NWAVES = 4;                 // waves per block
 constexpr int TILE = 16;                  // cache rows per MFMA tile
-constexpr int WTILES = 4;                 // tiles per wave
-constexpr int WROWS = TILE * WTILES;      // cache rows per wave
-constexpr int CHUNK = NWAVES * WROWS;     // cache rows per block
+constexpr int GRAIN = 2 * NWAVES * TILE;  // a split is a multiple of this many rows (two tiles per wave)
+constexpr int MAX_SPLITS = 64;            // the combine holds one split per lane
 
 struct DecParams {
   const bf16* q;
   const bf16* k;
   const bf16* v;
   float* part;     // [B, Hkv, splits, G, dh + 2]
+  bf16* out;       // [B, Hq * dh]: written directly when splits == 1
   int q_heads, kv_heads, kv_len, splits;
+  int rows_per_split;   // multiple of GRAIN
   int64_t kv_bs, kv_hs;
   float scale_log2e;
   const int* kv_pos;   // per-sequence: rows [0, kv_pos[b]] (clamped to kv_len - 1); NULL: kv_len rows
@@ -74,11 +79,15 @@ __global__ __launch_bounds__(NWAVES * 64, 3) void attn_decode_kernel(DecParams p
 
   const bf16* kb = p.k + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
   const bf16* vb = p.v + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
-  const int row0 = split * CHUNK + wave * WROWS;
+  const int split_begin = split * p.rows_per_split;
+  // tiles of this wave that begin before the end of the range, rounded up to a pair (the loop
+  // takes two per trip; the loads stay unconditional so that their count per trip is fixed)
   // a split that lies wholly past the end of a short sequence writes a neutral partial
   // (maximum -1e30, sum 0), which the combine weighs with exactly 0
   const int kv_len = p.kv_pos != nullptr ? min(max(p.kv_pos[b], 0), p.kv_len - 1) + 1 : p.kv_len;
-  const int row_end = min(kv_len, (split + 1) * CHUNK);
+  const int row_end = min(kv_len, split_begin + p.rows_per_split);
+  const int rows_w = row_end - split_begin - wave * TILE;          // <= 0: no tile for this wave
+  const int ntile = rows_w > 0 ? (ceil_div(rows_w, NWAVES * TILE) + 1) / 2 * 2 : 0;
   const int last = kv_len - 1;
 
   // q as the MFMA B operand: lane = (head, chunk 4j + kg); heads >= G are zero columns
@@ -91,8 +100,10 @@ __global__ __launch_bounds__(NWAVES * 64, 3) void attn_decode_kernel(DecParams p
   }
 
   u32x4 kr[2][NJ], vr[2][VSTEPS];
+  // tile t of this wave: rows base .. base + 15 (the waves take the tiles of the range in turn)
+  auto tile_base = [&](int t) { return split_begin + (t * NWAVES + wave) * TILE; };
   auto load_tile = [&](int t, u32x4 (&kk)[NJ], u32x4 (&vv)[VSTEPS]) {
-    const int base = row0 + t * TILE;
+    const int base = tile_base(t);
 #pragma unroll
     for (int j = 0; j < NJ; ++j)   // rows past the end re-read the last row (masked below)
       kk[j] = *reinterpret_cast<const u32x4*>(kb + (int64_t)min(base + krow, last) * DH + (4 * j + kg) * 8);
@@ -111,11 +122,13 @@ __global__ __launch_bounds__(NWAVES * 64, 3) void attn_decode_kernel(DecParams p
     for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
   const float cl = p.scale_log2e;
 
+  for (int t0 = 0; t0 < ntile; t0 += 2) {
 #pragma unroll
-  for (int t = 0; t < WTILES; ++t) {
-    u32x4 (&kk)[NJ] = kr[t & 1];
-    u32x4 (&vv)[VSTEPS] = vr[t & 1];
-    const int base = row0 + t * TILE;
+   for (int u = 0; u < 2; ++u) {
+    const int t = t0 + u;
+    u32x4 (&kk)[NJ] = kr[u];
+    u32x4 (&vv)[VSTEPS] = vr[u];
+    const int base = tile_base(t);
     if (base < row_end) {     // wave-uniform: tiles wholly past the end contribute nothing
       // ---- scores ------------------------------------------------------------------------------
       floatx4 sacc = {0.f, 0.f, 0.f, 0.f};
@@ -180,7 +193,10 @@ __global__ __launch_bounds__(NWAVES * 64, 3) void attn_decode_kernel(DecParams p
       }
     }
     wave_lds_sync();   // this tile's LDS reads are done before the next tile's writes
-    if (t + 2 < WTILES) load_tile(t + 2, kr[t & 1], vr[t & 1]);   // refill the registers just consumed
+    // refill the registers just consumed (unconditional: past the end the last row is read
+    // again, which keeps the number of loads per trip, and with it the wait counts, fixed)
+    load_tile(t + 2, kr[u], vr[u]);
+   }
   }
 
   // ---- merge inside the wave: plain sums (one running maximum per head for the whole wave) -------
@@ -214,8 +230,12 @@ __global__ __launch_bounds__(NWAVES * 64, 3) void attn_decode_kernel(DecParams p
       o += sm[w][h][d] * a;
       lt += sm[w][h][DH + 1] * a;
     }
-    dst[h * (DH + 2) + d] = o;
-    if (d == 0) { dst[h * (DH + 2) + DH] = mn; dst[h * (DH + 2) + DH + 1] = lt; }
+    if (p.splits == 1) {   // the whole cache in one block: this is the result
+      p.out[((int64_t)b * p.q_heads + g * G + h) * DH + d] = (bf16)(o / lt);
+    } else {
+      dst[h * (DH + 2) + d] = o;
+      if (d == 0) { dst[h * (DH + 2) + DH] = mn; dst[h * (DH + 2) + DH + 1] = lt; }
+    }
   }
 }
 
@@ -258,23 +278,48 @@ __global__ __launch_bounds__(DH) void attn_decode_combine(const float* __restric
   out[((int64_t)b * q_heads + h) * DH + d] = (bf16)(o / ltot);
 }
 
+// Number of row ranges: about two blocks per compute unit, at most one range per GRAIN rows.
+struct SplitPlan { int splits, rows_per_split; };
+inline int decode_cus() {
+  static int cus = 0;     // same value on every device of a homogeneous node
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      v = 256;
+    cus = v;
+  }
+  return cus;
+}
+inline SplitPlan plan_splits(int batch, int kv_heads, int kv_len) {
+  const int64_t pairs = (int64_t)batch * kv_heads;
+  const int64_t for_two_per_cu = ceil_div64(2 * (int64_t)decode_cus(), pairs);
+  int want = for_two_per_cu < MAX_SPLITS ? (int)for_two_per_cu : MAX_SPLITS;
+  want = max(1, min(want, ceil_div(kv_len, GRAIN)));
+  const int rows = ceil_div(ceil_div(kv_len, want), GRAIN) * GRAIN;
+  return SplitPlan{ceil_div(kv_len, rows), rows};
+}
+
 template <int DH, int G>
 forge_status launch_dg(const AttnArgs& a, hipStream_t s) {
+  const SplitPlan pl = plan_splits(a.batch, a.kv_heads, a.kv_len);
   DecParams p;
   p.q = (const bf16*)a.q;
   p.k = (const bf16*)a.k;
   p.v = (const bf16*)a.v;
   p.part = (float*)a.workspace;
+  p.out = (bf16*)a.out;
   p.q_heads = a.q_heads;
   p.kv_heads = a.kv_heads;
   p.kv_len = a.kv_len;
-  p.splits = ceil_div(a.kv_len, CHUNK);
+  p.splits = pl.splits;
+  p.rows_per_split = pl.rows_per_split;
   p.kv_bs = a.kv_batch_stride;
   p.kv_hs = a.kv_head_stride;
   p.scale_log2e = a.scale * 1.4426950408889634f;
   p.kv_pos = a.kv_pos;
-  if (p.splits > 64) return FORGE_ERR_UNSUPPORTED;   // the combine holds one split per lane
   attn_decode_kernel<DH, G><<<dim3(p.splits, a.kv_heads, a.batch), NWAVES * 64, 0, s>>>(p);
+  if (p.splits == 1) return launch_status();
   if (hipGetLastError() != hipSuccess) return FORGE_ERR_HIP;
   attn_decode_combine<DH><<<dim3(a.q_heads, a.batch), DH, 0, s>>>(p.part, (bf16*)a.out, a.q_heads,
                                                                   a.kv_heads, p.splits);
@@ -294,13 +339,14 @@ forge_status launch_d(const AttnArgs& a, hipStream_t s) {
 }  // namespace
 
 size_t attn_decode_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim) {
-  const int splits = ceil_div(kv_len, CHUNK);
+  const int splits = plan_splits(batch, kv_heads, kv_len).splits;
+  if (splits == 1) return 0;       // one block per (kv head, sequence) writes the output itself
   return (size_t)batch * q_heads * splits * (head_dim + 2) * sizeof(float);
 }
 
 forge_status launch_attn_decode_bf16(const AttnArgs& a, hipStream_t s) {
   const size_t need = attn_decode_workspace_bytes(a.batch, a.q_heads, a.kv_heads, a.kv_len, a.head_dim);
-  if (a.workspace == nullptr || a.workspace_bytes < need) return FORGE_ERR_WORKSPACE;
+  if (need > 0 && (a.workspace == nullptr || a.workspace_bytes < need)) return FORGE_ERR_WORKSPACE;
   if (a.head_dim == 64) return launch_d<64>(a, s);
   if (a.head_dim == 128) return launch_d<128>(a, s);
   return FORGE_ERR_UNSUPPORTED;
