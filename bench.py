@@ -457,7 +457,8 @@ def main():
         at = sum(ad) / len(ad)
         if wl.seq == 1:
             kvb = 2.0 * wl.batch * sh.kv_heads * kvl * sh.head_dim * 2
-            attn = {"kernel": "attn_decode (split-KV) + combine", "avg_us": round(at * 1e6, 2),
+            label = "attn_decode (split-KV) + combine" if aws is not None else "attn_decode (one block per kv head and sequence)"
+            attn = {"kernel": label, "avg_us": round(at * 1e6, 2),
                     "hbm_gbs": round(kvb / at / 1e9, 1), "frac_of_hbm_peak": round(kvb / at / 1e9 / PEAK_HBM_GBS, 4)}
         else:
             attn = {"kernel": "attn_prefill<%d>" % sh.head_dim, "avg_us": round(at * 1e6, 2),
