@@ -33,7 +33,7 @@ def ipos(pos):
 @pytest.mark.parametrize("bf16,Hq,Hkv,dh", [(True, 8, 2, 128), (True, 4, 4, 64), (True, 8, 1, 64), (False, 4, 2, 64)],
                          ids=["g4_d128", "g1_d64", "g8_d64_valu", "f32"])
 def test_attn_decode_varlen(F, bf16, Hq, Hkv, dh):
-    pos = [0, 3, 255, 256, 700, 511, 1]              # lengths 1 .. 701: one to three 256-row splits
+    pos = [0, 3, 255, 256, 700, 511, 1]              # lengths 1 .. 701: some sequences end before the later KV splits begin
     B, cap = len(pos), 704
     q = I.normal(96, 0, "q", (B, Hq, 1, dh), 1.0, bf16=bf16)
     k = I.normal(96, 0, "k_cache", (B, Hkv, cap, dh), 1.0, bf16=bf16)
