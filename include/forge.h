@@ -26,8 +26,14 @@
  *   - `workspace` is caller-provided device scratch of `workspace_bytes` bytes (16-byte
  *     aligned); the matching *_workspace_bytes() function gives the size needed (may be 0,
  *     then NULL is accepted).  Too small -> FORGE_ERR_WORKSPACE.
- *   - No global mutable state; calls on different streams with disjoint buffers are
+ *   - No global mutable state beyond per-device caches of launch attributes (safe to fill
+ *     from several host threads); calls on different streams with disjoint buffers are
  *     independent.  Results are bitwise reproducible run to run (no atomics in reductions).
+ *   - Size limits of one call, beyond which FORGE_ERR_UNSUPPORTED is returned (and the
+ *     *_workspace_bytes() query returns 0): batch * q_len <= 2^24 rows; batch and head
+ *     counts <= 65535; GEMM M, N <= 2^24 with M * N <= 2^36.  Element offsets inside the
+ *     kernels are 64-bit.  Position arithmetic (pos0 + q_len against kv_cap or n_pos) is
+ *     checked without overflow.
  */
 #ifndef FORGE_H_
 #define FORGE_H_

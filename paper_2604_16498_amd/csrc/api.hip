@@ -142,6 +142,7 @@ int forge_version(void) { return 100; }
 size_t forge_attn_fused_workspace_bytes(int batch, int q_heads, int kv_heads, int q_len, int kv_len,
                                         int head_dim, forge_dtype dt) {
   if (batch < 1 || q_heads < 1 || kv_heads < 1 || q_len < 1 || kv_len < 1) return 0;
+  if (!grid_ok(batch, q_heads) || !rows_ok(batch, q_len)) return 0;
   return attn_ws(batch, q_heads, kv_heads, q_len, kv_len, head_dim, dt);
 }
 
@@ -156,6 +157,7 @@ forge_status forge_attn_fused(const void* q, const void* k, const void* v, void*
   if (q_heads % kv_heads != 0) return FORGE_ERR_INVALID_ARG;
   if (causal && kv_len < q_len) return FORGE_ERR_INVALID_ARG;
   if (head_dim != 64 && head_dim != 128) return FORGE_ERR_UNSUPPORTED;
+  if (!grid_ok(batch, q_heads) || !rows_ok(batch, q_len)) return FORGE_ERR_UNSUPPORTED;
   if (kv_head_stride < (int64_t)kv_len * head_dim || kv_batch_stride < kv_head_stride * kv_heads)
     return FORGE_ERR_INVALID_ARG;
   if (kv_head_stride % 8 != 0 || kv_batch_stride % 8 != 0) return FORGE_ERR_INVALID_ARG;
@@ -180,6 +182,7 @@ forge_status forge_attn_fused_masked(const void* q, const void* k, const void* v
   if (q_heads % kv_heads != 0) return FORGE_ERR_INVALID_ARG;
   if (causal && kv_len < q_len) return FORGE_ERR_INVALID_ARG;
   if (head_dim != 64 && head_dim != 128) return FORGE_ERR_UNSUPPORTED;
+  if (!grid_ok(batch, q_heads) || !rows_ok(batch, q_len)) return FORGE_ERR_UNSUPPORTED;
   if (kv_head_stride < (int64_t)kv_len * head_dim || kv_batch_stride < kv_head_stride * kv_heads)
     return FORGE_ERR_INVALID_ARG;
   if (kv_head_stride % 8 != 0 || kv_batch_stride % 8 != 0) return FORGE_ERR_INVALID_ARG;
@@ -195,7 +198,7 @@ forge_status forge_attn_fused_masked(const void* q, const void* k, const void* v
 }
 
 size_t forge_gemm_workspace_bytes(int M, int N, int K, forge_act act, forge_dtype dt) {
-  if (M < 1 || N < 1 || K < 1) return 0;
+  if (M < 1 || N < 1 || K < 1 || !gemm_size_ok(M, N)) return 0;
   return gemm_ws(M, N, K, act, dt, false);
 }
 
@@ -212,7 +215,7 @@ forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias
     return FORGE_ERR_INVALID_ARG;
   if (M < 1 || N < 1 || K < 1 || ldy < 0 || (ldy > 0 && ldy < N)) return FORGE_ERR_INVALID_ARG;
   if (act < FORGE_ACT_NONE || act > FORGE_ACT_GELU_ERF) return FORGE_ERR_INVALID_ARG;
-  if (K % (dt == FORGE_BF16 ? 8 : 4) != 0) return FORGE_ERR_UNSUPPORTED;
+  if (K % (dt == FORGE_BF16 ? 8 : 4) != 0 || !gemm_size_ok(M, N)) return FORGE_ERR_UNSUPPORTED;
   if (y == x || y == w) return FORGE_ERR_INVALID_ARG;
   // only the decode-sized bf16 problems cannot run without their partial-sum planes
   const size_t need = dt == FORGE_BF16 && M <= 64 ? gemm_ws(M, N, K, act, dt, false) : 0;
@@ -222,7 +225,7 @@ forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias
 }
 
 size_t forge_gemm_w8_workspace_bytes(int M, int N, int K, forge_act act) {
-  if (M < 1 || N < 1 || K < 1) return 0;
+  if (M < 1 || N < 1 || K < 1 || !gemm_size_ok(M, N)) return 0;
   return gemm_ws(M, N, K, act, FORGE_BF16, true);
 }
 
@@ -233,7 +236,7 @@ forge_status forge_gemm_w8(const void* x, const int8_t* wq, const float* wscale,
     return FORGE_ERR_INVALID_ARG;
   if (M < 1 || N < 1 || K < 1 || ldy < 0 || (ldy > 0 && ldy < N)) return FORGE_ERR_INVALID_ARG;
   if (act < FORGE_ACT_NONE || act > FORGE_ACT_GELU_ERF) return FORGE_ERR_INVALID_ARG;
-  if (K % 128 != 0) return FORGE_ERR_UNSUPPORTED;
+  if (K % 128 != 0 || !gemm_size_ok(M, N)) return FORGE_ERR_UNSUPPORTED;
   if (y == x) return FORGE_ERR_INVALID_ARG;
   if (workspace_bytes < gemm_ws(M, N, K, act, FORGE_BF16, true)) return FORGE_ERR_WORKSPACE;
   GemmArgs a = {x, wq, bias, residual, y, M, N, K, ldy, act, nullptr, nullptr, workspace, workspace_bytes, wscale};
@@ -268,7 +271,8 @@ forge_status forge_rope(void* x, int batch, int heads, int n_rows, int head_dim,
   if (batch < 1 || heads < 1 || n_rows < 1 || row0 < 0 || pos0 < 0 || !(base > 1.0f))
     return FORGE_ERR_INVALID_ARG;
   if (head_dim < 16 || head_dim % 16 != 0) return FORGE_ERR_UNSUPPORTED;
-  if (head_stride < (int64_t)(row0 + n_rows) * head_dim || batch_stride < head_stride * heads)
+  if (!rows_ok(batch, n_rows)) return FORGE_ERR_UNSUPPORTED;
+  if (head_stride < ((int64_t)row0 + n_rows) * head_dim || batch_stride < head_stride * heads)
     return FORGE_ERR_INVALID_ARG;
   if (head_stride % 8 != 0 || batch_stride % 8 != 0) return FORGE_ERR_INVALID_ARG;
   return launch_rope(x, batch, heads, n_rows, head_dim, batch_stride, head_stride, row0, pos0, base,
@@ -279,9 +283,8 @@ forge_status forge_embed(const int32_t* ids, const void* wte, const void* wpe, v
                          int seq, int d, int vocab, int n_pos, int pos0, forge_dtype dt,
                          void* stream) {
   if (!dtype_ok(dt) || ids == nullptr || !req(wte) || !req(wpe) || !req(h)) return FORGE_ERR_INVALID_ARG;
-  if (batch < 1 || seq < 1 || d < 1 || vocab < 1 || pos0 < 0 || pos0 + seq > n_pos)
-    return FORGE_ERR_INVALID_ARG;
-  if (d % 8 != 0) return FORGE_ERR_UNSUPPORTED;
+  if (batch < 1 || d < 1 || vocab < 1 || !span_ok(pos0, seq, n_pos)) return FORGE_ERR_INVALID_ARG;
+  if (d % 8 != 0 || !rows_ok(batch, seq)) return FORGE_ERR_UNSUPPORTED;
   return launch_embed(ids, wte, wpe, h, batch, seq, d, vocab, n_pos, pos0, dt,
                       static_cast<hipStream_t>(stream));
 }
@@ -289,6 +292,7 @@ forge_status forge_embed(const int32_t* ids, const void* wte, const void* wpe, v
 size_t forge_decoder_block_workspace_bytes(const forge_block_desc* desc, int batch, int q_len,
                                            int kv_cap) {
   if (check_block_desc(desc) != FORGE_OK || batch < 1 || q_len < 1 || kv_cap < q_len) return 0;
+  if (!grid_ok(batch, desc->q_heads) || !rows_ok(batch, q_len)) return 0;
   return plan_block(desc, batch, q_len, kv_cap).total;
 }
 
@@ -299,7 +303,8 @@ forge_status forge_decoder_block(const forge_block_desc* desc, const void* x_in,
   if (st != FORGE_OK) return st;
   if (!req(x_in) || !req(x_out) || !req(k_cache) || !req(v_cache) || !req(workspace))
     return FORGE_ERR_INVALID_ARG;
-  if (batch < 1 || q_len < 1 || pos0 < 0 || pos0 + q_len > kv_cap) return FORGE_ERR_INVALID_ARG;
+  if (batch < 1 || !span_ok(pos0, q_len, kv_cap)) return FORGE_ERR_INVALID_ARG;
+  if (!grid_ok(batch, desc->q_heads) || !rows_ok(batch, q_len)) return FORGE_ERR_UNSUPPORTED;
   if (workspace_bytes < plan_block(desc, batch, q_len, kv_cap).total) return FORGE_ERR_WORKSPACE;
   return run_block(desc, x_in, x_out, k_cache, v_cache, batch, q_len, pos0, kv_cap, workspace,
                    static_cast<hipStream_t>(stream));
@@ -307,6 +312,7 @@ forge_status forge_decoder_block(const forge_block_desc* desc, const void* x_in,
 
 size_t forge_model_workspace_bytes(const forge_model_desc* model, int batch, int q_len, int kv_cap) {
   if (check_model(model) != FORGE_OK || batch < 1 || q_len < 1 || kv_cap < q_len) return 0;
+  if (!grid_ok(batch, 1) || !rows_ok(batch, q_len)) return 0;
   return plan_model(model, batch, q_len, kv_cap).total;
 }
 
@@ -318,9 +324,10 @@ static forge_status model_forward(const forge_model_desc* model, const void* inp
   if (st != FORGE_OK) return st;
   if (input == nullptr || !req(output) || !req(k_cache) || !req(v_cache) || !req(workspace))
     return FORGE_ERR_INVALID_ARG;
-  if (batch < 1 || q_len < 1 || pos0 < 0 || pos0 + q_len > kv_cap) return FORGE_ERR_INVALID_ARG;
+  if (batch < 1 || !span_ok(pos0, q_len, kv_cap)) return FORGE_ERR_INVALID_ARG;
   const bool tokens = model->wte != nullptr;
-  if (tokens && pos0 + q_len > model->n_pos) return FORGE_ERR_INVALID_ARG;
+  if (tokens && !span_ok(pos0, q_len, model->n_pos)) return FORGE_ERR_INVALID_ARG;
+  if (!grid_ok(batch, 1) || !rows_ok(batch, q_len)) return FORGE_ERR_UNSUPPORTED;
   if (!tokens && !aligned16(input)) return FORGE_ERR_INVALID_ARG;
   const ModelPlan pl = plan_model(model, batch, q_len, kv_cap);
   if (workspace_bytes < pl.total) return FORGE_ERR_WORKSPACE;
@@ -378,6 +385,7 @@ forge_status forge_attn_decode_varlen(const void* q, const void* k, const void* 
   if (batch < 1 || q_heads < 1 || kv_heads < 1 || max_pos < 0 || max_pos == INT32_MAX) return FORGE_ERR_INVALID_ARG;
   if (q_heads % kv_heads != 0) return FORGE_ERR_INVALID_ARG;
   if (head_dim != 64 && head_dim != 128) return FORGE_ERR_UNSUPPORTED;
+  if (!grid_ok(batch, q_heads)) return FORGE_ERR_UNSUPPORTED;
   const int kv_len = max_pos + 1;
   if (kv_head_stride < (int64_t)kv_len * head_dim || kv_batch_stride < kv_head_stride * kv_heads)
     return FORGE_ERR_INVALID_ARG;
@@ -399,6 +407,7 @@ forge_status forge_decoder_block_decode(const forge_block_desc* desc, const void
   if (!req(x_in) || !req(x_out) || !req(k_cache) || !req(v_cache) || !req(workspace) || !seq_pos_ok(seq_pos))
     return FORGE_ERR_INVALID_ARG;
   if (batch < 1 || max_pos < 0 || max_pos >= kv_cap) return FORGE_ERR_INVALID_ARG;
+  if (!grid_ok(batch, desc->q_heads)) return FORGE_ERR_UNSUPPORTED;
   if (workspace_bytes < plan_block(desc, batch, 1, kv_cap).total) return FORGE_ERR_WORKSPACE;
   return run_block(desc, x_in, x_out, k_cache, v_cache, batch, 1, max_pos, kv_cap, workspace,
                    static_cast<hipStream_t>(stream), seq_pos);

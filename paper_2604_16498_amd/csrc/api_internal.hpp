@@ -10,6 +10,20 @@ inline bool dtype_ok(forge_dtype dt) { return dt == FORGE_F32 || dt == FORGE_BF1
 inline bool req(const void* p) { return p != nullptr && aligned16(p); }
 inline bool opt(const void* p) { return p == nullptr || aligned16(p); }
 
+// Size limits of one call (beyond them: FORGE_ERR_UNSUPPORTED).  Row counts and element offsets
+// are 64-bit inside the kernels; these bounds keep tile counts and thread counts inside 32 bits
+// and batch / head counts inside a grid dimension.
+constexpr int64_t kMaxRows = 1ll << 24;        // batch * q_len, GEMM rows, GEMM columns
+constexpr int64_t kMaxOutputs = 1ll << 36;     // GEMM rows * columns
+constexpr int kMaxGridDim = 65535;             // batch, heads
+inline bool rows_ok(int batch, int q_len) { return (int64_t)batch * q_len <= kMaxRows; }
+inline bool grid_ok(int batch, int heads) { return batch <= kMaxGridDim && heads <= kMaxGridDim; }
+inline bool gemm_size_ok(int M, int N) {
+  return M <= kMaxRows && N <= kMaxRows && (int64_t)M * N <= kMaxOutputs;
+}
+// rows [pos0, pos0 + n) lie inside [0, cap), without overflowing the sum
+inline bool span_ok(int pos0, int n, int cap) { return pos0 >= 0 && n >= 1 && n <= cap && pos0 <= cap - n; }
+
 // carve 256-byte aligned pieces out of one workspace
 struct Carver {
   char* base;
@@ -52,6 +66,7 @@ inline forge_status check_block_desc(const forge_block_desc* d) {
   if (d->d_model < 8 || d->q_heads < 1 || d->kv_heads < 1 || d->d_ff < 8) return FORGE_ERR_INVALID_ARG;
   if (d->q_heads % d->kv_heads != 0) return FORGE_ERR_INVALID_ARG;
   if (d->head_dim != 64 && d->head_dim != 128) return FORGE_ERR_UNSUPPORTED;
+  if (d->q_heads > kMaxGridDim || d->d_ff > kMaxRows) return FORGE_ERR_UNSUPPORTED;
   if (d->d_model % 8 != 0 || d->d_ff % 8 != 0 || d->d_model > 16384) return FORGE_ERR_UNSUPPORTED;
   if (d->mlp_act != FORGE_ACT_GELU_TANH && d->mlp_act != FORGE_ACT_SWIGLU &&
       d->mlp_act != FORGE_ACT_RELU && d->mlp_act != FORGE_ACT_SILU && d->mlp_act != FORGE_ACT_GELU_ERF)
@@ -90,6 +105,7 @@ inline forge_status check_model(const forge_model_desc* m) {
   if ((m->wte == nullptr) != (m->wpe == nullptr)) return FORGE_ERR_INVALID_ARG;
   if (m->wte != nullptr && (!req(m->wte) || !req(m->wpe) || m->vocab < 1 || m->n_pos < 1))
     return FORGE_ERR_INVALID_ARG;
+  if (m->wte != nullptr && m->vocab > kMaxRows) return FORGE_ERR_UNSUPPORTED;
   if (m->logits_ld != 0 && m->logits_ld < m->vocab) return FORGE_ERR_INVALID_ARG;
   return FORGE_OK;
 }

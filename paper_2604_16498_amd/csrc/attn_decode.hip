@@ -280,20 +280,9 @@ __global__ __launch_bounds__(DH) void attn_decode_combine(const float* __restric
 
 // Number of row ranges: about two blocks per compute unit, at most one range per GRAIN rows.
 struct SplitPlan { int splits, rows_per_split; };
-inline int decode_cus() {
-  static int cus = 0;     // same value on every device of a homogeneous node
-  if (cus == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-      v = 256;
-    cus = v;
-  }
-  return cus;
-}
 inline SplitPlan plan_splits(int batch, int kv_heads, int kv_len) {
   const int64_t pairs = (int64_t)batch * kv_heads;
-  const int64_t for_two_per_cu = ceil_div64(2 * (int64_t)decode_cus(), pairs);
+  const int64_t for_two_per_cu = ceil_div64(2 * (int64_t)compute_units(), pairs);
   int want = for_two_per_cu < MAX_SPLITS ? (int)for_two_per_cu : MAX_SPLITS;
   want = max(1, min(want, ceil_div(kv_len, GRAIN)));
   const int rows = ceil_div(ceil_div(kv_len, want), GRAIN) * GRAIN;

@@ -179,13 +179,8 @@ forge_status launch_f32(const AttnArgs& a, hipStream_t s) {
   constexpr int NW = F32Cfg<DH>::NW;
   constexpr int smem = NW * 2 * F32_BK * (DH + 4) * (int)sizeof(float);
   auto kern = attn_f32_kernel<DH>;
-  static bool configured = false;   // idempotent attribute, set once per instantiation
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-      return FORGE_ERR_HIP;
-    configured = true;
-  }
+  static std::atomic<uint64_t> lds_raised{0};   // per kernel instantiation
+  if (raise_lds_limit(reinterpret_cast<const void*>(kern), smem, lds_raised) != FORGE_OK) return FORGE_ERR_HIP;
   dim3 grid(ceil_div(a.q_len, F32_BQ), a.q_heads, a.batch), block(NW * 64);
   kern<<<grid, block, smem, s>>>((const float*)a.q, (const float*)a.k, (const float*)a.v, (float*)a.out,
                                  a.q_heads, a.kv_heads, a.q_len, a.kv_len, a.kv_batch_stride,

@@ -365,13 +365,8 @@ forge_status launch_dh(const AttnArgs& a, hipStream_t s) {
   p.mask_hs = a.mask_head_stride;
   constexpr int smem = 2 * 64 * ((DH * 2 + 16) + (DH * 2 + 64));
   auto kern = attn_prefill_kernel<DH, MASKED>;
-  static bool configured = false;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-      return FORGE_ERR_HIP;
-    configured = true;
-  }
+  static std::atomic<uint64_t> lds_raised{0};   // per kernel instantiation
+  if (raise_lds_limit(reinterpret_cast<const void*>(kern), smem, lds_raised) != FORGE_OK) return FORGE_ERR_HIP;
   dim3 grid(a.q_heads * a.batch, p.n_qblocks), block(512);
   kern<<<grid, block, smem, s>>>(p);
   return launch_status();

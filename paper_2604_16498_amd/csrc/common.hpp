@@ -4,6 +4,8 @@
 #include <stdint.h>
 #include <stddef.h>
 
+#include <atomic>
+
 #include "../../include/forge.h"
 
 namespace forge {
@@ -115,6 +117,33 @@ template <int ACT> __device__ inline float apply_act(float x) {
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline forge_status launch_status() {
   return hipGetLastError() == hipSuccess ? FORGE_OK : FORGE_ERR_HIP;
+}
+
+// Compute units of the current device (256 when no device answers, e.g. a size query on a
+// host without a GPU).  Read once: the launch heuristics assume a homogeneous node.
+inline int compute_units() {
+  static const int cus = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      v = 256;
+    return v;
+  }();
+  return cus;
+}
+
+// Raise a kernel's dynamic-LDS limit to `bytes`, once per device: the attribute belongs to the
+// (kernel, device) pair.  `done` is a bit mask over device ordinals owned by the caller (one per
+// kernel instantiation); callers may race, setting the attribute twice is harmless.
+inline forge_status raise_lds_limit(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return FORGE_ERR_HIP;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return FORGE_OK;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+    return FORGE_ERR_HIP;
+  done.fetch_or(bit, std::memory_order_release);
+  return FORGE_OK;
 }
 
 // ---- internal launchers (one per kernel family; defined in the .hip files) ---------------

@@ -251,8 +251,9 @@ forge_status forge_compile_model(const forge_model_desc* model, int batch, int q
   *out = nullptr;
   forge_status st = check_model(model);
   if (st != FORGE_OK) return st;
-  if (batch < 1 || q_len < 1 || pos0 < 0 || pos0 + q_len > kv_cap) return FORGE_ERR_INVALID_ARG;
-  if (model->wte != nullptr && pos0 + q_len > model->n_pos) return FORGE_ERR_INVALID_ARG;
+  if (batch < 1 || !span_ok(pos0, q_len, kv_cap)) return FORGE_ERR_INVALID_ARG;
+  if (model->wte != nullptr && !span_ok(pos0, q_len, model->n_pos)) return FORGE_ERR_INVALID_ARG;
+  if (!grid_ok(batch, 1) || !rows_ok(batch, q_len)) return FORGE_ERR_UNSUPPORTED;
   forge_compiled* c = nullptr;
   try {
     c = new forge_compiled();

@@ -862,20 +862,6 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p, int sp
   }
 }
 
-// Persistent launch: one block per resident slot (the 256 x 256 tile fills a CU, two 128 x 128
-// blocks share one), in multiples of the 8 XCDs.
-inline int compute_units() {
-  static int cus = 0;     // same value on every device of a homogeneous node
-  if (cus == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-      v = 256;
-    cus = v;
-  }
-  return cus;
-}
-
 // Split-K second stage of the QKV projection with the rotary embedding applied to the q and k
 // heads before the single rounding to bf16.  One thread owns 4 consecutive pair indices of one
 // head of one row: columns d..d+3 and d+dh/2..d+dh/2+3.  Angles as in rope_kernel: fp64
@@ -1010,18 +996,15 @@ forge_status launch_generic(const GemmParams& p0, int splits, hipStream_t s) {
   p.tiles_n = ceil_div(p.N, BN_OUT);
   constexpr int smem = 2 * (BM + BN) * BK * 2;
   auto kern = gemm_bf16_generic_kernel<BM, BN, WM, WN, ACT, MODE>;
-  static bool configured = false;   // idempotent attribute, set once per instantiation
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-      return FORGE_ERR_HIP;
-    configured = true;
-  }
+  static std::atomic<uint64_t> lds_raised{0};   // per kernel instantiation
+  if (raise_lds_limit(reinterpret_cast<const void*>(kern), smem, lds_raised) != FORGE_OK) return FORGE_ERR_HIP;
   dim3 grid(p.tiles_m * p.tiles_n, splits), block(WM * WN * 64);
   kern<<<grid, block, smem, s>>>(p);
   return launch_status();
 }
 
+// Persistent launch: one block per resident slot (the 256 x 256 tile fills a CU, two 128 x 128
+// blocks share one), in multiples of the 8 XCDs.
 template <int BM, int BN, int WM, int WN, int ACT, int MODE>
 forge_status launch_pers(const GemmParams& p0, hipStream_t s) {
   GemmParams p = p0;
@@ -1031,13 +1014,8 @@ forge_status launch_pers(const GemmParams& p0, hipStream_t s) {
   constexpr int smem = 2 * (BM + BN) * BK * 2;
   constexpr int per_cu = smem <= 80 * 1024 ? 2 : 1;
   auto kern = gemm_bf16_pers_kernel<BM, BN, WM, WN, ACT, MODE>;
-  static bool configured = false;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-      return FORGE_ERR_HIP;
-    configured = true;
-  }
+  static std::atomic<uint64_t> lds_raised{0};   // per kernel instantiation
+  if (raise_lds_limit(reinterpret_cast<const void*>(kern), smem, lds_raised) != FORGE_OK) return FORGE_ERR_HIP;
   const int slots = compute_units() * per_cu / 8 * 8;
   const int nitems = p.tiles_m * p.tiles_n * (MODE == MODE_SPLITK ? p.splits : 1);
   const int blocks = min(slots, (nitems + 7) / 8 * 8);
@@ -1111,13 +1089,8 @@ template <int BN, bool W8>
 forge_status launch_wstream(const GemmParams& q, int splits, hipStream_t s) {
   using C = WStream<BN, W8>;
   auto kern = gemm_bf16_wstream_kernel<BN, W8>;
-  static bool configured = false;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM) != hipSuccess)
-      return FORGE_ERR_HIP;
-    configured = true;
-  }
+  static std::atomic<uint64_t> lds_raised{0};   // per kernel instantiation
+  if (raise_lds_limit(reinterpret_cast<const void*>(kern), C::SMEM, lds_raised) != FORGE_OK) return FORGE_ERR_HIP;
   kern<<<dim3(ceil_div(q.N, BN), splits), C::NWV * 64, C::SMEM, s>>>(q);
   return launch_status();
 }

@@ -70,6 +70,17 @@ def test_argument_errors_are_caught_on_the_host():
     assert l.forge_attn_fused(*a, 1, 4, 4, 8, 8, 32, 4 * 8 * 32, 8 * 32, 0.1, 1, 1, None, 0, None) == 2
     assert l.forge_attn_fused(*a, 1, 4, 3, 8, 8, 64, 3 * 8 * 64, 8 * 64, 0.1, 1, 1, None, 0, None) == 1
     assert l.forge_attn_fused(*a, 1, 4, 4, 8, 4, 64, 4 * 4 * 64, 4 * 64, 0.1, 1, 1, None, 0, None) == 1
+    # size limits: batch or heads past a grid dimension, too many rows, too many GEMM outputs
+    assert l.forge_attn_fused(*a, 65536, 4, 4, 8, 8, 64, 4 * 8 * 64, 8 * 64, 0.1, 1, 1, None, 0, None) == 2
+    assert l.forge_attn_fused(*a, 1, 65536, 65536, 8, 8, 64, 65536 * 8 * 64, 8 * 64, 0.1, 1, 1, None, 0, None) == 2
+    assert l.forge_attn_fused(*a, 4096, 4, 4, 8192, 8192, 64, 4 * 8192 * 64, 8192 * 64, 0.1, 1, 1, None, 0, None) == 2
+    assert l.forge_attn_fused_workspace_bytes(65536, 4, 4, 1, 8, 64, 1) == 0
+    assert l.forge_gemm_bias_gelu(good, vp(0x2000), None, None, vp(0x3000), (1 << 24) + 1, 8, 16, 0, 0, 1, None, 0, None) == 2
+    assert l.forge_gemm_bias_gelu(good, vp(0x2000), None, None, vp(0x3000), 1 << 20, 1 << 20, 16, 0, 0, 1, None, 0, None) == 2
+    assert l.forge_gemm_workspace_bytes(1 << 20, 1 << 20, 16, 0, 1) == 0
+    # positions: pos0 + seq must not wrap around
+    assert l.forge_embed(good, vp(0x2000), vp(0x3000), vp(0x4000), 1, 2, 64, 100, 512, 2**31 - 1, 1, None) == 1
+    assert l.forge_embed(good, vp(0x2000), vp(0x3000), vp(0x4000), 1, 8, 64, 100, 512, 505, 1, None) == 1
     # block: NULL descriptor; workspace size of an invalid descriptor is 0
     assert l.forge_decoder_block(None, good, good, good, good, 1, 1, 0, 1, good, 0, None) == 1
     d = B.BlockDesc()

@@ -201,6 +201,9 @@ def test_compile_rejects_bad_arguments():
     assert l.forge_compile_model(C.byref(model), 1, 128, 8, 128, C.byref(h)) == 1      # past the cache
     assert l.forge_compile_model(C.byref(model), 1, 128, 0, 1024, None) == 1
     assert l.forge_compile_model(C.byref(model), 1, 600, 0, 1024, C.byref(h)) == 1     # past n_pos = 512
+    assert l.forge_compile_model(C.byref(model), 1, 2, 2**31 - 1, 1024, C.byref(h)) == 1  # pos0 + q_len wraps
+    assert l.forge_compile_model(C.byref(model), 70000, 1, 0, 128, C.byref(h)) == 2       # batch past a grid dimension
+    assert l.forge_compile_model(C.byref(model), 40000, 512, 0, 512, C.byref(h)) == 2     # more than 2^24 rows
     assert not h.value
     assert l.forge_compiled_run(None, None) == 1
     cm = B.CompiledModel(model, 1, 128, 0, 128)
