@@ -34,8 +34,10 @@ torch CPU fp64 library routines as special cases.
 Weight-only int8: quantize_int8 / dequantize_int8 (pins: half-step error bound, grid
 weights returned exactly, sign symmetry, idempotence, pure-Python loops); a quantised linear is
 `linear` on the dequantised weight.
-Parity unpinned: the RoPE pairing convention (rotate-half) and the GQA grouping
-order (contiguous groups) are conventions, fixed only by the docstrings below.
+The two conventions the paper leaves open are pinned by library routines: the GQA
+grouping order (contiguous groups) by torch's grouped-query scaled_dot_product_attention,
+the RoPE pairing (rotate-half), sign and frequencies by the Llama rotary-embedding
+routines of the `transformers` package (to the fp32 precision of that module's angles).
 """
 from __future__ import annotations
 

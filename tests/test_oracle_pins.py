@@ -178,6 +178,35 @@ def test_rope_known_quarter_turn():
     assert np.allclose(r[:, 0], np.cos([1, 2, 3])) and np.allclose(r[:, 1], np.sin([1, 2, 3]))
 
 
+def test_rope_convention_vs_llama_reference_routines():
+    """The pairing (i, i + dh/2), the sign of the rotation and theta_i = base^(-2i/dh) are the
+    convention of the Llama family.  The rotary-embedding module and `apply_rotary_pos_emb` of the
+    `transformers` package (a library, nothing of ours) apply it to the same q and k; the module
+    keeps its inverse frequencies in fp32, hence 1e-5 and not 1e-13 - an interleaved pairing, a
+    flipped sign or a different exponent is off by O(1)."""
+    tf = pytest.importorskip("transformers")
+    from transformers.models.llama.modeling_llama import LlamaRotaryEmbedding, apply_rotary_pos_emb
+    dh, H, base = 16, 2, 500000.0
+    cfg = tf.LlamaConfig(hidden_size=H * dh, num_attention_heads=H, num_key_value_heads=H, rope_theta=base,
+                         max_position_embeddings=4096, num_hidden_layers=1, intermediate_size=8, vocab_size=8)
+    rot = LlamaRotaryEmbedding(config=cfg)
+    pos = np.array([0, 1, 2, 5, 9, 33, 63, 2048])
+    q, k = rnd(1, H, len(pos), dh), rnd(1, H, len(pos), dh)
+    tq, tk = torch.from_numpy(q), torch.from_numpy(k)
+    cos, sin = rot(tq, torch.from_numpy(pos)[None, :])
+    q_lib, k_lib = apply_rotary_pos_emb(tq, tk, cos.double(), sin.double())
+    # position 2048 times an fp32 frequency: the angle itself carries ~1e-4 of rounding
+    tol = np.where(pos[:, None] > 100, 2e-3, 1e-5)
+    assert np.all(np.abs(q_lib.numpy() - O.rope(q, pos, base)) < tol)
+    assert np.all(np.abs(k_lib.numpy() - O.rope(k, pos, base)) < tol)
+    # the check has teeth: the interleaved pairing (2i, 2i+1) of the same angles is far away
+    half = dh // 2
+    perm = np.concatenate([np.arange(0, dh, 2), np.arange(1, dh, 2)])
+    inter = np.empty_like(q)
+    inter[..., perm] = O.rope(q[..., perm], pos, base)
+    assert np.abs(inter[:, :, 1:] - q_lib.numpy()[:, :, 1:]).max() > 0.1
+
+
 # ---------------------------------------------------------------------------
 # norms
 # ---------------------------------------------------------------------------
