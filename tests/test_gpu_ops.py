@@ -242,6 +242,11 @@ ATTN_SHAPES = [  # B, Hq, Hkv, Sq, Skv, cap, dh
     (1, 8, 4, 1, 700, 704, 64),
     (1, 6, 2, 1, 300, 300, 128),
     (2, 4, 4, 1, 257, 257, 128),
+    # decode with many (sequence, KV head) pairs: one block walks the whole cache, no combine
+    (66, 8, 8, 1, 777, 800, 64),
+    (130, 8, 4, 1, 45, 64, 128),
+    # ... and with about one pair per CU: two row ranges
+    (33, 32, 8, 1, 1000, 1000, 128),
 ]
 
 
