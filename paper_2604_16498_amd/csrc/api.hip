@@ -33,15 +33,23 @@ BlockPlan plan_block(const forge_block_desc* d, int batch, int q_len, int kv_cap
   return p;
 }
 
+// where a layer keeps its normalised rows: the first piece carved from its workspace
+inline void* block_norm_rows(void* workspace) { return workspace; }
+
 // the launch list of one layer; all arguments already validated
 // seq_pos (device, [batch], or NULL): per-sequence positions of a decode step (q_len == 1); pos0 is
 // then the largest position the caller vouches for
+// next_norm / x_normed chain the layers of a decode-sized stack (only where gemm_fuses_tail()
+// holds for the model width): the reduce step of the MLP down projection also produces the rows
+// the NEXT consumer normalises (next layer's first norm, or the model's final norm) into
+// next_norm->y_norm, and a layer called with x_normed finds its first norm already done.
 forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out, void* k_cache,
                        void* v_cache, int batch, int q_len, int pos0, int kv_cap, void* workspace,
-                       hipStream_t s, const int* seq_pos = nullptr) {
+                       hipStream_t s, const int* seq_pos = nullptr, const NormTail* next_norm = nullptr,
+                       bool x_normed = false) {
   const BlockPlan pl = plan_block(d, batch, q_len, kv_cap);
   Carver cv(workspace);
-  void* y = cv.take(pl.y);
+  void* y = cv.take(pl.y);          // == block_norm_rows(workspace)
   void* q = cv.take(pl.q);
   void* o = cv.take(pl.o);
   void* u = cv.take(pl.u);
@@ -53,9 +61,11 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
   const int64_t kv_hs = (int64_t)kv_cap * dh, kv_bs = kv_hs * d->kv_heads;
   forge_status st;
 
-  // 1. first norm
-  st = launch_residual_norm(x_in, nullptr, d->norm1_g, d->norm1_b, nullptr, y, T, dm, d->eps, d->norm, d->dt, s);
-  if (st != FORGE_OK) return st;
+  // 1. first norm (unless the previous layer's last reduce step left it in y)
+  if (!x_normed) {
+    st = launch_residual_norm(x_in, nullptr, d->norm1_g, d->norm1_b, nullptr, y, T, dm, d->eps, d->norm, d->dt, s);
+    if (st != FORGE_OK) return st;
+  }
   // 2. QKV projection, written head-major: q to the workspace, k and v into the cache rows
   // (a decode-sized QKV projection rotates q and k in its own reduce step)
   const bool rope_in_gemm = d->use_rope && gemm_fuses_tail(T, nqkv, d->dt);
@@ -96,7 +106,8 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
   // 8. MLP down projection + bias + residual
-  g = GemmArgs{u, d->w_down, d->b_down, x_out, x_out, T, dm, d->d_ff, 0, FORGE_ACT_NONE, nullptr, nullptr, gws, pl.gemm, d->s_down};
+  //    (+ the next consumer's norm of the new residual stream, see above)
+  g = GemmArgs{u, d->w_down, d->b_down, x_out, x_out, T, dm, d->d_ff, 0, FORGE_ACT_NONE, nullptr, next_norm, gws, pl.gemm, d->s_down};
   return gemm_dispatch(g, d->dt, s);
 }
 
@@ -348,16 +359,28 @@ static forge_status model_forward(const forge_model_desc* model, const void* inp
     if (st != FORGE_OK) return st;
     x = h;
   }
+  // decode-sized steps: every norm after the first rides on the reduce step of the projection
+  // before it (one launch less per layer, and the norm sees the fp32 sum before it is rounded)
+  const bool chain = gemm_fuses_tail(T, dm, dt);
   for (int l = 0; l < model->n_layers; ++l) {
+    NormTail nt;
+    if (chain) {
+      const forge_block_desc* nx = l + 1 < model->n_layers ? &model->layers[l + 1] : nullptr;
+      nt = nx != nullptr ? NormTail{nx->norm1_g, nx->norm1_b, block_norm_rows(bws), nx->eps, nx->norm}
+                         : NormTail{model->normf_g, model->normf_b, yf, d0->eps, d0->norm};
+    }
     st = run_block(&model->layers[l], x, h, static_cast<char*>(k_cache) + l * layer_kv_bytes,
                    static_cast<char*>(v_cache) + l * layer_kv_bytes, batch, q_len, pos0, kv_cap, bws, s,
-                   seq_pos);
+                   seq_pos, chain ? &nt : nullptr, chain && l > 0);
     if (st != FORGE_OK) return st;
     x = h;
   }
-  st = launch_residual_norm(h, nullptr, model->normf_g, model->normf_b, nullptr, yf, T, dm, d0->eps,
-                            d0->norm, dt, s);
-  if (st != FORGE_OK || !tokens) return st;
+  if (!chain) {
+    st = launch_residual_norm(h, nullptr, model->normf_g, model->normf_b, nullptr, yf, T, dm, d0->eps,
+                              d0->norm, dt, s);
+    if (st != FORGE_OK) return st;
+  }
+  if (!tokens) return FORGE_OK;
   // tied LM head: the token table is the weight of the last projection
   GemmArgs g = {yf, model->wte, nullptr, nullptr, output, T, model->vocab, dm, model->logits_ld, FORGE_ACT_NONE,
                 nullptr, nullptr, bws, pl.block};

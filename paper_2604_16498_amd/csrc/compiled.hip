@@ -29,7 +29,9 @@ struct Instr {
   int out;     // result register, REG_EXT = caller's output, REG_NONE = works in place / on the cache
   int x;       // main operand
   int res;     // residual operand
-  int aux;     // second result (normalised rows of a fused output projection)
+  int aux;     // second result: the rows the next consumer normalises (output projection: the
+               // layer's second norm; MLP down: the next layer's first norm or the final norm,
+               // REG_EXT when that is the caller's output)
   int ws;      // scratch register
 };
 
@@ -91,6 +93,10 @@ void lower(forge_compiled* c) {
     h = lo.new_reg(h_bytes);
     lo.emit({FORGE_OP_EMBED, -1, 0, h, REG_EXT, REG_NONE, REG_NONE, REG_NONE}, {});
   }
+  // decode-sized steps chain the norms: the reduce step of a layer's MLP down projection also
+  // produces what the next consumer normalises (the plain launcher does the same)
+  const bool chain = gemm_fuses_tail(Ti, dm, dt);
+  int y_chained = REG_NONE;
   for (int l = 0; l < m.n_layers; ++l) {
     const forge_block_desc& d = c->layers[l];
     const int hd = d.q_heads * d.head_dim, nqkv = (d.q_heads + 2 * d.kv_heads) * d.head_dim;
@@ -98,8 +104,11 @@ void lower(forge_compiled* c) {
     const bool norm_in_gemm = gemm_fuses_tail(Ti, dm, dt);
     const bool w8 = block_w8(&d);
 
-    const int y = lo.new_reg(h_bytes);
-    lo.emit({FORGE_OP_NORM, l, 0, y, h, REG_NONE, REG_NONE, REG_NONE}, {h});
+    int y = y_chained;
+    if (!chain || l == 0) {
+      y = lo.new_reg(h_bytes);
+      lo.emit({FORGE_OP_NORM, l, 0, y, h, REG_NONE, REG_NONE, REG_NONE}, {h});
+    }
     const int q = lo.new_reg(T * hd * es);
     int ws = lo.new_reg(gemm_ws(Ti, nqkv, dm, FORGE_ACT_NONE, dt, w8));
     lo.emit({FORGE_OP_GEMM_QKV, l, rope_in_gemm ? 1 : 0, q, y, REG_NONE, REG_NONE, ws}, {y, ws});
@@ -125,17 +134,31 @@ void lower(forge_compiled* c) {
     const int u = lo.new_reg(T * d.d_ff * es);
     ws = lo.new_reg(gemm_ws(Ti, d.d_ff, dm, d.mlp_act, dt, w8));
     lo.emit({FORGE_OP_GEMM_ACT, l, 0, u, y2, REG_NONE, REG_NONE, ws}, {y2, ws});
-    const int h_out = lo.new_reg(h_bytes);
-    ws = lo.new_reg(gemm_ws(Ti, dm, d.d_ff, FORGE_ACT_NONE, dt, w8));
-    lo.emit({FORGE_OP_GEMM_RES, l, 1, h_out, u, h_mid, REG_NONE, ws}, {u, h_mid, ws});
-    h = h_out;
+    if (chain && l + 1 == m.n_layers && !tokens) {
+      // the final norm is the caller's output; nobody reads the last residual stream, which is
+      // added in place (no register of its own)
+      y_chained = REG_EXT;
+      ws = lo.new_reg(gemm_ws(Ti, dm, d.d_ff, FORGE_ACT_NONE, dt, w8));
+      lo.emit({FORGE_OP_GEMM_RES, l, 1, REG_NONE, u, h_mid, y_chained, ws}, {u, h_mid, ws});
+      h = h_mid;
+    } else {
+      const int h_out = lo.new_reg(h_bytes);
+      if (chain) y_chained = lo.new_reg(h_bytes);
+      ws = lo.new_reg(gemm_ws(Ti, dm, d.d_ff, FORGE_ACT_NONE, dt, w8));
+      lo.emit({FORGE_OP_GEMM_RES, l, 1, h_out, u, h_mid, chain ? y_chained : REG_NONE, ws},
+              {u, h_mid, chain ? y_chained : REG_NONE, ws});
+      h = h_out;
+    }
   }
   if (tokens) {
-    const int yf = lo.new_reg(h_bytes);
-    lo.emit({FORGE_OP_NORM, -1, 2, yf, h, REG_NONE, REG_NONE, REG_NONE}, {h});
+    int yf = y_chained;
+    if (!chain) {
+      yf = lo.new_reg(h_bytes);
+      lo.emit({FORGE_OP_NORM, -1, 2, yf, h, REG_NONE, REG_NONE, REG_NONE}, {h});
+    }
     const int ws = lo.new_reg(gemm_ws(Ti, m.vocab, dm, FORGE_ACT_NONE, dt, false));
     lo.emit({FORGE_OP_GEMM, -1, 0, REG_EXT, yf, REG_NONE, REG_NONE, ws}, {yf, ws});
-  } else {
+  } else if (!chain) {
     lo.emit({FORGE_OP_NORM, -1, 2, REG_EXT, h, REG_NONE, REG_NONE, REG_NONE}, {h});
   }
 
@@ -206,11 +229,17 @@ forge_status run_program(const forge_compiled* c, hipStream_t s) {
         break;
       }
       case FORGE_OP_GEMM_RES: {
-        NormTail nt = {d->norm2_g, d->norm2_b, out(I.aux), d->eps, d->norm};
         const bool o_proj = I.which == 0;
+        // whose norm rides on this projection: the layer's second, the next layer's first, the final one
+        const forge_block_desc* nx = I.layer + 1 < m.n_layers ? &c->layers[I.layer + 1] : nullptr;
+        NormTail nt = o_proj ? NormTail{d->norm2_g, d->norm2_b, out(I.aux), d->eps, d->norm}
+                             : (nx != nullptr ? NormTail{nx->norm1_g, nx->norm1_b, out(I.aux), nx->eps, nx->norm}
+                                              : NormTail{m.normf_g, m.normf_b, out(I.aux), d0.eps, d0.norm});
+        // out == REG_NONE: the sum replaces the residual operand
+        void* y = I.out == REG_NONE ? const_cast<void*>(in(I.res)) : out(I.out);
         GemmArgs g = {in(I.x), o_proj ? d->w_o : d->w_down, o_proj ? d->b_o : d->b_down, in(I.res),
-                      out(I.out), T, dm, o_proj ? hd : d->d_ff, 0, FORGE_ACT_NONE, nullptr,
-                      I.aux >= 0 ? &nt : nullptr, out(I.ws), bytes(I.ws), o_proj ? d->s_o : d->s_down};
+                      y, T, dm, o_proj ? hd : d->d_ff, 0, FORGE_ACT_NONE, nullptr,
+                      I.aux != REG_NONE ? &nt : nullptr, out(I.ws), bytes(I.ws), o_proj ? d->s_o : d->s_down};
         st = gemm_dispatch(g, dt, s);
         break;
       }

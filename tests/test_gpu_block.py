@@ -180,6 +180,44 @@ def test_model_forward_hidden_llama(F):
     assert l2 < 2e-2 and mx < 6e-2
 
 
+@pytest.mark.parametrize("sh_name", ["llama", "gpt"])
+def test_model_decode_step_hidden_state_stack(F, sh_name):
+    """One decode step of a 3-layer stack fed with hidden states (no token table), against the
+    oracle's layers applied one after the other on the same caches.  In a bf16 step of at most 64
+    rows every norm after the first is produced by the reduce step of the projection before it
+    (the second norm by the output projection, the next layer's first norm and the final norm by
+    the MLP down projection), and the final norm lands in the caller's output."""
+    sh = SMALL_LLAMA if sh_name == "llama" else SMALL_GPT
+    L, B, cap, pos0 = 3, 5, 100, 70
+    wl = I.scaled(I.WORKLOADS[4], block=sh, layers=L, batch=B, seq=1)
+    mw = I.model_weights(wl, random_affine=True)
+    layers = [I.block_weights(sh, 79, l, bf16=True, random_affine=True, weight_std=0.05) for l in range(L)]
+    x = I.normal(79, 0, "x", (B, 1, sh.d_model), 1.0, bf16=True)
+    kc = I.normal(79, 0, "k_cache", (L, B, sh.kv_heads, cap, sh.head_dim), 1.0, bf16=True)
+    vc = I.normal(79, 0, "v_cache", (L, B, sh.kv_heads, cap, sh.head_dim), 1.0, bf16=True)
+    h = x.astype(np.float64)
+    for l in range(L):
+        h = O.decoder_block(sh, layers[l], h, kc[l].astype(np.float64), vc[l].astype(np.float64), pos0=pos0)
+    _, ref = O.residual_norm(h, None, mw["normf_g"], mw.get("normf_b"), sh.eps, sh.norm)
+    tl = [dev_dict(w, True) for w in layers]
+    tm = dev_dict(mw, True)
+    model = F.make_model_desc([F.make_block_desc(sh, w) for w in tl], tm)
+    out = torch.empty(B, 1, sh.d_model, dtype=torch.bfloat16, device="cuda")
+    tk, tv = dev(kc, True), dev(vc, True)
+    ws = F.workspace(F.forge_model_workspace_bytes(model, B, 1, cap))
+    F.forge_model_forward(model, dev(x, True), out, tk, tv, pos0, ws)
+    torch.cuda.synchronize()
+    mx, l2 = rel_err(host(out), ref)
+    print("%s decode stack: max rel %.3e l2 %.3e" % (sh_name, mx, l2))
+    assert l2 < 2e-2 and mx < 6e-2
+    # per-sequence positions: the same step through forge_model_decode
+    out2 = torch.empty_like(out)
+    tk2, tv2 = dev(kc, True), dev(vc, True)
+    F.forge_model_decode(model, dev(x, True), out2, tk2, tv2, torch.full((B,), pos0, dtype=torch.int32, device="cuda"), pos0, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out2, out) and torch.equal(tk2, tk) and torch.equal(tv2, tv)
+
+
 def test_block_wide_model_short_prompt(F):
     """A 100-token prompt through a wide layer (d_model 1024, MLP 4096): every projection has few
     output tiles and a long reduction, i.e. the k-split path of the tile kernel, including the

@@ -140,7 +140,7 @@ def test_compiled_program_and_plan_match_the_oracle(case):
     T = batch * q_len
     small = dt == B.FORGE_BF16 and T <= 64
     prog, kinds = P.decoder_program(L, tokens, rope_separate=shape.use_rope and not small,
-                                    norm2_separate=not small)
+                                    norm2_separate=not small, norm1_separate=not small)
     assert (ni, nr) == (len(prog), len(kinds))
     assert ops == [p[0] for p in prog]
     assert out_reg == [p[1] for p in prog]
