@@ -248,6 +248,10 @@ forge_status forge_decoder_block(const forge_block_desc* desc, const void* x_in,
  * `input` is int32 ids [B,q_len] and `output` receives logits [B,q_len,vocab] with row stride
  * logits_ld (padding columns, if any, are left untouched).
  * k_cache, v_cache: [n_layers,B,Hkv,kv_cap,dh].
+ * In a bf16 step of at most 64 rows (a decode step) the reduce step of a layer's MLP down
+ * projection also produces the next layer's Norm1 (after the last layer: the final norm), so
+ * only the first layer launches a norm of its own: same results up to rounding order (the norm
+ * takes the fp32 sum before it is rounded to bf16).
  * ------------------------------------------------------------------------------------ */
 typedef struct {
   int n_layers, vocab, n_pos;
