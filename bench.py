@@ -253,7 +253,7 @@ def main():
         print(json.dumps(rec, indent=1))
         return
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+        print("bench.py: the library runs on ONE GPU only (no collectives, no sharding); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
     import torch
