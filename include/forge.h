@@ -144,6 +144,15 @@ forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias
                                   forge_act act, forge_dtype dt,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* A gated weight whose rows alternate (gate 0, up 0, gate 1, up 1, ...) re-laid once, out of
+ * place, into the layout FORGE_ACT_SWIGLU takes (all gate rows, then all up rows): row r of
+ * dst = row 2r of src, row n_pairs + r of dst = row 2r + 1 of src, rows of row_bytes bytes
+ * (K * element size for a weight, the element size for a bias; any element type, int8 rows and
+ * their fp32 scales included).  src, dst: device pointers to 2 * n_pairs rows each, not
+ * overlapping (FORGE_ERR_INVALID_ARG); no alignment required. */
+forge_status forge_deinterleave_gated_rows(const void* src, void* dst, int n_pairs, size_t row_bytes,
+                                          void* stream);
+
 /* ---------------------------------------------------------------------------------------
  * Weight-only int8 (Sec. "Precision Strategy for Llama-3.1-8B": symmetric int8 weights with
  * 16-bit activations).  The paper gives no granularity or rounding; taken here: one fp32 scale

@@ -65,6 +65,7 @@ SIGNATURES = {
     "forge_gemm_variant": (C.c_char_p, [_i, _i, _i, _i, _i, _i]),
     "forge_gemm_bias_gelu": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
     "forge_quantize_int8": (_i, [_vp, _vp, _vp, _i, _i, _i, _vp]),
+    "forge_deinterleave_gated_rows": (_i, [_vp, _vp, _i, C.c_size_t, _vp]),
     "forge_gemm_w8_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "forge_gemm_w8": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
     "forge_residual_norm": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _f, _i, _i, _vp]),
@@ -207,6 +208,16 @@ def forge_gemm_bias_gelu(x, w, bias, residual, y, act="gelu_tanh", workspace=Non
     _check(lib().forge_gemm_bias_gelu(_p(x), _p(w), _p(bias), _p(residual), _p(y), M, N, K, ldy,
                                       ACT[act], _dt(x), wp, wb, _stream()), "forge_gemm_bias_gelu")
     return y
+
+
+def forge_deinterleave_gated_rows(src):
+    """src [2N, ...] with alternating gate / up rows -> new tensor, gate rows first."""
+    assert src.is_cuda and src.is_contiguous() and src.shape[0] % 2 == 0
+    dst = torch.empty_like(src)
+    row_bytes = src[0].numel() * src.element_size()
+    _check(lib().forge_deinterleave_gated_rows(_p(src), _p(dst), src.shape[0] // 2, row_bytes, _stream()),
+           "forge_deinterleave_gated_rows")
+    return dst
 
 
 def forge_quantize_int8(w):

@@ -235,6 +235,17 @@ forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias
   return gemm_dispatch(a, dt, static_cast<hipStream_t>(stream));
 }
 
+forge_status forge_deinterleave_gated_rows(const void* src, void* dst, int n_pairs, size_t row_bytes,
+                                          void* stream) {
+  if (src == nullptr || dst == nullptr || n_pairs < 1 || row_bytes < 1) return FORGE_ERR_INVALID_ARG;
+  if (n_pairs > (1 << 30) || row_bytes > ((size_t)1 << 40)) return FORGE_ERR_UNSUPPORTED;
+  // out of place: the two 2 * n_pairs * row_bytes ranges must not overlap
+  const uintptr_t a = reinterpret_cast<uintptr_t>(src), b = reinterpret_cast<uintptr_t>(dst);
+  const size_t total = 2 * (size_t)n_pairs * row_bytes;
+  if ((a <= b ? b - a : a - b) < total) return FORGE_ERR_INVALID_ARG;
+  return launch_deinterleave_rows(src, dst, n_pairs, row_bytes, static_cast<hipStream_t>(stream));
+}
+
 size_t forge_gemm_w8_workspace_bytes(int M, int N, int K, forge_act act) {
   if (M < 1 || N < 1 || K < 1 || !gemm_size_ok(M, N)) return 0;
   return gemm_ws(M, N, K, act, FORGE_BF16, true);

@@ -10,6 +10,9 @@ inline bool dtype_ok(forge_dtype dt) { return dt == FORGE_F32 || dt == FORGE_BF1
 inline bool req(const void* p) { return p != nullptr && aligned16(p); }
 inline bool opt(const void* p) { return p == nullptr || aligned16(p); }
 
+// rows (2r, 2r + 1) of src -> rows (r, pairs + r) of dst (defined with the elementwise kernels)
+forge_status launch_deinterleave_rows(const void* src, void* dst, int pairs, size_t row_bytes, hipStream_t s);
+
 // Size limits of one call (beyond them: FORGE_ERR_UNSUPPORTED).  Row counts and element offsets
 // are 64-bit inside the kernels; these bounds keep tile counts and thread counts inside 32 bits
 // and batch / head counts inside a grid dimension.

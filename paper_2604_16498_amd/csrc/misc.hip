@@ -1,6 +1,7 @@
-// Rotary position embedding (in place), token + position embedding, and the one-time int8
-// quantisation of a weight.  HBM-bound elementwise kernels.
-#include "common.hpp"
+// Rotary position embedding (in place), token + position embedding, the one-time int8
+// quantisation of a weight and the one-time re-layout of an interleaved gated weight.  HBM-bound
+// elementwise kernels.
+#include "api_internal.hpp"
 
 namespace forge {
 namespace {
@@ -105,7 +106,31 @@ __global__ __launch_bounds__(256) void quantize_int8_kernel(const T* __restrict_
   }
 }
 
+// Destination row r < pairs takes source row 2r, destination row pairs + r takes source row
+// 2r + 1.  One block per destination row; 16-byte copies when rows and pointers allow.
+__global__ __launch_bounds__(256) void deinterleave_rows_kernel(const char* __restrict__ src,
+                                                                char* __restrict__ dst, int pairs,
+                                                                int64_t row_bytes, int vec) {
+  const int r = blockIdx.x;
+  const int64_t s = r < pairs ? 2 * (int64_t)r : 2 * (int64_t)(r - pairs) + 1;
+  const char* a = src + s * row_bytes;
+  char* b = dst + (int64_t)r * row_bytes;
+  if (vec) {
+    for (int64_t i = (int64_t)threadIdx.x * 16; i < row_bytes; i += 256 * 16)
+      *reinterpret_cast<u32x4*>(b + i) = *reinterpret_cast<const u32x4*>(a + i);
+  } else {
+    for (int64_t i = threadIdx.x; i < row_bytes; i += 256) b[i] = a[i];
+  }
+}
+
 }  // namespace
+
+forge_status launch_deinterleave_rows(const void* src, void* dst, int pairs, size_t row_bytes, hipStream_t s) {
+  const int vec = row_bytes % 16 == 0 && aligned16(src) && aligned16(dst);
+  deinterleave_rows_kernel<<<2 * (unsigned)pairs, 256, 0, s>>>((const char*)src, (char*)dst, pairs,
+                                                               (int64_t)row_bytes, vec);
+  return launch_status();
+}
 
 forge_status launch_quantize_int8(const void* w, int8_t* q, float* scale, int N, int K, forge_dtype dt,
                                   hipStream_t s) {

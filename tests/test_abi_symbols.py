@@ -81,6 +81,10 @@ def test_argument_errors_are_caught_on_the_host():
     # positions: pos0 + seq must not wrap around
     assert l.forge_embed(good, vp(0x2000), vp(0x3000), vp(0x4000), 1, 2, 64, 100, 512, 2**31 - 1, 1, None) == 1
     assert l.forge_embed(good, vp(0x2000), vp(0x3000), vp(0x4000), 1, 8, 64, 100, 512, 505, 1, None) == 1
+    # row re-layout: NULL, overlapping ranges, no rows
+    assert l.forge_deinterleave_gated_rows(None, good, 4, 16, None) == 1
+    assert l.forge_deinterleave_gated_rows(good, vp(0x1000 + 64), 4, 16, None) == 1      # 128-byte ranges overlap
+    assert l.forge_deinterleave_gated_rows(good, vp(0x2000), 0, 16, None) == 1
     # block: NULL descriptor; workspace size of an invalid descriptor is 0
     assert l.forge_decoder_block(None, good, good, good, good, 1, 1, 0, 1, good, 0, None) == 1
     d = B.BlockDesc()

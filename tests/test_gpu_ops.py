@@ -73,6 +73,31 @@ def test_gemm_bias_act(F, bf16, act, M, N, K):
         check(ty, ref, bf16, "gemm %s" % act)
 
 
+@pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
+@pytest.mark.parametrize("M,N,K", [(40, 136, 64), (200, 515, 72)])
+def test_gated_weight_with_alternating_rows(F, bf16, M, N, K):
+    """A gated weight stored (gate 0, up 0, gate 1, up 1, ...) is re-laid once into gate rows, then
+    up rows (bit-exact row permutation, weights and bias), and the SwiGLU GEMM on it matches the
+    oracle on the blocked weight."""
+    w = I.normal(67, 0, "w_up", (2 * N, K), 1.0 / math.sqrt(K), bf16=bf16)     # blocked: gate rows, up rows
+    b = I.normal(67, 0, "b_up", (2 * N,), 0.5, bf16=bf16)
+    x = I.normal(67, 0, "x", (M, K), 1.0, bf16=bf16)
+    wi = np.empty_like(w); wi[0::2] = w[:N]; wi[1::2] = w[N:]                      # what a caller holds
+    bi = np.empty_like(b); bi[0::2] = b[:N]; bi[1::2] = b[N:]
+    tw = F.forge_deinterleave_gated_rows(dev(wi, bf16))
+    tb = F.forge_deinterleave_gated_rows(dev(bi, bf16))
+    torch.cuda.synchronize()
+    assert np.array_equal(host(tw), w.astype(np.float64)) and np.array_equal(host(tb), b.astype(np.float64))
+    q = torch.arange(2 * 7 * 5, dtype=torch.int8, device="cuda").reshape(14, 5)    # odd row size: byte copies
+    got = F.forge_deinterleave_gated_rows(q).cpu().numpy()
+    assert np.array_equal(got, np.concatenate([q.cpu().numpy()[0::2], q.cpu().numpy()[1::2]]))
+    ty = torch.empty(M, N, dtype=tdtype(bf16), device="cuda")
+    ws = F.workspace(F.forge_gemm_workspace_bytes(M, N, K, "swiglu", tdtype(bf16)))
+    F.forge_gemm_bias_gelu(dev(x, bf16), tw, tb, None, ty, "swiglu", ws)
+    torch.cuda.synchronize()
+    check(ty, O.gemm_bias_act(x, w, b, None, "swiglu"), bf16, "swiglu on a re-laid weight")
+
+
 @pytest.mark.parametrize("M,N,K,ld", [(300, 1001, 128, 1008), (257, 515, 64, 520), (130, 50257, 64, 50264)])
 def test_gemm_padded_row_stride(F, M, N, K, ld):
     """Odd N with a padded, 16-byte aligned row stride: fast store path; the padding stays untouched."""
