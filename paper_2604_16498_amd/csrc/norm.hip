@@ -5,11 +5,11 @@
 // variance and the normalisation all run without a second pass over memory.
 //
 // Two launch shapes:
-//   - d <= 4096: one 64-lane wave per row (4 rows per 256-thread block, up to 8 chunks per lane),
-//     reductions by cross-lane shuffles only.  No block barrier, and a wave keeps its whole row
-//     in flight: at d = 2048 / 4096 this measured 12 % / 7 % faster than a block per row, whose
-//     two barriers per reduction leave too few bytes in flight per CU;
-//   - d  > 4096: one 256-thread block per row, wave shuffles then a 4-entry LDS exchange.
+//   - one 64-lane wave per row (4 rows per 256-thread block, up to 4 chunks per lane), reductions
+//     by cross-lane shuffles only: d <= 1024, and d <= 2048 when there are at least 1024 rows (no
+//     block barrier and a whole row in flight per wave: 13.4 vs 14.6 us for 8192 x 2048 inside the
+//     model; with few rows, or at d = 4096, the block per row is the faster one);
+//   - one 256-thread block per row, wave shuffles then a 4-entry LDS exchange.
 // Each lane owns CH chunks of 8 consecutive elements (one 128-bit access for bf16, two for
 // fp32), chunk c of lane l covers elements 8*(l + c*G) .. +8 with G lanes per row, so that
 // consecutive lanes touch consecutive 16 B.
@@ -125,8 +125,9 @@ forge_status launch_t(const void* x, const void* delta, const void* gamma, const
   return launch_g<T, CH, G>(x, delta, gamma, beta, h_out, y, rows, d, eps, kind, s)
   if (chunks <= 64) FORGE_NORM_CASE(1, 64);
   if (chunks <= 128) FORGE_NORM_CASE(2, 64);
-  if (chunks <= 256) FORGE_NORM_CASE(4, 64);
-  if (chunks <= 512) FORGE_NORM_CASE(8, 64);
+  if (chunks <= 256 && rows >= 1024) FORGE_NORM_CASE(4, 64);
+  if (chunks <= 256) FORGE_NORM_CASE(1, 256);
+  if (chunks <= 512) FORGE_NORM_CASE(2, 256);
   if (chunks <= 1024) FORGE_NORM_CASE(4, 256);
   if (chunks <= 2048) FORGE_NORM_CASE(8, 256);
 #undef FORGE_NORM_CASE

@@ -30,7 +30,7 @@ def tdtype(bf16):
 @pytest.mark.parametrize("bf16", [False, True], ids=["f32", "bf16"])
 @pytest.mark.parametrize("kind", ["layernorm", "rmsnorm"])
 @pytest.mark.parametrize("rows,d", [(128, 768), (64, 4096), (37, 2048), (5, 8), (3, 16384),
-                                    (1000, 1032), (9, 520), (8192, 768), (13, 3000), (6, 5000)])
+                                    (1000, 1032), (9, 520), (8192, 768), (13, 3000), (6, 5000), (1100, 1288), (2048, 2048)])
 def test_residual_norm(F, bf16, kind, rows, d):
     x = I.normal(60, 0, "x", (rows, d), 1.5, mean=0.3, bf16=bf16)
     dl = I.normal(60, 0, "delta", (rows, d), 0.7, bf16=bf16)
