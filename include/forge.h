@@ -85,8 +85,10 @@ int forge_version(void);
  * same call reads a packed prefill tensor or a KV cache with capacity > kv_len.
  * out: [B,q_len,Hq*dh] dense (heads concatenated per token).  out must not alias q, k, v.
  * Requirements: Hq % Hkv == 0; dh in {64,128}; q_len >= 1; kv_len >= q_len when causal;
- * strides multiples of 8 elements.  q_len == 1 takes the split-KV (decode) path, which
- * needs workspace.
+ * strides multiples of 8 elements; scale positive and finite (else FORGE_ERR_INVALID_ARG: the
+ * paper's scale is 1/sqrt(d_k)).  q_len == 1 takes the split-KV (decode) path, which needs
+ * workspace; the size reported for (.., q_len 1, kv_len L, ..) also serves every shorter
+ * length, so a generation loop asks once, for the capacity of its cache.
  * ------------------------------------------------------------------------------------ */
 size_t forge_attn_fused_workspace_bytes(int batch, int q_heads, int kv_heads, int q_len,
                                         int kv_len, int head_dim, forge_dtype dt);
@@ -323,8 +325,10 @@ forge_status forge_model_decode(const forge_model_desc* model, const void* input
  *   n_instr+1 entries, dead_regs one per register with end >= 0.
  * forge_plan_linear_scan (Alg. "Linear-Scan Buffer Allocation"): intervals in order of start
  *   (ties: register number); before each, active intervals that ended strictly before its
- *   start release their buffers (first released, first reused); *n_bufs = M.  reg_to_buf[r] =
- *   -1 where start[r] < 0.  The buffer reduction ratio of Eq. "buf_reduction" is 1 - M/N.
+ *   start release their buffers; the interval takes the lowest-numbered free buffer (the
+ *   algorithm leaves the choice open), else a new one, numbered in order of creation;
+ *   *n_bufs = M.  reg_to_buf[r] = -1 where start[r] < 0.  The buffer reduction ratio of
+ *   Eq. "buf_reduction" is 1 - M/N.
  * forge_plan_workspace: byte offsets in one workspace.  Registers of equal nbytes share
  *   buffers through a linear scan of their own; registers that live within one instruction
  *   (start == end, e.g. scratch areas) form one further group sized to its largest member; the

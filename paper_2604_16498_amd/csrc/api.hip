@@ -165,7 +165,7 @@ forge_status forge_attn_fused(const void* q, const void* k, const void* v, void*
   if (!dtype_ok(dt) || !req(q) || !req(k) || !req(v) || !req(out) || !opt(workspace))
     return FORGE_ERR_INVALID_ARG;
   if (batch < 1 || q_heads < 1 || kv_heads < 1 || q_len < 1 || kv_len < 1) return FORGE_ERR_INVALID_ARG;
-  if (q_heads % kv_heads != 0) return FORGE_ERR_INVALID_ARG;
+  if (q_heads % kv_heads != 0 || !scale_ok(scale)) return FORGE_ERR_INVALID_ARG;
   if (causal && kv_len < q_len) return FORGE_ERR_INVALID_ARG;
   if (head_dim != 64 && head_dim != 128) return FORGE_ERR_UNSUPPORTED;
   if (!grid_ok(batch, q_heads) || !rows_ok(batch, q_len)) return FORGE_ERR_UNSUPPORTED;
@@ -190,7 +190,7 @@ forge_status forge_attn_fused_masked(const void* q, const void* k, const void* v
       (reinterpret_cast<uintptr_t>(mask) & 3u) != 0)
     return FORGE_ERR_INVALID_ARG;
   if (batch < 1 || q_heads < 1 || kv_heads < 1 || q_len < 1 || kv_len < 1) return FORGE_ERR_INVALID_ARG;
-  if (q_heads % kv_heads != 0) return FORGE_ERR_INVALID_ARG;
+  if (q_heads % kv_heads != 0 || !scale_ok(scale)) return FORGE_ERR_INVALID_ARG;
   if (causal && kv_len < q_len) return FORGE_ERR_INVALID_ARG;
   if (head_dim != 64 && head_dim != 128) return FORGE_ERR_UNSUPPORTED;
   if (!grid_ok(batch, q_heads) || !rows_ok(batch, q_len)) return FORGE_ERR_UNSUPPORTED;
@@ -417,7 +417,7 @@ forge_status forge_attn_decode_varlen(const void* q, const void* k, const void* 
   if (!dtype_ok(dt) || !req(q) || !req(k) || !req(v) || !req(out) || !opt(workspace) || !seq_pos_ok(seq_pos))
     return FORGE_ERR_INVALID_ARG;
   if (batch < 1 || q_heads < 1 || kv_heads < 1 || max_pos < 0 || max_pos == INT32_MAX) return FORGE_ERR_INVALID_ARG;
-  if (q_heads % kv_heads != 0) return FORGE_ERR_INVALID_ARG;
+  if (q_heads % kv_heads != 0 || !scale_ok(scale)) return FORGE_ERR_INVALID_ARG;
   if (head_dim != 64 && head_dim != 128) return FORGE_ERR_UNSUPPORTED;
   if (!grid_ok(batch, q_heads)) return FORGE_ERR_UNSUPPORTED;
   const int kv_len = max_pos + 1;

@@ -9,6 +9,10 @@ inline size_t esize(forge_dtype dt) { return dt == FORGE_BF16 ? 2 : 4; }
 inline bool dtype_ok(forge_dtype dt) { return dt == FORGE_F32 || dt == FORGE_BF16; }
 inline bool req(const void* p) { return p != nullptr && aligned16(p); }
 inline bool opt(const void* p) { return p == nullptr || aligned16(p); }
+// The softmax scale: positive and finite.  The matrix-core kernels take the running maximum of
+// the raw scores and apply the scale afterwards, which is the maximum of the scaled scores only
+// for a positive factor.
+inline bool scale_ok(float scale) { return scale > 0.0f && scale <= 3.0e38f; }
 
 // rows (2r, 2r + 1) of src -> rows (r, pairs + r) of dst (defined with the elementwise kernels)
 forge_status launch_deinterleave_rows(const void* src, void* dst, int pairs, size_t row_bytes, hipStream_t s);

@@ -280,13 +280,22 @@ __global__ __launch_bounds__(DH) void attn_decode_combine(const float* __restric
 
 // Number of row ranges: about two blocks per compute unit, at most one range per GRAIN rows.
 struct SplitPlan { int splits, rows_per_split; };
-inline SplitPlan plan_splits(int batch, int kv_heads, int kv_len) {
+// the most ranges a batch is ever cut into, whatever the cache length
+inline int max_splits(int batch, int kv_heads) {
   const int64_t pairs = (int64_t)batch * kv_heads;
   const int64_t for_two_per_cu = ceil_div64(2 * (int64_t)compute_units(), pairs);
-  int want = for_two_per_cu < MAX_SPLITS ? (int)for_two_per_cu : MAX_SPLITS;
-  want = max(1, min(want, ceil_div(kv_len, GRAIN)));
+  return for_two_per_cu < MAX_SPLITS ? (int)for_two_per_cu : MAX_SPLITS;
+}
+inline SplitPlan plan_splits(int batch, int kv_heads, int kv_len) {
+  const int want = max(1, min(max_splits(batch, kv_heads), ceil_div(kv_len, GRAIN)));
   const int rows = ceil_div(ceil_div(kv_len, want), GRAIN) * GRAIN;
-  return SplitPlan{ceil_div(kv_len, rows), rows};
+  return SplitPlan{ceil_div(kv_len, rows), rows};   // rows >= kv_len / want, so splits <= want
+}
+// Upper bound of plan_splits(.., len).splits over every len <= kv_len: the number of ranges is
+// not monotone in the length (the range size is rounded up to GRAIN), the scratch size must be,
+// because a generation loop sizes its scratch once, for the capacity of its cache.
+inline int splits_bound(int batch, int kv_heads, int kv_len) {
+  return max(1, min(max_splits(batch, kv_heads), ceil_div(kv_len, GRAIN)));
 }
 
 template <int DH, int G>
@@ -328,13 +337,15 @@ forge_status launch_d(const AttnArgs& a, hipStream_t s) {
 }  // namespace
 
 size_t attn_decode_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim) {
-  const int splits = plan_splits(batch, kv_heads, kv_len).splits;
+  const int splits = splits_bound(batch, kv_heads, kv_len);
   if (splits == 1) return 0;       // one block per (kv head, sequence) writes the output itself
   return (size_t)batch * q_heads * splits * (head_dim + 2) * sizeof(float);
 }
 
 forge_status launch_attn_decode_bf16(const AttnArgs& a, hipStream_t s) {
-  const size_t need = attn_decode_workspace_bytes(a.batch, a.q_heads, a.kv_heads, a.kv_len, a.head_dim);
+  // what THIS launch writes (at most the bound the size query reports for any cache >= kv_len)
+  const int splits = plan_splits(a.batch, a.kv_heads, a.kv_len).splits;
+  const size_t need = splits == 1 ? 0 : (size_t)a.batch * a.q_heads * splits * (a.head_dim + 2) * sizeof(float);
   if (need > 0 && (a.workspace == nullptr || a.workspace_bytes < need)) return FORGE_ERR_WORKSPACE;
   if (a.head_dim == 64) return launch_d<64>(a, s);
   if (a.head_dim == 128) return launch_d<128>(a, s);

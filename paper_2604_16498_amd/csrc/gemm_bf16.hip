@@ -535,8 +535,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
         for (int itp = 0; itp < NITP; ++itp) {
           const int row = piece_row(pass * NITP + itp);
           const int gm = min(m0 + row, M - 1);
+          // a chunk that starts inside the row lies inside its padded stride (ldy % 8 == 0, host);
+          // chunks wholly past the end fetch something valid, unused
           int gn = n0 + piece_chunk(row) * 8;
-          if (gn + 8 > N) gn = 0;     // chunks past the end fetch something valid, unused
+          if (gn >= N) gn = 0;
           __builtin_amdgcn_global_load_lds((const void*)(p.residual + (int64_t)gm * p.ldy + gn),
                                            (lds_void*)(stg + (itp * NW + wave) * 1024), 16, 0, 0);
         }
@@ -557,7 +559,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
           for (int gp = 0; gp < 2; ++gp) {
             const int cl = (wn * TN_OUT + j) * 4 + 2 * fh + gp;   // chunk inside the tile row
             const int n = n0 + cl * 8;
-            // bias / residual only with N % 8 == 0 (host): a chunk is all in or all out
+            // the last chunk of a row may be ragged (N % 8 != 0, never with SwiGLU: host); its
+            // columns past N are computed on whatever the padding holds and never stored
             const bool in = n + 8 <= N;
             float o[8];
 #pragma unroll
@@ -572,11 +575,15 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
 #pragma unroll
                 for (int e = 0; e < 8; ++e) run2[gp][e] += bb[e];
               }
+            } else if (!SWIGLU && p.bias != nullptr && n < N) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (n + e < N) o[e] += (float)p.bias[n + e];
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = SWIGLU ? silu_f(o[e]) * run2[gp][e] : apply_act<ACT>(o[e]);
             bf16* slot = reinterpret_cast<bf16*>(stg + (rp * NCH + (cl ^ (rp & (NCH - 1)))) * 16);
-            if (has_res && in) {
+            if (has_res && n < N) {
               float rr[8];
               Vec8<bf16>::load(slot, rr);
 #pragma unroll
@@ -1026,13 +1033,13 @@ forge_status launch_pers(const GemmParams& p0, hipStream_t s) {
 // Which kernel and tile a problem gets.  Fast path: K a multiple of the slab and 16-byte aligned
 // output rows (the head split and the fp32 partials have their own alignment rules).
 enum Variant { V_FAST_256 = 0, V_FAST_128 = 1, V_GEN_256 = 2, V_GEN_128 = 3, V_SKINNY_FAST = 4, V_SKINNY_GEN = 5 };
-inline Variant choose_variant(int M, int N, int K, int ldy, forge_act act, bool qkv, bool epi_loads) {
+inline Variant choose_variant(int M, int N, int K, int ldy, forge_act act, bool qkv) {
   const bool k_ok = K % BK == 0;
   // the fast kernels address x and w with 32-bit byte offsets
   const int64_t w_rows = act == FORGE_ACT_SWIGLU ? 2 * (int64_t)N : N;
   const bool small_ok = (int64_t)M * K * 2 < (1ll << 32) && w_rows * K * 2 < (1ll << 32);
   if (M <= 64) return k_ok ? V_SKINNY_FAST : V_SKINNY_GEN;
-  const bool rows_ok = qkv ? N % 8 == 0 : (ldy % 8 == 0 && (N % 8 == 0 || (act != FORGE_ACT_SWIGLU && !epi_loads)));
+  const bool rows_ok = qkv ? N % 8 == 0 : (ldy % 8 == 0 && (N % 8 == 0 || act != FORGE_ACT_SWIGLU));
   const bool fast = k_ok && rows_ok && small_ok;
   // the 256-row tile multiplies faster (half the operand traffic per flop) but fills a CU on its
   // own: take it when its tiles come to whole rounds over the CUs, or to many rounds
@@ -1097,8 +1104,7 @@ forge_status launch_wstream(const GemmParams& q, int splits, hipStream_t s) {
 
 template <int ACT, int MODE>
 forge_status launch_act(const GemmParams& p, hipStream_t s) {
-  const Variant v = choose_variant(p.M, p.N, p.K, p.ldy, (forge_act)ACT, MODE == MODE_QKV,
-                                   p.bias != nullptr || p.residual != nullptr);
+  const Variant v = choose_variant(p.M, p.N, p.K, p.ldy, (forge_act)ACT, MODE == MODE_QKV);
   switch (v) {
     case V_FAST_256: return launch_pers<256, 256, 2, 4, ACT, MODE>(p, s);
     case V_FAST_128: {
@@ -1175,7 +1181,7 @@ bool gemm_fuses_tail(int M, int N, forge_dtype dt) {
 }
 
 const char* gemm_bf16_variant(int M, int N, int K, int ldy, forge_act act) {
-  switch (choose_variant(M, N, K, ldy, act, false, false)) {
+  switch (choose_variant(M, N, K, ldy, act, false)) {   // the call launch_act makes for a plain output
     case V_FAST_256: return "gemm_bf16_pers<256,256,2,4>";
     case V_FAST_128: return act == FORGE_ACT_SWIGLU ? "gemm_bf16_pers<128,128,2,2>" : "gemm_bf16_pers<128,128,2,4>";
     case V_GEN_256: return "gemm_bf16_generic<256,256,2,4>";

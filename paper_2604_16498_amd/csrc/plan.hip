@@ -4,8 +4,10 @@
 #include "plan.hpp"
 
 #include <algorithm>
-#include <deque>
-#include <numeric>
+#include <functional>
+#include <queue>
+#include <utility>
+#include <vector>
 
 #include "../../include/forge.h"
 
@@ -25,6 +27,11 @@ void plan_liveness(int n_instr, const int* out_reg, const int* in_begin, const i
   }
 }
 
+// Alg. "Linear-Scan Buffer Allocation" as an event sweep: the intervals arrive by ascending start;
+// the ones still holding a buffer wait in a heap keyed by their end, so the arrivals' expiry step
+// pops exactly those that ended strictly before the new start; released buffers wait in a second
+// heap keyed by their number.  The algorithm only says that a free buffer is popped: which one is
+// this library's choice (the lowest-numbered), documented at the entry point.
 int plan_linear_scan(int n_regs, const int* start, const int* end, int* reg_to_buf) {
   std::vector<int> order;
   order.reserve(n_regs);
@@ -32,27 +39,26 @@ int plan_linear_scan(int n_regs, const int* start, const int* end, int* reg_to_b
     reg_to_buf[r] = -1;
     if (start[r] >= 0) order.push_back(r);
   }
-  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return start[a] < start[b]; });
-  struct Active { int end, buf; };
-  std::vector<Active> active, keep;
-  std::deque<int> free_pool;
+  std::sort(order.begin(), order.end(),
+            [&](int a, int b) { return start[a] != start[b] ? start[a] < start[b] : a < b; });
+  typedef std::pair<int, int> Held;   // (end of the interval, its buffer)
+  std::priority_queue<Held, std::vector<Held>, std::greater<Held>> holding;
+  std::priority_queue<int, std::vector<int>, std::greater<int>> idle;
   int n_bufs = 0;
   for (int r : order) {
-    keep.clear();
-    for (const Active& a : active) {
-      if (a.end < start[r]) free_pool.push_back(a.buf);
-      else keep.push_back(a);
+    while (!holding.empty() && holding.top().first < start[r]) {
+      idle.push(holding.top().second);
+      holding.pop();
     }
-    active.swap(keep);
     int b;
-    if (!free_pool.empty()) {
-      b = free_pool.front();
-      free_pool.pop_front();
+    if (!idle.empty()) {
+      b = idle.top();
+      idle.pop();
     } else {
       b = n_bufs++;
     }
     reg_to_buf[r] = b;
-    active.push_back({end[r], b});
+    holding.push(Held(end[r], b));
   }
   return n_bufs;
 }

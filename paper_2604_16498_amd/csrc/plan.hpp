@@ -15,10 +15,9 @@ void plan_liveness(int n_instr, const int* out_reg, const int* in_begin, const i
                    int n_regs, int* start, int* end);
 
 // Intervals are visited by ascending start (ties: ascending register number).  Before each one,
-// active intervals whose end lies strictly before its start hand their buffer to the free pool,
-// in the order they were activated; the interval takes the oldest buffer of the pool, else a
-// new one (numbered 0, 1, ... in creation order).  Registers with start < 0 get buffer -1.
-// Returns the number of buffers.
+// intervals whose end lies strictly before its start give their buffer back; the interval takes
+// the lowest-numbered free buffer, else a new one (numbered 0, 1, ... in creation order).
+// Registers with start < 0 get buffer -1.  Returns the number of buffers.
 int plan_linear_scan(int n_regs, const int* start, const int* end, int* reg_to_buf);
 
 // Byte layout: registers of equal byte size form a group, except that all registers living within

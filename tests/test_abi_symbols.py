@@ -89,3 +89,58 @@ def test_argument_errors_are_caught_on_the_host():
     assert l.forge_decoder_block(None, good, good, good, good, 1, 1, 0, 1, good, 0, None) == 1
     d = B.BlockDesc()
     assert l.forge_decoder_block_workspace_bytes(C.byref(d), 1, 1, 1) == 0
+
+
+def test_attention_scale_must_be_positive_and_finite():
+    from paper_2604_16498_amd import binding as B
+    l = B.lib()
+    vp = C.c_void_p
+    a = (vp(0x1000), vp(0x2000), vp(0x3000), vp(0x4000))
+    mask = C.cast(vp(0x5000), C.POINTER(C.c_float))
+    pos = C.cast(vp(0x6000), C.POINTER(C.c_int32))
+    for bad in (0.0, -0.125, float("inf"), float("nan")):
+        assert l.forge_attn_fused(*a, 1, 4, 4, 8, 8, 64, 4 * 8 * 64, 8 * 64, bad, 1, 1, None, 0, None) == 1
+        assert l.forge_attn_fused(*a, 1, 4, 4, 8, 8, 64, 4 * 8 * 64, 8 * 64, bad, 1, 0, None, 0, None) == 1
+        assert l.forge_attn_fused_masked(a[0], a[1], a[2], mask, a[3], 1, 4, 4, 8, 8, 64, 4 * 8 * 64, 8 * 64,
+                                         0, 0, bad, 0, 1, None) == 1
+        assert l.forge_attn_decode_varlen(*a, pos, 1, 4, 4, 7, 64, 4 * 8 * 64, 8 * 64, bad, 1, None, 0, None) == 1
+
+
+def test_decode_attention_scratch_is_monotone_in_the_cache_length():
+    """A generation loop asks once, for the capacity of its cache, and then attends over every
+    shorter length: the size for a longer cache must never be smaller, and the layer's and
+    the model's workspace (sized for kv_cap) must cover the attention call at every step."""
+    from paper_2604_16498_amd import binding as B
+    l = B.lib()
+    for batch, hq, hkv, dh in [(8, 32, 8, 128), (4, 12, 12, 64), (2, 12, 12, 64), (1, 32, 8, 128),
+                               (3, 16, 4, 128), (16, 8, 8, 64), (64, 32, 8, 128)]:
+        prev = 0
+        for kv_len in list(range(1, 700)) + list(range(700, 9000, 37)):
+            need = l.forge_attn_fused_workspace_bytes(batch, hq, hkv, 1, kv_len, dh, B.FORGE_BF16)
+            assert need >= prev, (batch, hq, hkv, dh, kv_len, need, prev)
+            prev = need
+        # never more than one partial (dh + 2 floats) per query head and split, 64 splits at most
+        assert prev <= batch * hq * 64 * (dh + 2) * 4
+    # the two cases that used to shrink with the length
+    a = l.forge_attn_fused_workspace_bytes(8, 32, 8, 1, 769, 128, B.FORGE_BF16)
+    b = l.forge_attn_fused_workspace_bytes(8, 32, 8, 1, 2049, 128, B.FORGE_BF16)
+    assert 0 < a <= b
+
+
+def test_gemm_variant_names_the_kernel_that_runs():
+    """The diagnostic applies the launcher's own rule: unaligned output rows (an odd dense N) and
+    a reduction that is not a whole number of 64-element slabs go to the generic kernel, a
+    decode-sized problem to the weight-streaming one, everything else to the persistent one."""
+    import torch
+    from paper_2604_16498_amd import binding as F
+    v = lambda M, N, K, act="none", ldy=0: F.forge_gemm_variant(M, N, K, act, torch.bfloat16, ldy=ldy)
+    assert v(300, 1001, 128) == "gemm_bf16_generic<128,128,2,2>"            # rows of 2002 bytes
+    assert v(300, 1001, 128, ldy=1008) == "gemm_bf16_pers<128,128,2,4>"
+    assert v(300, 1000, 72) == "gemm_bf16_generic<128,128,2,2>"             # K % 64 != 0
+    assert v(8192, 3072, 768, "gelu_tanh") == "gemm_bf16_pers<128,128,2,4>"
+    assert v(8192, 50257, 768, ldy=50264) == "gemm_bf16_pers<256,256,2,4>"
+    assert v(4096, 14336, 4096, "swiglu") == "gemm_bf16_pers<256,256,2,4>"
+    assert v(4096, 1001, 4096, "swiglu", ldy=1008) == "gemm_bf16_generic<128,128,2,2>"   # gated pairs need N % 8 == 0
+    assert v(64, 4096, 4096) == "gemm_bf16_wstream+splitk"
+    assert v(64, 4096, 72) == "gemm_bf16_generic<64,64,2,2>+splitk"
+    assert F.forge_gemm_variant(128, 768, 768, "none", torch.float32) == "gemm_f32<64,64,2,2>"

@@ -14,7 +14,7 @@ import torch
 
 from oracle import forge_oracle as O
 from paper_2604_16498_amd import inputs as I
-from util import check, dev, dev_dict, host, rel_err
+from util import check, check_drift, dev, dev_dict, host, strict_err
 
 pytestmark = pytest.mark.gpu
 
@@ -83,8 +83,8 @@ def test_config2_gpt2_small_full_batch(F):
     check(logits[B - 1, rows], O.lm_head(yf[rows], mw["wte"]), True, "config 2 logits (own hidden state)", chain=True)
     # end to end against the oracle's own 12 layers, sequence 0: drift reported
     ref = O.gpt_forward(sh, layers, mw, ids=ids[:1])
-    mx, l2 = rel_err(host(logits[0]), ref[0])
-    print("config2 end-to-end logits: max rel %.3e  l2 %.3e" % (mx, l2))
+    mx, l2 = strict_err(host(logits[0]), ref[0])
+    print("config2 end-to-end logits after 12 layers (reported, the l2 error loosely gated): strict elementwise %.3e  l2 %.3e" % (mx, l2))
     assert l2 < 3e-2
     # bitwise reproducible
     again = torch.empty_like(full)

@@ -10,7 +10,7 @@ import torch
 
 from oracle import forge_oracle as O
 from paper_2604_16498_amd import inputs as I
-from util import check, dev, dev_dict, host, rel_err
+from util import check, check_drift, dev, dev_dict, host
 
 pytestmark = pytest.mark.gpu
 
@@ -132,8 +132,7 @@ def test_generation_loop_ragged_batch(F, compiled):
         ws = F.workspace(F.forge_model_workspace_bytes(model, 1, n, cap))
         F.forge_model_forward(model, tids[b:b + 1, :n].contiguous(), lg, k1, v1, 0, ws)
         torch.cuda.synchronize()
-        mx, l2 = rel_err(host(lg), refs[b][:, :n])
-        assert l2 < 2e-2 and mx < 6e-2
+        check_drift(lg, refs[b][:, :n], "prompt of sequence %d" % b)
         kc[:, b] = k1[:, 0]; vc[:, b] = v1[:, 0]
 
     seq_pos = ipos(lens)
@@ -166,9 +165,8 @@ def test_generation_loop_ragged_batch(F, compiled):
             torch.cuda.synchronize()
         got = host(logits)
         for b in range(B):
-            mx, l2 = rel_err(got[b], refs[b][0, lens[b] + i:lens[b] + i + 1])
+            _, l2 = check_drift(got[b], refs[b][0, lens[b] + i:lens[b] + i + 1], "step %d sequence %d" % (i, b))
             worst = max(worst, l2)
-            assert l2 < 2e-2 and mx < 6e-2, "step %d sequence %d: l2 %.3e max %.3e" % (i, b, l2, mx)
         seq_pos += 1                                                # the positions advance on the device
     print("ragged generation loop (%s): worst l2 %.3e" % ("compiled" if compiled else "plain", worst))
     if compiled:

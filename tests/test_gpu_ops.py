@@ -98,19 +98,22 @@ def test_gated_weight_with_alternating_rows(F, bf16, M, N, K):
     check(ty, O.gemm_bias_act(x, w, b, None, "swiglu"), bf16, "swiglu on a re-laid weight")
 
 
+@pytest.mark.parametrize("epi", ["bias+residual", "bias", "residual", "none"])
 @pytest.mark.parametrize("M,N,K,ld", [(300, 1001, 128, 1008), (257, 515, 64, 520), (130, 50257, 64, 50264)])
-def test_gemm_padded_row_stride(F, M, N, K, ld):
-    """Odd N with a padded, 16-byte aligned row stride: fast store path; the padding stays untouched."""
+def test_gemm_padded_row_stride(F, M, N, K, ld, epi):
+    """Odd N with a padded, 16-byte aligned row stride takes the persistent kernel with or
+    without a bias / residual (the ragged last 8-column chunk of a row takes its bias element by
+    element and its residual from inside the padded stride); the padding stays untouched."""
     x = I.normal(67, 0, "x", (M, K), 1.0, bf16=True)
     w = I.normal(67, 0, "w_up", (N, K), 0.1, bf16=True)
-    b = I.normal(67, 0, "b_up", (N,), 0.5, bf16=True)
-    r = I.normal(67, 0, "residual", (M, ld), 1.0, bf16=True)
-    ref = O.gemm_bias_act(x, w, b, r[:, :N], "gelu_tanh")
+    b = I.normal(67, 0, "b_up", (N,), 0.5, bf16=True) if "bias" in epi else None
+    r = I.normal(67, 0, "residual", (M, ld), 1.0, bf16=True) if "residual" in epi else None
+    ref = O.gemm_bias_act(x, w, b, None if r is None else r[:, :N], "gelu_tanh")
     ty = torch.full((M, ld), 7.0, dtype=torch.bfloat16, device="cuda")
     assert "pers" in F.forge_gemm_variant(M, N, K, "gelu_tanh", torch.bfloat16, ldy=ld)
     F.forge_gemm_bias_gelu(dev(x, True), dev(w, True), dev(b, True), dev(r, True), ty, "gelu_tanh", n=N)
     torch.cuda.synchronize()
-    check(ty[:, :N], ref, True, "padded-stride gemm")
+    check(ty[:, :N], ref, True, "padded-stride gemm, %s" % epi)
     assert torch.all(ty[:, N:] == 7.0)
 
 
@@ -121,6 +124,8 @@ def test_gemm_padded_row_stride(F, M, N, K, ld):
     (5200, 1792, 192, "none", False, True, 0),       # residual only
     (5893, 5896, 192, "none", True, True, 0),        # 256-tiles: 576 > resident blocks, ragged edges
     (5893, 5891, 64, "relu", False, False, 5896),    # 256-tiles, odd N
+    (5893, 5891, 128, "gelu_tanh", True, True, 5896),  # 256-tiles, odd N, bias and residual on the ragged chunk
+    (5137, 1825, 640, "none", True, True, 1832),     # 128-tiles, odd N, bias and residual
     (5893, 2824, 128, "swiglu", True, False, 0),     # gated 256 x 128 output tiles
 ])
 def test_gemm_many_tiles_per_block(F, M, N, K, act, use_b, use_r, ld):

@@ -1,7 +1,10 @@
 """Host logic of the static buffer plan, through the C ABI, against the plan oracle: exact
-integer equality on random programs and on the launch lists of compiled decoder stacks.
-No GPU: the plan functions are host code, and compiling a model launches nothing (the weight
-pointers below are made-up aligned addresses that are never dereferenced).
+integer equality on random programs, and on the launch lists of compiled decoder stacks (the
+oracle plans the very program the library reports).  The lowering itself -- which launches a
+decoder stack becomes -- is not a paper object: it is checked against lists written out by hand
+below and, for more shapes, against the generator in tests/launch_list.py, as a regression
+check.  No GPU: the plan functions are host code, and compiling a model launches nothing (the
+weight pointers below are made-up aligned addresses that are never dereferenced).
 
 Sec. "Phase 4: IR Analysis & Optimization" (Eq. "liveness", Alg. "Linear-Scan Buffer
 Allocation"), Alg. "FX -> NPUIR Lowering".
@@ -13,7 +16,8 @@ import pytest
 
 from oracle import plan_oracle as P
 from paper_2604_16498_amd import binding as B
-from test_plan_oracle_pins import random_program
+from launch_list import OPS, decoder_program
+from test_plan_oracle_pins import max_alive, random_program
 
 
 def to_lists(iv):
@@ -114,39 +118,41 @@ GPT = Shape(d_model=256, q_heads=4, kv_heads=4, head_dim=64, d_ff=1024, norm="la
 LLAMA = Shape(d_model=512, q_heads=4, kv_heads=2, head_dim=128, d_ff=1408, norm="rmsnorm",
               mlp_act="swiglu", use_rope=True)
 
+# Which steps a launch absorbs, listed by hand per case (not computed by the library's rule):
+# `rope` = q and k are rotated by launches of their own, `norm2` / `norm1` = the second / every
+# first norm is a launch of its own.  A bf16 step of at most 64 rows folds all three into the
+# reduce steps of its projections; fp32 steps and prompts keep them apart.
 CASES = [
-    # name, shape, layers, tokens, dtype, batch, q_len, pos0, kv_cap
-    ("gpt_prefill_bf16", GPT, 3, True, B.FORGE_BF16, 2, 128, 0, 128),
-    ("gpt_prefill_f32", GPT, 2, True, B.FORGE_F32, 1, 128, 0, 128),
-    ("llama_prefill_bf16", LLAMA, 4, False, B.FORGE_BF16, 1, 256, 0, 256),
-    ("llama_decode_bf16", LLAMA, 4, False, B.FORGE_BF16, 8, 1, 300, 301),
-    ("llama_decode_f32", LLAMA, 2, False, B.FORGE_F32, 8, 1, 40, 64),
-    ("gpt_decode_bf16", GPT, 12, True, B.FORGE_BF16, 4, 1, 100, 128),
-    ("llama_decode_int8", LLAMA, 3, False, B.FORGE_BF16, 16, 1, 300, 320),
-    ("llama_prefill_int8", LLAMA, 2, False, B.FORGE_BF16, 1, 96, 0, 96),
+    # name, shape, layers, tokens, dtype, batch, q_len, pos0, kv_cap, rope, norm2, norm1
+    ("gpt_prefill_bf16", GPT, 3, True, B.FORGE_BF16, 2, 128, 0, 128, False, True, True),
+    ("gpt_prefill_f32", GPT, 2, True, B.FORGE_F32, 1, 128, 0, 128, False, True, True),
+    ("llama_prefill_bf16", LLAMA, 4, False, B.FORGE_BF16, 1, 256, 0, 256, True, True, True),
+    ("llama_decode_bf16", LLAMA, 4, False, B.FORGE_BF16, 8, 1, 300, 301, False, False, False),
+    ("llama_decode_f32", LLAMA, 2, False, B.FORGE_F32, 8, 1, 40, 64, True, True, True),
+    ("gpt_decode_bf16", GPT, 12, True, B.FORGE_BF16, 4, 1, 100, 128, False, False, False),
+    ("llama_decode_int8", LLAMA, 3, False, B.FORGE_BF16, 16, 1, 300, 320, False, False, False),
+    ("llama_prefill_int8", LLAMA, 2, False, B.FORGE_BF16, 1, 96, 0, 96, True, True, True),
 ]
 
 
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
-def test_compiled_program_and_plan_match_the_oracle(case):
-    name, shape, L, tokens, dt, batch, q_len, pos0, kv_cap = case
+def test_compiled_program_and_its_plan(case):
+    name, shape, L, tokens, dt, batch, q_len, pos0, kv_cap, rope, norm2, norm1 = case
     w8 = name.endswith("int8")
     model = fake_model(shape, L, tokens, dt, w8=w8)
     cm = B.CompiledModel(model, batch, q_len, pos0, kv_cap)
     ops, out_reg, ins, reg_bytes, reg_offset = cm.program()
     ni, nr, _, nb = cm.counts()
 
-    # which operators the small-row split-K projections absorb (bf16, at most 64 rows)
-    T = batch * q_len
-    small = dt == B.FORGE_BF16 and T <= 64
-    prog, kinds = P.decoder_program(L, tokens, rope_separate=shape.use_rope and not small,
-                                    norm2_separate=not small, norm1_separate=not small)
+    # the lowering (regression check against the fixture generator)
+    prog, kinds = decoder_program(L, tokens, rope_separate=rope, norm2_separate=norm2, norm1_separate=norm1)
     assert (ni, nr) == (len(prog), len(kinds))
     assert ops == [p[0] for p in prog]
     assert out_reg == [p[1] for p in prog]
     assert ins == [p[2] for p in prog]
 
     # byte sizes of the tensor registers, from the shapes
+    T = batch * q_len
     es = 2 if dt == B.FORGE_BF16 else 4
     want = {"h": T * shape.d_model * es, "y": T * shape.d_model * es,
             "q": T * shape.q_heads * shape.head_dim * es, "o": T * shape.q_heads * shape.head_dim * es,
@@ -154,7 +160,8 @@ def test_compiled_program_and_plan_match_the_oracle(case):
     for r, k in enumerate(kinds):
         if k in want:
             assert reg_bytes[r] == want[k], (r, k)
-    # scratch registers: what the library's own workspace queries report for that launch
+    # the scratch registers' sizes are the library's own business: they are an INPUT of the plan
+    # below; here only that each is what the public size query of that launch reports
     act = B.ACT[shape.mlp_act]
     nqkv = (shape.q_heads + 2 * shape.kv_heads) * shape.head_dim
     hd = shape.q_heads * shape.head_dim
@@ -171,15 +178,102 @@ def test_compiled_program_and_plan_match_the_oracle(case):
         if k in scratch:
             assert reg_bytes[r] == scratch[k], (r, k)
 
-    # the plan: oracle's liveness + byte plan over the oracle's program and these sizes
-    iv = P.live_intervals([(o, i) for _, o, i in prog], len(kinds))
+    # the plan (oracle parity): liveness and byte plan of the program the library reports, with
+    # the sizes it reports, computed by the oracle
+    iv = P.live_intervals(list(zip(out_reg, ins)), nr)
     off, total, bufs = P.workspace_plan(iv, reg_bytes)
     assert reg_offset == off
     assert cm.workspace_bytes() == total
     assert nb == bufs
-    # fewer buffers than registers, and the count does not depend on the depth
+    # fewer buffers than registers
     assert nb < nr
     cm.close()
+
+
+def _names(prog):
+    return [(OPS[op], out, ins) for op, out, ins in prog]
+
+
+# One Llama-shaped decode step of two layers, eight rows, bf16, written out by hand from the
+# layer's steps.  Registers are numbered as they appear: per instruction its output, then its
+# second result, then its scratch area.  At this size the reduce step of the QKV projection
+# rotates q and k, the one of the output projection also writes the second norm's rows (y2, a
+# second result: listed among the inputs), and the one of the MLP down projection writes the NEXT
+# layer's first-norm rows; the last layer's down projection writes the caller's output (the final
+# norm) and adds the residual stream in place, so it has no output register.
+LLAMA_DECODE_2L = [
+    ("norm", 0, []),                      # y = Norm1(x), x is the caller's
+    ("gemm_qkv", 1, [0, 2]),              # q (k, v go to the cache), scratch 2
+    ("attn", 3, [1, 4]),                  # o, scratch 4
+    ("gemm_res", 5, [3, 6, 7]),           # h = x + o Wo^T; second result y2 = 6; scratch 7
+    ("gemm_act", 8, [6, 9]),              # u = act(y2 Wup^T), scratch 9
+    ("gemm_res", 10, [8, 5, 11, 12]),     # h' = h + u Wdown^T; next layer's rows 11; scratch 12
+    ("gemm_qkv", 13, [11, 14]),
+    ("attn", 15, [13, 16]),
+    ("gemm_res", 17, [15, 10, 18, 19]),
+    ("gemm_act", 20, [18, 21]),
+    ("gemm_res", -1, [20, 17, 22]),       # in place; the caller's output takes the final norm
+]
+
+# One GPT-shaped layer with token input and the tied head, a 256-row prompt: every step is a
+# launch of its own (no rotary embedding in this family).
+GPT_PREFILL_1L = [
+    ("embed", 0, []),
+    ("norm", 1, [0]),
+    ("gemm_qkv", 2, [1, 3]),
+    ("attn", 4, [2, 5]),
+    ("gemm_res", 6, [4, 0, 7]),
+    ("norm", 8, [6]),
+    ("gemm_act", 9, [8, 10]),
+    ("gemm_res", 11, [9, 6, 12]),
+    ("norm", 13, [11]),
+    ("gemm", -1, [13, 14]),
+]
+
+
+@pytest.mark.parametrize("hand,shape,L,tokens,batch,q_len,pos0,kv_cap,flags", [
+    (LLAMA_DECODE_2L, LLAMA, 2, False, 8, 1, 300, 301, (False, False, False)),
+    (GPT_PREFILL_1L, GPT, 1, True, 2, 128, 0, 128, (False, True, True)),
+], ids=["llama_decode_2L", "gpt_prefill_1L"])
+def test_lowering_against_hand_written_lists(hand, shape, L, tokens, batch, q_len, pos0, kv_cap, flags):
+    cm = B.CompiledModel(fake_model(shape, L, tokens, B.FORGE_BF16), batch, q_len, pos0, kv_cap)
+    ops, out_reg, ins, _, _ = cm.program()
+    cm.close()
+    assert list(zip(ops, out_reg, ins)) == _names(hand)
+    # the fixture generator used for the other shapes writes the same list
+    prog, _ = decoder_program(L, tokens, *flags)
+    assert [tuple(p) for p in prog] == _names(hand)
+
+
+# ------------------------------------------------------------------ the fixture generator itself
+
+@pytest.mark.parametrize("tokens,rope,norm2", [(True, False, True), (False, True, True), (False, False, False)])
+def test_decoder_program_shape(tokens, rope, norm2):
+    L = 3
+    prog, kinds = decoder_program(L, tokens, rope, norm2)
+    per_layer = 6 + (2 if rope else 0) + (1 if norm2 else 0)
+    assert len(prog) == L * per_layer + (3 if tokens else 1)
+    # every register is written or first mentioned before any later use, numbering is dense
+    iv = P.live_intervals([(o, i) for _, o, i in prog], len(kinds))
+    assert all(x is not None for x in iv)
+    starts = [s for s, _ in iv]
+    assert starts == sorted(starts)
+    # scratch areas live inside one instruction only
+    assert all(iv[r][0] == iv[r][1] for r, k in enumerate(kinds) if k.startswith("ws_"))
+    buf, m = P.linear_scan(iv)
+    n = len(kinds)
+    assert 0.0 < P.buffer_reduction(m, n) < 1.0
+    assert m == max_alive(iv)
+
+
+def test_decoder_program_buffer_count_does_not_grow_with_depth():
+    counts = []
+    for L in (1, 2, 12, 32):
+        prog, kinds = decoder_program(L, True, False, True)
+        iv = P.live_intervals([(o, i) for _, o, i in prog], len(kinds))
+        counts.append(P.linear_scan(iv)[1])
+    assert counts[1] == counts[2] == counts[3]
+    assert counts[0] <= counts[1]
 
 
 def test_buffer_count_is_independent_of_depth_and_reduction_grows():

@@ -77,14 +77,19 @@ def test_fan_out_keeps_the_source_alive():
     assert m == 3                                    # a, plus the alternating pair of the chain
 
 
-def test_free_pool_is_first_in_first_out():
-    # three registers die one after the other (ends 1, 2, 3), then three are born at index 5,
-    # 6 and 7: they must take the released buffers in the order of release
+def test_lowest_numbered_free_buffer_is_taken():
+    # three registers die one after the other (ends 1, 2, 3); each of the three born at 5, 6 and
+    # 7 lives for one instruction, so every one of them finds buffer 0 free again
     iv = [(0, 1), (0, 2), (0, 3), (5, 5), (6, 6), (7, 7)]
     buf, m = P.linear_scan(iv)
     assert m == 3
-    assert buf[:3] == [0, 1, 2]
-    assert buf[3:] == [0, 1, 2]
+    assert buf == [0, 1, 2, 0, 0, 0]
+    # buffers 2 and 3 come free together at index 2 (r4 takes 2, 3 stays free), buffer 1 at
+    # index 4: r5 then has {1, 3} to choose from and takes the lower number, not the one that
+    # has been free for longer
+    iv = [(0, 9), (0, 3), (0, 1), (0, 1), (2, 9), (4, 9)]
+    buf, m = P.linear_scan(iv)
+    assert (buf, m) == ([0, 1, 2, 3, 2, 1], 4)
 
 
 def test_scratch_register_and_unread_output():
@@ -201,36 +206,3 @@ def test_workspace_plan_hand_worked():
     # ended at 2 -> buffer 0; stride 1024.  group "single": one buffer of 4096 B after it.
     assert off == [0, 2048, 1024, 2048, 0]
     assert (total, nb) == (2048 + 4096, 3)
-
-
-# ------------------------------------------------------------------ the decoder launch list
-
-@pytest.mark.parametrize("tokens,rope,norm2", [(True, False, True), (False, True, True), (False, False, False)])
-def test_decoder_program_shape(tokens, rope, norm2):
-    L = 3
-    prog, kinds = P.decoder_program(L, tokens, rope, norm2)
-    per_layer = 6 + (2 if rope else 0) + (1 if norm2 else 0)
-    assert len(prog) == L * per_layer + (3 if tokens else 1)
-    # every register is written or first mentioned before any later use, numbering is dense
-    iv = P.live_intervals([(o, i) for _, o, i in prog], len(kinds))
-    assert all(x is not None for x in iv)
-    starts = [s for s, _ in iv]
-    assert starts == sorted(starts)
-    # scratch areas live inside one instruction only
-    assert all(iv[r][0] == iv[r][1] for r, k in enumerate(kinds) if k.startswith("ws_"))
-    # the residual stream of a layer is read twice after it is written: by the next norm and by
-    # the next output projection
-    buf, m = P.linear_scan(iv)
-    n = len(kinds)
-    assert 0.0 < P.buffer_reduction(m, n) < 1.0
-    assert m == max_alive(iv)
-
-
-def test_decoder_program_buffer_count_does_not_grow_with_depth():
-    counts = []
-    for L in (1, 2, 12, 32):
-        prog, kinds = P.decoder_program(L, True, False, True)
-        iv = P.live_intervals([(o, i) for _, o, i in prog], len(kinds))
-        counts.append(P.linear_scan(iv)[1])
-    assert counts[1] == counts[2] == counts[3]
-    assert counts[0] <= counts[1]
