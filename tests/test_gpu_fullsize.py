@@ -14,6 +14,7 @@ import torch
 
 from oracle import forge_oracle as O
 from paper_2604_16498_amd import inputs as I
+from layer_parts import layer_by_parts
 from util import check, check_drift, dev, dev_dict, host, strict_err
 
 pytestmark = pytest.mark.gpu
@@ -64,8 +65,10 @@ def test_config2_gpt2_small_full_batch(F):
             for b in (0, B - 1):
                 ref = O.decoder_block(sh, layers[l], host(h[b:b + 1]))
                 worst = max(worst, check(out[b:b + 1], ref, True, "config 2 layer %d seq %d" % (l, b), chain=True))
+        if l == 0:
+            layer_by_parts(F, sh, layers[l], tl[l], h, out, 0, None, "config 2 layer 0 seq 0")
         h = out
-    print("config2 per-layer worst l2 err %.3e" % worst)
+    print("config2 per-layer worst strict elementwise err %.3e" % worst)
 
     # the whole model as the benchmark launches it
     ld = (wl.vocab + 7) // 8 * 8          # padded logits rows, as the benchmark launches it
@@ -107,7 +110,8 @@ def test_config3_1p3b_layer_and_head(F):
     for b in (0, B - 1):
         ref = O.decoder_block(sh, w, x[b:b + 1])
         e = check(out[b:b + 1], ref, True, "config 3 layer seq %d" % b, chain=True)
-        print("config3 layer seq %d l2 err %.3e" % (b, e))
+        print("config3 layer seq %d strict elementwise err %.3e" % (b, e))
+    layer_by_parts(F, sh, w, tw, dev(x, True), out, 0, list(range(0, S, 16)) + [S - 1], "config 3 layer seq 0")
     # tied head at full size: y [8192, 2048] x wte [50272, 2048]
     wte = I.normal(3, 0, "wte", (wl.vocab, sh.d_model), 0.02, bf16=True)
     y = I.normal(3, 0, "misc", (B * S, sh.d_model), 1.0, bf16=True)
@@ -135,7 +139,8 @@ def test_config4_llama8b_prefill_layer(F):
     kc = np.zeros((1, sh.kv_heads, S, sh.head_dim)); vc = np.zeros_like(kc)
     ref = O.decoder_block(sh, w, x, kc, vc, pos0=0, query_rows=rows)
     e = check(out[:, rows], ref, True, "config 4 layer rows", chain=True)
-    print("config4 layer: %d sampled rows, l2 err %.3e" % (len(rows), e))
+    print("config4 layer: %d sampled rows, strict elementwise err %.3e" % (len(rows), e))
+    layer_by_parts(F, sh, w, tw, dev(x, True), out, 0, rows, "config 4 layer")
     check(tk, kc, True, "config 4 K cache (RoPE applied)")
     check(tv, vc, True, "config 4 V cache")
     out2, _, _ = gpu_block(F, desc, dev(x, True), 0, S, sh)
@@ -161,7 +166,7 @@ def test_config5_llama8b_decode_layer(F):
     kcs = kc[sample].astype(np.float64); vcs = vc[sample].astype(np.float64)
     ref = O.decoder_block(sh, w, x[sample], kcs, vcs, pos0=pos0)
     e = check(out[sample], ref, True, "config 5 decode layer", chain=True)
-    print("config5 decode layer l2 err %.3e" % e)
+    print("config5 decode layer strict elementwise err %.3e" % e)
     check(tk[sample, :, pos0], kcs[:, :, pos0], True, "config 5 appended K row")
     check(tv[sample, :, pos0], vcs[:, :, pos0], True, "config 5 appended V row")
     assert torch.equal(tk[:, :, :pos0].cpu(), dev(kc, True)[:, :, :pos0].cpu())   # old rows untouched
@@ -202,7 +207,7 @@ def test_config5_llama8b_decode_layer_int8_weights(F):
     kcs = kc[sample].astype(np.float64); vcs = vc[sample].astype(np.float64)
     ref = O.decoder_block(sh, wo, x[sample], kcs, vcs, pos0=pos0)
     e = check(out[sample], ref, True, "config 5 decode layer, int8 weights", chain=True)
-    print("config5 int8 decode layer l2 err %.3e" % e)
+    print("config5 int8 decode layer strict elementwise err %.3e" % e)
     check(tk[sample, :, pos0], kcs[:, :, pos0], True, "appended K row")
     check(tv[sample, :, pos0], vcs[:, :, pos0], True, "appended V row")
 
