@@ -299,6 +299,24 @@ forge_status forge_attn_decode_varlen(const void* q, const void* k, const void* 
                                       int max_pos, int head_dim, int64_t kv_batch_stride,
                                       int64_t kv_head_stride, float scale, forge_dtype dt,
                                       void* workspace, size_t workspace_bytes, void* stream);
+/* For callers that cannot allocate device memory and have no workspace to hand over (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation): forge_attn_fused for
+ * one new query per sequence (q_len 1, causal, bf16), with the split-KV partial results kept in a
+ * fixed array inside the library's device image instead of a caller workspace.  Same kernels,
+ * same order, bit-identical output.  The call allocates nothing and frees nothing; its first use
+ * on a device looks the array's address up once.
+ * Limit: forge_attn_fused_workspace_bytes(batch, q_heads, kv_heads, 1, kv_len, head_dim,
+ * FORGE_BF16) must not exceed forge_attn_decode_static_max_bytes() (4 MiB; each GPU the library
+ * runs on holds that much until the process ends), else FORGE_ERR_WORKSPACE and nothing is
+ * enqueued.  Every call on one GPU shares the array: calls that may overlap on one GPU (different
+ * streams, different threads) race and must be ordered by the caller.  Nothing in it needs
+ * clearing between calls: every partial a call reads it has written first.
+ * Other arguments, layouts and errors as forge_attn_fused. */
+size_t forge_attn_decode_static_max_bytes(void);
+forge_status forge_attn_decode_static(const void* q, const void* k, const void* v, void* out,
+                                      int batch, int q_heads, int kv_heads, int kv_len, int head_dim,
+                                      int64_t kv_batch_stride, int64_t kv_head_stride, float scale,
+                                      void* stream);
 forge_status forge_decoder_block_decode(const forge_block_desc* desc, const void* x_in, void* x_out,
                                         void* k_cache, void* v_cache, const int32_t* seq_pos,
                                         int batch, int max_pos, int kv_cap, void* workspace,

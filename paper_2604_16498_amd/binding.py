@@ -76,6 +76,8 @@ SIGNATURES = {
     "forge_model_workspace_bytes": (_sz, [C.POINTER(ModelDesc), _i, _i, _i]),
     "forge_model_forward": (_i, [C.POINTER(ModelDesc), _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]),
     "forge_attn_decode_varlen": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _vp, _sz, _vp]),
+    "forge_attn_decode_static_max_bytes": (_sz, []),
+    "forge_attn_decode_static": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _vp]),
     "forge_decoder_block_decode": (_i, [C.POINTER(BlockDesc), _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _sz, _vp]),
     "forge_model_decode": (_i, [C.POINTER(ModelDesc), _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _sz, _vp]),
     "forge_compiled_bind_decode": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -349,6 +351,24 @@ def forge_attn_decode_varlen(q, k, v, out, seq_pos, max_pos, scale=None, workspa
     _check(lib().forge_attn_decode_varlen(_p(q), _p(k), _p(v), _p(out), _p(seq_pos), B, Hq, Hkv, max_pos, dh,
                                           Hkv * cap * dh, cap * dh, scale, _dt(q), wp, wb, _stream()),
            "forge_attn_decode_varlen")
+    return out
+
+
+def forge_attn_decode_static_max_bytes() -> int:
+    return int(lib().forge_attn_decode_static_max_bytes())
+
+
+def forge_attn_decode_static(q, k, v, out, kv_len=None, scale=None):
+    """forge_attn_fused for q_len 1 (bf16, causal) with the library's own fixed scratch: no workspace.
+    q [B,Hq,1,dh]; k, v [B,Hkv,cap,dh]; out [B,1,Hq*dh]."""
+    B, Hq, Sq, dh = q.shape
+    assert Sq == 1 and q.dtype == torch.bfloat16
+    Hkv, cap = k.shape[1], k.shape[2]
+    kv_len = cap if kv_len is None else kv_len
+    scale = dh ** -0.5 if scale is None else scale
+    _check(lib().forge_attn_decode_static(_p(q), _p(k), _p(v), _p(out), B, Hq, Hkv, kv_len, dh,
+                                          Hkv * cap * dh, cap * dh, scale, _stream()),
+           "forge_attn_decode_static")
     return out
 
 

@@ -432,6 +432,32 @@ forge_status forge_attn_decode_varlen(const void* q, const void* k, const void* 
   return attn_dispatch(a, dt, static_cast<hipStream_t>(stream));
 }
 
+forge_status forge_attn_decode_static(const void* q, const void* k, const void* v, void* out, int batch,
+                                      int q_heads, int kv_heads, int kv_len, int head_dim,
+                                      int64_t kv_batch_stride, int64_t kv_head_stride, float scale,
+                                      void* stream) {
+  if (!req(q) || !req(k) || !req(v) || !req(out)) return FORGE_ERR_INVALID_ARG;
+  if (batch < 1 || q_heads < 1 || kv_heads < 1 || kv_len < 1) return FORGE_ERR_INVALID_ARG;
+  if (q_heads % kv_heads != 0 || !scale_ok(scale)) return FORGE_ERR_INVALID_ARG;
+  if (head_dim != 64 && head_dim != 128) return FORGE_ERR_UNSUPPORTED;
+  if (!grid_ok(batch, q_heads)) return FORGE_ERR_UNSUPPORTED;
+  if (kv_head_stride < (int64_t)kv_len * head_dim || kv_batch_stride < kv_head_stride * kv_heads)
+    return FORGE_ERR_INVALID_ARG;
+  if (kv_head_stride % 8 != 0 || kv_batch_stride % 8 != 0) return FORGE_ERR_INVALID_ARG;
+  if (out == q || out == k || out == v) return FORGE_ERR_INVALID_ARG;
+  // the partials of this call must fit the fixed array
+  if (attn_ws(batch, q_heads, kv_heads, 1, kv_len, head_dim, FORGE_BF16) > attn_decode_static_scratch_bytes())
+    return FORGE_ERR_WORKSPACE;
+  void* scratch_ptr = nullptr;
+  const forge_status st = attn_decode_static_scratch(&scratch_ptr);
+  if (st != FORGE_OK) return st;
+  AttnArgs a = {q, k, v, out, batch, q_heads, kv_heads, 1, kv_len, head_dim, kv_batch_stride, kv_head_stride,
+                scale, 1, scratch_ptr, attn_decode_static_scratch_bytes(), nullptr, 0, 0};
+  return attn_dispatch(a, FORGE_BF16, static_cast<hipStream_t>(stream));
+}
+
+size_t forge_attn_decode_static_max_bytes(void) { return attn_decode_static_scratch_bytes(); }
+
 forge_status forge_decoder_block_decode(const forge_block_desc* desc, const void* x_in, void* x_out,
                                         void* k_cache, void* v_cache, const int32_t* seq_pos,
                                         int batch, int max_pos, int kv_cap, void* workspace,

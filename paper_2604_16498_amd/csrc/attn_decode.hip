@@ -342,6 +342,32 @@ size_t attn_decode_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_
   return (size_t)batch * q_heads * splits * (head_dim + 2) * sizeof(float);
 }
 
+// ---- scratch that nobody allocates -----------------------------------------------------------
+// For callers that can neither allocate nor bring a workspace: the split-KV partials go to a
+// fixed array in the library's own device image.  Each GPU holds its own copy at its own address;
+// the name below is only a host-side handle for it, so host code looks the address up once per
+// device (with that device current) and passes the pointer on, as it would a caller's workspace.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+
+size_t attn_decode_static_scratch_bytes() { return kStaticScratchBytes; }
+
+forge_status attn_decode_static_scratch(void** ptr) {
+  static std::atomic<void*> per_device[kMaxDevices];   // zero-initialised; filled on first use
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return FORGE_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return FORGE_ERR_UNSUPPORTED;
+  void* p = per_device[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    // racing first calls look the same address up twice: harmless
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return FORGE_ERR_HIP;
+    per_device[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return FORGE_OK;
+}
+
 forge_status launch_attn_decode_bf16(const AttnArgs& a, hipStream_t s) {
   // what THIS launch writes (at most the bound the size query reports for any cache >= kv_len)
   const int splits = plan_splits(a.batch, a.kv_heads, a.kv_len).splits;

@@ -232,6 +232,10 @@ forge_status launch_attn_simple_bf16(const AttnArgs& a, hipStream_t s);
 forge_status launch_attn_prefill_bf16(const AttnArgs& a, hipStream_t s);
 forge_status launch_attn_decode_bf16(const AttnArgs& a, hipStream_t s);
 size_t attn_decode_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim);
+// The library's own fixed scratch array for the decode attention (one per GPU): its size, and its
+// address on the current device.  Every call on a GPU shares it.
+size_t attn_decode_static_scratch_bytes();
+forge_status attn_decode_static_scratch(void** ptr);
 
 forge_status launch_residual_norm(const void* x, const void* delta, const void* gamma,
                                   const void* beta, void* h_out, void* y, int rows, int d,
