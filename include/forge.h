@@ -420,6 +420,21 @@ forge_status forge_compiled_bind_decode(forge_compiled* c, const void* input, vo
                                         void* workspace, size_t workspace_bytes, void* stream);
 forge_status forge_compiled_run(forge_compiled* c, void* stream);
 
+/* ---------------------------------------------------------------------------------------
+ * Where a step's time goes (Sec. "Evaluation Protocol" measures whole-model latency; this is the
+ * per-operator breakdown of the same launch list).  Between forge_trace_start and
+ * forge_trace_stop, forge_decoder_block, forge_model_forward and their *_decode forms record one
+ * HIP event on their stream after every operator of the list (forge_op: a launch, or the two
+ * launches of a split-K projection); operator i took the time between events i and i + 1, launch
+ * gaps included.  forge_trace_start creates capacity + 1 events and records the first on `stream`
+ * (operators past `capacity` are not recorded); forge_trace_stop waits for the last recorded
+ * event, writes min(*n_ops, capacity) operator codes and durations in milliseconds, and destroys
+ * the events.  One trace at a time (a second start -> FORGE_ERR_INVALID_ARG); a profiling aid,
+ * not for use under stream capture.  The compiled executor's replays are not traced.
+ * ------------------------------------------------------------------------------------ */
+forge_status forge_trace_start(int capacity, void* stream);
+forge_status forge_trace_stop(int* n_ops, int* ops, float* ms, int capacity);
+
 #ifdef __cplusplus
 }
 #endif

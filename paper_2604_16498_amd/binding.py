@@ -76,6 +76,8 @@ SIGNATURES = {
     "forge_model_workspace_bytes": (_sz, [C.POINTER(ModelDesc), _i, _i, _i]),
     "forge_model_forward": (_i, [C.POINTER(ModelDesc), _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]),
     "forge_attn_decode_varlen": (_i, [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _vp, _sz, _vp]),
+    "forge_trace_start": (_i, [_i, _vp]),
+    "forge_trace_stop": (_i, [_ip, _ip, C.POINTER(C.c_float), _i]),
     "forge_attn_decode_static_max_bytes": (_sz, []),
     "forge_attn_decode_static": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _vp]),
     "forge_decoder_block_decode": (_i, [C.POINTER(BlockDesc), _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp, _sz, _vp]),
@@ -352,6 +354,22 @@ def forge_attn_decode_varlen(q, k, v, out, seq_pos, max_pos, scale=None, workspa
                                           Hkv * cap * dh, cap * dh, scale, _dt(q), wp, wb, _stream()),
            "forge_attn_decode_varlen")
     return out
+
+
+OP_NAMES = ["embed", "norm", "gemm_qkv", "rope_q", "rope_k", "attn", "gemm_res", "gemm_act", "gemm"]
+
+
+def forge_trace_start(capacity: int):
+    _check(lib().forge_trace_start(capacity, _stream()), "forge_trace_start")
+
+
+def forge_trace_stop(capacity: int):
+    """-> [(operator name, milliseconds)] of the launch lists run since forge_trace_start."""
+    n = C.c_int(0)
+    ops = (C.c_int * capacity)()
+    ms = (C.c_float * capacity)()
+    _check(lib().forge_trace_stop(C.byref(n), ops, ms, capacity), "forge_trace_stop")
+    return [(OP_NAMES[ops[i]], float(ms[i])) for i in range(min(n.value, capacity))]
 
 
 def forge_attn_decode_static_max_bytes() -> int:

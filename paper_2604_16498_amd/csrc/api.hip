@@ -4,7 +4,32 @@
 
 using namespace forge;
 
+#include <mutex>
+#include <vector>
+
 namespace {
+
+// ---- per-operator timing of the launch lists (forge_trace_*) ---------------------------------
+// While a trace is open, the launch lists record one HIP event on their stream after every
+// operator (a launch, or a split-K launch pair); the time between two events is that operator's
+// duration inside the step, launch gaps included.  The events are created when the trace is
+// opened, so the launch lists themselves still allocate nothing.
+struct Trace {
+  std::mutex mu;
+  bool open = false;
+  int n = 0;
+  std::vector<hipEvent_t> ev;    // ev[0] opens the trace, ev[i + 1] follows operator i
+  std::vector<int> op;
+};
+Trace g_trace;
+
+inline void trace_mark(hipStream_t s, forge_op op) {
+  if (!g_trace.open) return;                    // unsynchronised fast path: a trace is opened and
+  std::lock_guard<std::mutex> lock(g_trace.mu); // closed by the thread that also launches
+  if (!g_trace.open || g_trace.n + 1 >= (int)g_trace.ev.size()) return;
+  if (hipEventRecord(g_trace.ev[g_trace.n + 1], s) != hipSuccess) return;
+  g_trace.op[g_trace.n++] = (int)op;
+}
 
 struct BlockPlan {
   size_t y, q, o, u, attn, gemm, total;
@@ -65,6 +90,7 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
   if (!x_normed) {
     st = launch_residual_norm(x_in, nullptr, d->norm1_g, d->norm1_b, nullptr, y, T, dm, d->eps, d->norm, d->dt, s);
     if (st != FORGE_OK) return st;
+    trace_mark(s, FORGE_OP_NORM);
   }
   // 2. QKV projection, written head-major: q to the workspace, k and v into the cache rows
   // (a decode-sized QKV projection rotates q and k in its own reduce step)
@@ -74,20 +100,24 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
   GemmArgs g = {y, d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, 0, FORGE_ACT_NONE, &sp, nullptr, gws, pl.gemm, d->s_qkv};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
+  trace_mark(s, FORGE_OP_GEMM_QKV);
   // 3. rotary embedding of the new q and k rows
   if (d->use_rope && !rope_in_gemm) {
     st = launch_rope(q, batch, d->q_heads, q_len, dh, (int64_t)d->q_heads * q_len * dh,
                      (int64_t)q_len * dh, 0, pos0, d->rope_base, d->dt, s, seq_pos, false);
     if (st != FORGE_OK) return st;
+    trace_mark(s, FORGE_OP_ROPE_Q);
     st = launch_rope(k_cache, batch, d->kv_heads, q_len, dh, kv_bs, kv_hs, pos0, pos0, d->rope_base, d->dt, s,
                      seq_pos, true);
     if (st != FORGE_OK) return st;
+    trace_mark(s, FORGE_OP_ROPE_K);
   }
   // 4. fused causal attention over cache rows [0, pos0 + q_len)
   AttnArgs at = {q, k_cache, v_cache, o, batch, d->q_heads, d->kv_heads, q_len, pos0 + q_len, dh,
                  kv_bs, kv_hs, 1.0f / sqrtf((float)dh), 1, aws, pl.attn, nullptr, 0, 0, seq_pos};
   st = attn_dispatch(at, d->dt, s);
   if (st != FORGE_OK) return st;
+  trace_mark(s, FORGE_OP_ATTN);
   // 5. output projection + bias + residual
   //    (decode-sized: the reduce step of the projection also produces the second norm)
   const bool norm_in_gemm = gemm_fuses_tail(T, dm, d->dt);
@@ -96,19 +126,24 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
                norm_in_gemm ? &nt : nullptr, gws, pl.gemm, d->s_o};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
+  trace_mark(s, FORGE_OP_GEMM_RES);
   // 6. second norm
   if (!norm_in_gemm) {
     st = launch_residual_norm(x_out, nullptr, d->norm2_g, d->norm2_b, nullptr, y, T, dm, d->eps, d->norm, d->dt, s);
     if (st != FORGE_OK) return st;
+    trace_mark(s, FORGE_OP_NORM);
   }
   // 7. MLP up projection + bias + activation (SwiGLU: gate and up in one pass)
   g = GemmArgs{y, d->w_up, d->b_up, nullptr, u, T, d->d_ff, dm, 0, d->mlp_act, nullptr, nullptr, gws, pl.gemm, d->s_up};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;
+  trace_mark(s, FORGE_OP_GEMM_ACT);
   // 8. MLP down projection + bias + residual
   //    (+ the next consumer's norm of the new residual stream, see above)
   g = GemmArgs{u, d->w_down, d->b_down, x_out, x_out, T, dm, d->d_ff, 0, FORGE_ACT_NONE, nullptr, next_norm, gws, pl.gemm, d->s_down};
-  return gemm_dispatch(g, d->dt, s);
+  st = gemm_dispatch(g, d->dt, s);
+  if (st == FORGE_OK) trace_mark(s, FORGE_OP_GEMM_RES);
+  return st;
 }
 
 struct ModelPlan {
@@ -149,6 +184,49 @@ const char* forge_status_string(forge_status s) {
 }
 
 int forge_version(void) { return 100; }
+
+forge_status forge_trace_start(int capacity, void* stream) {
+  if (capacity < 1 || capacity > (1 << 20)) return FORGE_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_trace.mu);
+  if (g_trace.open) return FORGE_ERR_INVALID_ARG;
+  g_trace.ev.assign(capacity + 1, nullptr);
+  g_trace.op.assign(capacity, 0);
+  g_trace.n = 0;
+  for (hipEvent_t& e : g_trace.ev) {
+    if (hipEventCreate(&e) != hipSuccess) {
+      for (hipEvent_t& f : g_trace.ev)
+        if (f != nullptr) (void)hipEventDestroy(f);
+      g_trace.ev.clear();
+      return FORGE_ERR_HIP;
+    }
+  }
+  if (hipEventRecord(g_trace.ev[0], static_cast<hipStream_t>(stream)) != hipSuccess) {
+    for (hipEvent_t& f : g_trace.ev) (void)hipEventDestroy(f);
+    g_trace.ev.clear();
+    return FORGE_ERR_HIP;
+  }
+  g_trace.open = true;
+  return FORGE_OK;
+}
+
+forge_status forge_trace_stop(int* n_ops, int* ops, float* ms, int capacity) {
+  std::lock_guard<std::mutex> lock(g_trace.mu);
+  if (!g_trace.open) return FORGE_ERR_INVALID_ARG;
+  g_trace.open = false;
+  forge_status st = FORGE_OK;
+  const int n = g_trace.n;
+  if (n_ops != nullptr) *n_ops = n;
+  if (n > 0 && hipEventSynchronize(g_trace.ev[n]) != hipSuccess) st = FORGE_ERR_HIP;
+  for (int i = 0; i < n && i < capacity && st == FORGE_OK; ++i) {
+    if (ops != nullptr) ops[i] = g_trace.op[i];
+    if (ms != nullptr && hipEventElapsedTime(&ms[i], g_trace.ev[i], g_trace.ev[i + 1]) != hipSuccess)
+      st = FORGE_ERR_HIP;
+  }
+  for (hipEvent_t& e : g_trace.ev) (void)hipEventDestroy(e);
+  g_trace.ev.clear();
+  g_trace.op.clear();
+  return st;
+}
 
 size_t forge_attn_fused_workspace_bytes(int batch, int q_heads, int kv_heads, int q_len, int kv_len,
                                         int head_dim, forge_dtype dt) {
@@ -368,6 +446,7 @@ static forge_status model_forward(const forge_model_desc* model, const void* inp
     st = launch_embed(static_cast<const int32_t*>(input), model->wte, model->wpe, h, batch, q_len,
                       dm, model->vocab, model->n_pos, pos0, dt, s, seq_pos);
     if (st != FORGE_OK) return st;
+    trace_mark(s, FORGE_OP_EMBED);
     x = h;
   }
   // decode-sized steps: every norm after the first rides on the reduce step of the projection
@@ -390,12 +469,15 @@ static forge_status model_forward(const forge_model_desc* model, const void* inp
     st = launch_residual_norm(h, nullptr, model->normf_g, model->normf_b, nullptr, yf, T, dm, d0->eps,
                               d0->norm, dt, s);
     if (st != FORGE_OK) return st;
+    trace_mark(s, FORGE_OP_NORM);
   }
   if (!tokens) return FORGE_OK;
   // tied LM head: the token table is the weight of the last projection
   GemmArgs g = {yf, model->wte, nullptr, nullptr, output, T, model->vocab, dm, model->logits_ld, FORGE_ACT_NONE,
                 nullptr, nullptr, bws, pl.block};
-  return gemm_dispatch(g, dt, s);
+  st = gemm_dispatch(g, dt, s);
+  if (st == FORGE_OK) trace_mark(s, FORGE_OP_GEMM);
+  return st;
 }
 
 forge_status forge_model_forward(const forge_model_desc* model, const void* input, void* output,
