@@ -60,8 +60,10 @@ __device__ inline void wave_lds_sync() {
 __device__ inline float xor16_max(float x) { return fmaxf(x, __shfl_xor(x, 16, 64)); }
 __device__ inline float xor32_max(float x) { return fmaxf(x, __shfl_xor(x, 32, 64)); }
 
+// G: query heads per KV head, 1 ... 8 (the MFMA's 16 head columns hold them zero-padded; the
+// P . V accumulators grow with G, so the larger groups run at two blocks per SIMD instead of three)
 template <int DH, int G>
-__global__ __launch_bounds__(NWAVES * 64, 3) void attn_decode_kernel(DecParams p) {
+__global__ __launch_bounds__(NWAVES * 64, G > 4 ? 2 : 3) void attn_decode_kernel(DecParams p) {
   constexpr int NJ = DH / 32;          // MFMAs (and K loads) per tile
   constexpr int LPR = DH / 8;          // lanes per V row
   constexpr int KPS = 64 / LPR;        // rows per wave-wide V load
@@ -329,8 +331,13 @@ forge_status launch_d(const AttnArgs& a, hipStream_t s) {
   switch (a.q_heads / a.kv_heads) {
     case 1: return launch_dg<DH, 1>(a, s);
     case 2: return launch_dg<DH, 2>(a, s);
+    case 3: return launch_dg<DH, 3>(a, s);
     case 4: return launch_dg<DH, 4>(a, s);
-    default: return launch_attn_simple_bf16(a, s);   // other group sizes: vector-ALU path
+    case 5: return launch_dg<DH, 5>(a, s);
+    case 6: return launch_dg<DH, 6>(a, s);
+    case 7: return launch_dg<DH, 7>(a, s);
+    case 8: return launch_dg<DH, 8>(a, s);
+    default: return launch_attn_simple_bf16(a, s);   // larger groups: vector-ALU path
   }
 }
 

@@ -277,6 +277,13 @@ ATTN_SHAPES = [  # B, Hq, Hkv, Sq, Skv, cap, dh
     (130, 8, 4, 1, 45, 64, 128),
     # ... and with about one pair per CU: two row ranges
     (33, 32, 8, 1, 1000, 1000, 128),
+    # decode with 3, 5, 6, 7, 8 and 16 query heads per KV head (16: the vector-ALU path)
+    (2, 64, 8, 1, 513, 520, 128),
+    (70, 16, 2, 1, 300, 300, 64),
+    (2, 10, 2, 1, 900, 900, 64),
+    (1, 12, 2, 1, 1500, 1504, 128),
+    (3, 7, 1, 1, 260, 264, 64),
+    (1, 32, 2, 1, 400, 400, 128),
 ]
 
 
