@@ -266,9 +266,15 @@ def operator_work(wl, F, torch, logits_ld):
             return ("hbm", float(nw) * K * es, inst)
         return ("mfma", 2.0 * T * nw * K, inst)
 
+    qkv = gemm(sh.qkv_out, d, "none", 1)
+    if sh.use_rope and wl.bf16 and wl.seq > 1 and T > 64:
+        # a bf16 prompt rotates q and k in the epilogue of its QKV projection (cos / sin table kernel
+        # + the head-split kernels in their rotating form, by columns: whole rounds of 256-tiles, the
+        # rest on 128-tiles)
+        qkv = (qkv[0], qkv[1], "rope_table + gemm_bf16_pers<256,256,2,4,0,3> + gemm_bf16_pers<128,128,2,2,0,3>")
     ops = {
         "norm": ("hbm", 2.0 * T * d * es, "residual_norm"),
-        "gemm_qkv": gemm(sh.qkv_out, d, "none", 1),
+        "gemm_qkv": qkv,
         "rope_q": ("hbm", 2.0 * T * hd * es, "rope"),
         "rope_k": ("hbm", 2.0 * T * sh.kv_heads * sh.head_dim * es, "rope"),
         "out_proj": gemm(d, hd, "none", 0),

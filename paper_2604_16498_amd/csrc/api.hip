@@ -48,7 +48,7 @@ BlockPlan plan_block(const forge_block_desc* d, int batch, int q_len, int kv_cap
   p.attn = align_up(attn_ws(batch, d->q_heads, d->kv_heads, q_len, kv_cap, d->head_dim, d->dt), 256);
   const bool w8 = block_w8(d);
   size_t g = 0;
-  for (size_t v : {gemm_ws((int)T, nqkv, d->d_model, FORGE_ACT_NONE, d->dt, w8),
+  for (size_t v : {gemm_qkv_workspace_bytes((int)T, nqkv, d->d_model, d->dt, w8, d->use_rope != 0, q_len, d->head_dim),
                    gemm_ws((int)T, d->d_model, hd, FORGE_ACT_NONE, d->dt, w8),
                    gemm_ws((int)T, d->d_ff, d->d_model, d->mlp_act, d->dt, w8),
                    gemm_ws((int)T, d->d_model, d->d_ff, FORGE_ACT_NONE, d->dt, w8)})
@@ -93,10 +93,11 @@ forge_status run_block(const forge_block_desc* d, const void* x_in, void* x_out,
     trace_mark(s, FORGE_OP_NORM);
   }
   // 2. QKV projection, written head-major: q to the workspace, k and v into the cache rows
-  // (a decode-sized QKV projection rotates q and k in its own reduce step)
-  const bool rope_in_gemm = d->use_rope && gemm_fuses_tail(T, nqkv, d->dt);
+  // (the projection rotates q and k itself where it can: in the reduce step of a decode-sized one,
+  // in the epilogue of a prompt-sized bf16 one)
+  const bool rope_in_gemm = d->use_rope && gemm_qkv_fuses_rope(T, nqkv, dm, dh, q_len, d->dt, block_w8(d));
   QkvSplit sp = {q, k_cache, v_cache, d->q_heads, d->kv_heads, dh, q_len, kv_cap, pos0,
-                 rope_in_gemm ? 1 : 0, d->rope_base, seq_pos};
+                 rope_in_gemm ? 1 : 0, d->rope_base, seq_pos, nullptr};
   GemmArgs g = {y, d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, 0, FORGE_ACT_NONE, &sp, nullptr, gws, pl.gemm, d->s_qkv};
   st = gemm_dispatch(g, d->dt, s);
   if (st != FORGE_OK) return st;

@@ -156,12 +156,13 @@ struct QkvSplit {
   void* k_cache;  // [B,Hkv,kv_cap,dh]
   void* v_cache;
   int q_heads, kv_heads, head_dim, q_len, kv_cap, pos0;
-  int rope;         // the GEMM rotates the new q and k rows itself (only where gemm_fuses_tail() says so)
+  int rope;         // the GEMM rotates the new q and k rows itself (only where gemm_qkv_fuses_rope() says so)
   float rope_base;
   // Per-sequence positions (decode step of a generation loop, q_len == 1): device array [B];
   // sequence b writes cache row pos[b] and rotates by pos[b].  pos0 is then the largest position
   // the caller vouches for: values are clamped to [0, pos0] so a bad entry cannot leave the cache.
   const int* pos;
+  const float* rope_tab;   // set by the launcher: cos / sin table of a prompt-sized rotating projection
 };
 
 __device__ inline int seq_position(const int* pos, int b, int pos0) {
@@ -200,6 +201,11 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
 // the q / k heads of a head split (QkvSplit::rope) and normalise the rows of a residual GEMM
 // (GemmArgs::norm).  Otherwise both fields are ignored and the caller launches those operators.
 bool gemm_fuses_tail(int M, int N, forge_dtype dt);
+// True when the QKV projection of this size rotates q and k itself (QkvSplit::rope): the reduce
+// kernel of the split-K path (M <= 64), or the epilogue of the persistent kernels (prompts), which
+// then needs gemm_qkv_workspace_bytes() of workspace for its cos / sin table.
+bool gemm_qkv_fuses_rope(int M, int N, int K, int head_dim, int q_len, forge_dtype dt, bool w8);
+size_t gemm_qkv_workspace_bytes(int M, int N, int K, forge_dtype dt, bool w8, bool rope, int q_len, int head_dim);
 size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act);
 size_t gemm_w8_workspace_bytes(int M, int N, int K, forge_act act);   // required, any M
 // Symmetric int8 quantisation of a weight, one scale per row.

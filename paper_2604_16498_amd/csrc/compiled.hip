@@ -100,7 +100,7 @@ void lower(forge_compiled* c) {
   for (int l = 0; l < m.n_layers; ++l) {
     const forge_block_desc& d = c->layers[l];
     const int hd = d.q_heads * d.head_dim, nqkv = (d.q_heads + 2 * d.kv_heads) * d.head_dim;
-    const bool rope_in_gemm = d.use_rope && gemm_fuses_tail(Ti, nqkv, dt);
+    const bool rope_in_gemm = d.use_rope && gemm_qkv_fuses_rope(Ti, nqkv, dm, d.head_dim, c->q_len, dt, block_w8(&d));
     const bool norm_in_gemm = gemm_fuses_tail(Ti, dm, dt);
     const bool w8 = block_w8(&d);
 
@@ -110,7 +110,7 @@ void lower(forge_compiled* c) {
       lo.emit({FORGE_OP_NORM, l, 0, y, h, REG_NONE, REG_NONE, REG_NONE}, {h});
     }
     const int q = lo.new_reg(T * hd * es);
-    int ws = lo.new_reg(gemm_ws(Ti, nqkv, dm, FORGE_ACT_NONE, dt, w8));
+    int ws = lo.new_reg(gemm_qkv_workspace_bytes(Ti, nqkv, dm, dt, w8, d.use_rope != 0, c->q_len, d.head_dim));
     lo.emit({FORGE_OP_GEMM_QKV, l, rope_in_gemm ? 1 : 0, q, y, REG_NONE, REG_NONE, ws}, {y, ws});
     if (d.use_rope && !rope_in_gemm) {
       lo.emit({FORGE_OP_ROPE_Q, l, 0, REG_NONE, q, REG_NONE, REG_NONE, REG_NONE}, {q});
@@ -207,7 +207,7 @@ forge_status run_program(const forge_compiled* c, hipStream_t s) {
       }
       case FORGE_OP_GEMM_QKV: {
         QkvSplit sp = {out(I.out), kc, vc, d->q_heads, d->kv_heads, dh, c->q_len, c->kv_cap, c->pos0,
-                       I.which, d->rope_base, c->seq_pos};
+                       I.which, d->rope_base, c->seq_pos, nullptr};
         GemmArgs g = {in(I.x), d->w_qkv, d->b_qkv, nullptr, nullptr, T, nqkv, dm, 0, FORGE_ACT_NONE,
                       &sp, nullptr, out(I.ws), bytes(I.ws), d->s_qkv};
         st = gemm_dispatch(g, dt, s);

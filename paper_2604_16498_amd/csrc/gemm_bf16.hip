@@ -81,9 +81,12 @@ struct GemmParams {
   const int8_t* w8;     // weight-only int8 (M <= 64 streaming path): [N, K] bytes; w is NULL then
   const float* wscale;  // one scale per weight row, applied to the reduced sum before the bias
   int row0;             // row of the whole problem that row 0 of this launch is (head split only)
+  int col0;             // column of the whole problem that column 0 of this launch is (head split only)
 };
 
-enum Mode { MODE_PLAIN = 0, MODE_QKV = 1, MODE_SPLITK = 2 };
+// MODE_QKV_ROPE: the head split with the rotary embedding applied in the epilogue (prompt-sized
+// problems; the decode-sized ones rotate in their reduce kernel)
+enum Mode { MODE_PLAIN = 0, MODE_QKV = 1, MODE_SPLITK = 2, MODE_QKV_ROPE = 3 };
 
 template <int BM, int BN, int WM, int WN, int ACT, int MODE>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_generic_kernel(GemmParams p) {
@@ -284,6 +287,13 @@ __device__ inline void lds_barrier() {
 template <int BM, int BN, int WM, int WN, int ACT, int MODE>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams p) {
   constexpr bool SPLITK = MODE == MODE_SPLITK;   // raw fp32 partial tiles over grid-wide k ranges
+  constexpr bool QKV = MODE == MODE_QKV || MODE == MODE_QKV_ROPE;
+  // ROPE: the w slab rows are arranged so that accumulator (., 0) holds a 32-column block of the
+  // FIRST half of a head and accumulator (., 1) the block dh/2 columns further on: a lane then owns
+  // both members of every rotation pair (i, i + dh/2) of its row and rotates them in fp32, with
+  // cos / sin from a table indexed by (row of the sequence, i), before the single rounding.
+  constexpr bool ROPE = MODE == MODE_QKV_ROPE;
+  static_assert(!ROPE || (ACT == FORGE_ACT_NONE && BN / WN / 32 == 2), "rotation pairs two accumulators");
   static_assert(!SPLITK || ACT == FORGE_ACT_NONE, "the reduce kernel carries the epilogue");
   constexpr int NW = WM * WN;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -342,6 +352,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
     n0 = ((tile % in_group) / gsz) * BN_OUT;
   };
 
+  // ROPE: 32-column block of the tile that accumulator t of wave column wcol holds.  A head is
+  // 2 * hb blocks wide (hb = dh / 64: 1 or 2); wave columns go over (head, block of its first
+  // half), and t = 1 is the partner block hb further on.  dh = 64 gives the natural order.
+  const int rope_hb = ROPE ? p.sp.head_dim / 64 : 1;
+  auto rope_block = [&](int wcol, int t) { return (wcol / rope_hb) * (2 * rope_hb) + wcol % rope_hb + t * rope_hb; };
+
   // ---- direct-to-LDS copy plan, sources as 32-bit byte offsets ------------------------------------
   // wave-wide load i of this wave fills LDS rows (i*NW + wave)*8 .. +8 of a slab (1 KB at
   // lane*16): lane -> (row = base + lane/8, position = lane%8) -> logical chunk = position ^ f(row)
@@ -362,6 +378,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
         const int wcol = r / (32 * TN), t = (r / 32) % TN, rr = r % 32;
         const int col = n0 + (wcol * (TN / 2) + t % (TN / 2)) * 32 + rr;
         gn = min(col, N - 1) + (t >= TN / 2 ? N : 0);
+      } else if (ROPE) {
+        // wave column wcol, accumulator t -> 32-column block of the tile (see rope_block)
+        const int wcol = r / 64, t = (r / 32) & 1, rr = r % 32;
+        gn = min(n0 + rope_block(wcol, t) * 32 + rr, N - 1);
       } else {
         gn = min(n0 + r, N - 1);
       }
@@ -408,10 +428,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
   auto piece_chunk = [&](int row) { return (lane % NCH) ^ (row & (NCH - 1)); };
   // head split: n / head_dim by multiplication (exact for n * head_dim < 2^32), (batch, position)
   // of a row from those of the tile's first row
-  const unsigned dh_magic = MODE == MODE_QKV ? 0xffffffffu / (unsigned)p.sp.head_dim + 1u : 0u;
+  const unsigned dh_magic = QKV ? 0xffffffffu / (unsigned)p.sp.head_dim + 1u : 0u;
   auto dst_of = [&](int t_b, int t_s, int m0_, int row, int n) -> bf16* {
-    if (MODE == MODE_QKV) {
+    if (QKV) {
       // 8 consecutive columns never straddle a head (head_dim % 8 == 0, n % 8 == 0)
+      n += p.col0;
       int sb_ = t_b, ss_ = t_s + row;
       while (ss_ >= p.sp.q_len) { ss_ -= p.sp.q_len; ++sb_; }
       const int dh = p.sp.head_dim, nq = p.sp.q_heads * dh, nkv = p.sp.kv_heads * dh;
@@ -525,7 +546,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
     }
     const bool interior = m0 + BM <= M && n0 + BN_OUT <= N;
     int tb = 0, ts = 0;
-    if (MODE == MODE_QKV) { tb = m0 / p.sp.q_len; ts = m0 - tb * p.sp.q_len; }
+    if (QKV) { tb = m0 / p.sp.q_len; ts = m0 - tb * p.sp.q_len; }
 #pragma unroll
     for (int pass = 0; pass < NPASS; ++pass) {
       if (pass > 0) lds_barrier();    // the previous pass has been read out
@@ -550,6 +571,49 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
         const int rl = (wm * TM + i) * 32 + fr;       // row inside the tile
         if (rl / BMP != pass) continue;               // uniform over the wave
         const int rp = rl - pass * BMP;               // row inside the pass
+        if constexpr (ROPE) {
+          // this lane's row of the sequence: the table row of its angles
+          int ss_ = ts + rl;
+          while (ss_ >= p.sp.q_len) ss_ -= p.sp.q_len;
+          const int dh = p.sp.head_dim, half = dh / 2;
+          const float* tab = p.sp.rope_tab + (int64_t)ss_ * dh;      // [half] x (cos, sin)
+          float lo[2][8], hi[2][8];
+          runs_of(acc[i][0], lo);
+          runs_of(acc[i][1], hi);
+          const int blk = rope_block(wn, 0);
+#pragma unroll
+          for (int gp = 0; gp < 2; ++gp) {
+            const int cl = blk * 4 + 2 * fh + gp, ch = cl + rope_hb * 4;   // chunks of the pair's two halves
+            const int n_lo = n0 + cl * 8, n_hi = n0 + ch * 8;
+            if (p.bias != nullptr && n_hi + 8 <= N) {     // N % 8 == 0 (host): a chunk is all in or all out
+              float bb[8];
+              Vec8<bf16>::load(p.bias + n_lo, bb);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) lo[gp][e] += bb[e];
+              Vec8<bf16>::load(p.bias + n_hi, bb);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) hi[gp][e] += bb[e];
+            }
+            if (p.col0 + n_lo < (p.sp.q_heads + p.sp.kv_heads) * dh) {    // q and k heads rotate, v heads do not
+              const int d0 = (cl * 8) & (half - 1);              // pair index of the chunk's first column
+              float cs[16];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const floatx4 t4 = *reinterpret_cast<const floatx4*>(tab + 2 * d0 + 4 * e);
+                cs[4 * e] = t4[0]; cs[4 * e + 1] = t4[1]; cs[4 * e + 2] = t4[2]; cs[4 * e + 3] = t4[3];
+              }
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                const float c = cs[2 * e], sn = cs[2 * e + 1], a = lo[gp][e], d = hi[gp][e];
+                lo[gp][e] = a * c - d * sn;
+                hi[gp][e] = d * c + a * sn;
+              }
+            }
+            Vec8<bf16>::store(reinterpret_cast<bf16*>(stg + (rp * NCH + (cl ^ (rp & (NCH - 1)))) * 16), lo[gp]);
+            Vec8<bf16>::store(reinterpret_cast<bf16*>(stg + (rp * NCH + (ch ^ (rp & (NCH - 1)))) * 16), hi[gp]);
+          }
+          continue;
+        }
 #pragma unroll
         for (int j = 0; j < TN_OUT; ++j) {
           float run[2][8], run2[2][8];
@@ -1104,7 +1168,39 @@ forge_status launch_wstream(const GemmParams& q, int splits, hipStream_t s) {
 
 template <int ACT, int MODE>
 forge_status launch_act(const GemmParams& p, hipStream_t s) {
-  const Variant v = choose_variant(p.M, p.N, p.K, p.ldy, (forge_act)ACT, MODE == MODE_QKV);
+  const Variant v = choose_variant(p.M, p.N, p.K, p.ldy, (forge_act)ACT, MODE == MODE_QKV || MODE == MODE_QKV_ROPE);
+  if constexpr (MODE == MODE_QKV || MODE == MODE_QKV_ROPE) {
+    // A head split whose 256-tiles do not come to whole rounds over the CUs (4096 x 6144: 384 tiles
+    // on 256 CUs) is cut by columns: as many columns as make whole rounds of 256-tiles, the rest on
+    // 128-tiles (4096 + 2048 columns: one round each).  Worth it from K = 2048 on, where the large
+    // tile multiplies faster.  Each part writes its own heads; two launches.
+    if (v == V_FAST_128 && p.K >= 2048 && p.col0 == 0) {
+      const int cus = compute_units(), tm = ceil_div(p.M, 256);
+      int g = tm, r = cus;
+      while (r != 0) { const int t = g % r; g = r; r = t; }          // gcd(tm, cus)
+      const int64_t cols_per_round = (int64_t)(cus / g) * 256;
+      const int c = (int)(p.N / cols_per_round * cols_per_round);
+      if (c >= 256 && c < p.N && 2 * (int64_t)c >= p.N) {
+        GemmParams a = p, b = p;
+        a.N = c;
+        b.N = p.N - c;
+        b.col0 = c;
+        b.part = nullptr;          // the parts run unsplit along K: the reduce kernels know no column offset
+        b.part_bytes = 0;
+        b.w = p.w + (int64_t)c * p.K;
+        if (p.bias != nullptr) b.bias = p.bias + c;
+        const forge_status st = launch_act<ACT, MODE>(a, s);
+        return st != FORGE_OK ? st : launch_act<ACT, MODE>(b, s);
+      }
+    }
+  }
+  if constexpr (MODE == MODE_QKV_ROPE) {
+    // only the persistent kernels rotate in their epilogue; gemm_qkv_fuses_rope() has vouched for
+    // the fast path, and the 128-tile takes the wave layout with two accumulators per wave
+    if (v == V_FAST_256) return launch_pers<256, 256, 2, 4, ACT, MODE>(p, s);
+    if (v == V_FAST_128) return launch_pers<128, 128, 2, 2, ACT, MODE>(p, s);
+    return FORGE_ERR_UNSUPPORTED;
+  } else {
   switch (v) {
     case V_FAST_256: return launch_pers<256, 256, 2, 4, ACT, MODE>(p, s);
     case V_FAST_128: {
@@ -1157,9 +1253,45 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
   const int64_t threads = (int64_t)p.M * ceil_div(p.N, 4);
   splitk_reduce_kernel<ACT, MODE == MODE_QKV><<<(unsigned)ceil_div64(threads, 256), 256, 0, s>>>(p, sk.splits, sk.ncols);
   return launch_status();
+  }
+}
+
+// cos / sin of the rotary embedding for rows 0 .. q_len-1 of a prompt at positions pos0 + s:
+// tab[s][i] = (cos, sin)(p * theta_i), theta_i = base^(-2i/dh), evaluated in fp64 as rope_kernel
+// does (p * theta reaches thousands of radians) and stored as fp32.
+__global__ __launch_bounds__(256) void rope_table_kernel(float* __restrict__ tab, int q_len, int head_dim,
+                                                         int pos0, float base) {
+  const int half = head_dim / 2;
+  const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= q_len * half) return;
+  const int i = gid % half, s = gid / half;
+  const double theta = exp2(-2.0 * (double)i / (double)head_dim * log2((double)base));
+  double sv, cv;
+  sincos((double)(pos0 + s) * theta, &sv, &cv);
+  floatx2 o = {(float)cv, (float)sv};
+  *reinterpret_cast<floatx2*>(tab + 2 * (int64_t)gid) = o;
 }
 
 }  // namespace
+
+bool gemm_qkv_fuses_rope(int M, int N, int K, int head_dim, int q_len, forge_dtype dt, bool w8) {
+  if (dt != FORGE_BF16) return false;
+  if (M <= 64) return gemm_fuses_tail(M, N, dt);     // the reduce step of the weight-streaming path rotates
+  if (w8) return false;                              // int8 prompts run 64 rows at a time, unrotated
+  if (q_len == 1) return false;                      // a wide decode step may carry per-sequence positions
+  if (head_dim != 64 && head_dim != 128) return false;
+  const Variant v = choose_variant(M, N, K, N, FORGE_ACT_NONE, true);
+  if (v != V_FAST_256 && v != V_FAST_128) return false;
+  // a 128-tile problem that would rather split its reduction keeps the separate rotation
+  return v == V_FAST_256 || plan_pers_split(M, N, K).splits == 1;
+}
+
+size_t gemm_qkv_workspace_bytes(int M, int N, int K, forge_dtype dt, bool w8, bool rope, int q_len, int head_dim) {
+  if (rope && M > 64 && gemm_qkv_fuses_rope(M, N, K, head_dim, q_len, dt, w8))
+    return (size_t)q_len * head_dim * sizeof(float);            // the cos / sin table
+  if (w8) return gemm_w8_workspace_bytes(M, N, K, FORGE_ACT_NONE);
+  return dt == FORGE_BF16 ? gemm_bf16_workspace_bytes(M, N, K, FORGE_ACT_NONE) : gemm_f32_workspace_bytes(M, N, K, FORGE_ACT_NONE);
+}
 
 size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act) {
   if (M > 64) {     // optional: without it the problem runs unsplit
@@ -1216,12 +1348,30 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
     if (p.ldy != a.N) return FORGE_ERR_UNSUPPORTED;   // the norm tail writes dense rows
     p.nt = *a.norm;
   }
+  bool rope_epilogue = false;
   if (a.split != nullptr) {
     if (a.act != FORGE_ACT_NONE || a.residual != nullptr) return FORGE_ERR_UNSUPPORTED;
     p.sp = *a.split;
-    if (!tails) p.sp.rope = 0;
+    if (p.sp.rope && a.M > 64) {
+      // prompt-sized: the epilogue rotates, with cos / sin from a table written into the workspace
+      if (!gemm_qkv_fuses_rope(a.M, a.N, a.K, p.sp.head_dim, p.sp.q_len, FORGE_BF16, w8) || p.sp.pos != nullptr)
+        return FORGE_ERR_UNSUPPORTED;
+      const size_t tab_bytes = (size_t)p.sp.q_len * p.sp.head_dim * sizeof(float);
+      if (a.workspace == nullptr || a.workspace_bytes < tab_bytes) return FORGE_ERR_WORKSPACE;
+      const int n_tab = p.sp.q_len * (p.sp.head_dim / 2);
+      rope_table_kernel<<<ceil_div(n_tab, 256), 256, 0, s>>>((float*)a.workspace, p.sp.q_len, p.sp.head_dim,
+                                                           p.sp.pos0, p.sp.rope_base);
+      if (hipGetLastError() != hipSuccess) return FORGE_ERR_HIP;
+      p.sp.rope_tab = (const float*)a.workspace;
+      p.part = nullptr;
+      p.part_bytes = 0;
+      rope_epilogue = true;
+    } else if (!tails) {
+      p.sp.rope = 0;
+    }
   }
   auto dispatch = [&](const GemmParams& q) -> forge_status {
+    if (rope_epilogue) return launch_act<FORGE_ACT_NONE, MODE_QKV_ROPE>(q, s);
     if (a.split != nullptr) return launch_act<FORGE_ACT_NONE, MODE_QKV>(q, s);
     switch (a.act) {
       case FORGE_ACT_NONE: return launch_act<FORGE_ACT_NONE, MODE_PLAIN>(q, s);

@@ -14,10 +14,17 @@ from oracle import forge_oracle as O
 from util import check, host, strict_err
 
 
-def layer_by_parts(F, sh, w, tw, tx, block_out, seq, rows, what):
+def layer_by_parts(F, sh, w, tw, tx, block_out, seq, rows, what, block_k=None):
     """Prefill (position 0) of tx [B, S, d] (bf16, GPU) through the layer's operators.
     w / tw: the layer's weights on the host / the GPU.  The oracle checks sequence `seq`, rows
-    `rows` (a list, or None for all).  Returns {stage: (strict elementwise error, l2 error)}."""
+    `rows` (a list, or None for all).  block_k: the K cache forge_decoder_block wrote.
+    Returns {stage: (strict elementwise error, l2 error)}.
+
+    A bf16 layer with rotary embedding rotates q and k inside its QKV projection, before the one
+    rounding; taken apart, the projection rounds and forge_rope rounds again.  There the layer's
+    own K rows are checked against the oracle's projection + rotation of the same input (one
+    rounding: the strict bound), and the last operator's output is compared with the layer's
+    within the bf16 bound instead of bit for bit."""
     B, S, d = tx.shape
     Hq, Hkv, dh = sh.q_heads, sh.kv_heads, sh.head_dim
     T, hd, nqkv = B * S, Hq * dh, (Hq + 2 * Hkv) * dh
@@ -59,6 +66,10 @@ def layer_by_parts(F, sh, w, tw, tx, block_out, seq, rows, what):
         torch.cuda.synchronize()
         stage("rope q", q[seq][:, R], O.rope(q0, np.asarray(R), sh.rope_base))
         stage("rope k", k[seq][:, R], O.rope(k0, np.asarray(R), sh.rope_base))
+        if block_k is not None:
+            k64 = O.linear(host(y.view(B, S, d)[seq, R]), w["w_qkv"], w.get("b_qkv"))[:, hd:hd + Hkv * dh]
+            k64 = k64.reshape(len(R), Hkv, dh).transpose(1, 0, 2)
+            stage("qkv + rope in one kernel (the layer's K rows)", block_k[seq][:, R], O.rope(k64, np.asarray(R), sh.rope_base))
     # 4. fused attention
     o = new(B, S, hd)
     F.forge_attn_fused(q, k, v, o, causal=True)
@@ -96,7 +107,10 @@ def layer_by_parts(F, sh, w, tw, tx, block_out, seq, rows, what):
           O.gemm_bias_act(host(u.view(B, S, sh.d_ff)[seq, R]), w["w_down"], w.get("b_down"),
                           residual=host(h1.view(B, S, d)[seq, R])))
     assert not failures, "; ".join(failures)
-    assert torch.equal(h2.view(B, S, d), block_out), "%s: the operators one by one differ from forge_decoder_block" % what
+    if sh.use_rope:
+        check(h2.view(B, S, d)[seq, R], host(block_out[seq, R]), True, "%s: operators one by one vs the layer" % what)
+    else:
+        assert torch.equal(h2.view(B, S, d), block_out), "%s: the operators one by one differ from forge_decoder_block" % what
     print("%s, kernel by kernel on identical inputs (strict elementwise / l2): %s" %
           (what, ", ".join("%s %.2e / %.2e" % (n, e[0], e[1]) for n, e in errs.items())))
     return errs

@@ -140,7 +140,7 @@ def test_config4_llama8b_prefill_layer(F):
     ref = O.decoder_block(sh, w, x, kc, vc, pos0=0, query_rows=rows)
     e = check(out[:, rows], ref, True, "config 4 layer rows", chain=True)
     print("config4 layer: %d sampled rows, strict elementwise err %.3e" % (len(rows), e))
-    layer_by_parts(F, sh, w, tw, dev(x, True), out, 0, rows, "config 4 layer")
+    layer_by_parts(F, sh, w, tw, dev(x, True), out, 0, rows, "config 4 layer", block_k=tk)
     check(tk, kc, True, "config 4 K cache (RoPE applied)")
     check(tv, vc, True, "config 4 V cache")
     out2, _, _ = gpu_block(F, desc, dev(x, True), 0, S, sh)
