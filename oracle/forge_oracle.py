@@ -149,8 +149,11 @@ def gelu_tanh(x):
 def gelu_erf(x):
     """0.5 x (1 + erf(x / sqrt 2)): the exact form (the tanh form is the reading taken for the
     paper's "GELU"; this one is offered as the other fusion variant)."""
-    from scipy.special import erf
     x = _f64(x)
+    try:
+        from scipy.special import erf
+    except ImportError:            # the standard library's erf, element by element: slower, same values
+        erf = np.vectorize(math.erf, otypes=[np.float64])
     return 0.5 * x * (1.0 + erf(x / math.sqrt(2.0)))
 
 

@@ -276,3 +276,53 @@ def test_config2_compiled_replay_equals_the_plain_launch_list(F):
         side.synchronize()
         assert torch.equal(out, plain) and torch.equal(kc, kc0) and torch.equal(vc, vc0)
     cm.close()
+
+
+@pytest.mark.parametrize("cid", [3, 4], ids=["config3_24_layers", "config4_32_layers"])
+def test_full_stacks_are_finite_reproducible_and_equal_to_their_layers(F, cid):
+    """The whole 24- and 32-layer stacks as the benchmark launches them (forge_model_forward):
+    finite, bit-identical on a second run, and bit-identical to the same layers launched one at
+    a time through forge_decoder_block followed by the final norm (the per-layer parity above
+    then covers the stack).  Weights are drawn on the device here (7 B parameters on the host
+    would take minutes): a property test, no oracle value involved."""
+    wl = I.WORKLOADS[cid]
+    sh = wl.block
+    B, S, d = wl.batch, wl.seq, sh.d_model
+    g = torch.Generator(device="cuda").manual_seed(1000 + cid)
+    rnd = lambda shape, std: (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(torch.bfloat16)
+    ones = lambda n: torch.ones(n, device="cuda", dtype=torch.bfloat16)
+    bias = (lambda n: rnd((n,), 0.02)) if sh.has_bias else (lambda n: None)
+    shift = (lambda n: rnd((n,), 0.02)) if sh.norm == "layernorm" else (lambda n: None)
+    layers = [{"norm1_g": ones(d), "norm1_b": shift(d), "w_qkv": rnd((sh.qkv_out, d), 0.02), "b_qkv": bias(sh.qkv_out),
+               "w_o": rnd((d, sh.q_heads * sh.head_dim), 0.02), "b_o": bias(d), "norm2_g": ones(d), "norm2_b": shift(d),
+               "w_up": rnd((sh.up_out, d), 0.02), "b_up": bias(sh.up_out), "w_down": rnd((d, sh.d_ff), 0.02),
+               "b_down": bias(d)} for _ in range(wl.layers)]
+    mw = {"normf_g": ones(d), "normf_b": shift(d)}
+    descs = [F.make_block_desc(sh, w) for w in layers]
+    model = F.make_model_desc(descs, mw)                      # hidden states in, final norm out (no token table)
+    x = rnd((B, S, d), 1.0)
+    shape_kv = (wl.layers, B, sh.kv_heads, S, sh.head_dim)
+    kc = torch.zeros(shape_kv, dtype=torch.bfloat16, device="cuda"); vc = torch.zeros_like(kc)
+    out = torch.empty(B, S, d, dtype=torch.bfloat16, device="cuda")
+    ws = F.workspace(F.forge_model_workspace_bytes(model, B, S, S))
+    F.forge_model_forward(model, x, out, kc, vc, 0, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all() and torch.isfinite(kc.float()).all()
+    first, k_first = out.clone(), kc.clone()
+    kc.zero_(); vc.zero_(); out.zero_()
+    F.forge_model_forward(model, x, out, kc, vc, 0, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, first) and torch.equal(kc, k_first)
+    # layer by layer
+    h = x.clone()
+    bws = F.workspace(F.forge_decoder_block_workspace_bytes(descs[0], B, S, S))
+    k1 = torch.zeros(shape_kv[1:], dtype=torch.bfloat16, device="cuda"); v1 = torch.zeros_like(k1)
+    for l in range(wl.layers):
+        F.forge_decoder_block(descs[l], h, h, k1, v1, 0, bws)
+        if l in (0, wl.layers - 1):
+            torch.cuda.synchronize()
+            assert torch.equal(k1, kc[l])
+    y = torch.empty_like(h)
+    F.forge_residual_norm(h.view(B * S, d), None, mw["normf_g"], mw["normf_b"], None, y.view(B * S, d), sh.eps, sh.norm)
+    torch.cuda.synchronize()
+    assert torch.equal(y, first)
