@@ -38,6 +38,7 @@
 // rows per block, K split over grid.y to about one block per CU), fp32 partials, and fixed-order
 // reduce kernels that carry the epilogue (and, inside a decoder layer, RoPE or the following norm).
 // Prompt-sized M with few tiles and a long K: the tile kernel itself walks (k range, tile) items.
+#include <type_traits>
 #include "common.hpp"
 
 namespace forge {
@@ -391,22 +392,31 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
   auto issue = [&](int k0, int buf) {
     char* sa = smem + buf * STAGE;
     char* sb = sa + A_BYTES;
-    const char* xb = reinterpret_cast<const char*>(p.x) + k0 * 2;
-    const char* wb = reinterpret_cast<const char*>(p.w) + k0 * 2;
+    // uniform base + 32-bit lane offset: the offsets are pinned so that they are not turned into
+    // eight running 64-bit pointers (two registers each, live across the whole loop)
+    const char* xb = reinterpret_cast<const char*>(p.x);
+    const char* wb = reinterpret_cast<const char*>(p.w);
+    const unsigned kb = (unsigned)k0 * 2u;
 #pragma unroll
-    for (int i = 0; i < IA; ++i)
-      __builtin_amdgcn_global_load_lds((const void*)(xb + a_off[i]), (lds_void*)(sa + (i * NW + wave) * 1024), 16, 0, 0);
+    for (int i = 0; i < IA; ++i) {
+      unsigned o = a_off[i] + kb;
+      asm volatile("" : "+v"(o));
+      __builtin_amdgcn_global_load_lds((const void*)(xb + o), (lds_void*)(sa + (i * NW + wave) * 1024), 16, 0, 0);
+    }
 #pragma unroll
-    for (int i = 0; i < IB; ++i)
-      __builtin_amdgcn_global_load_lds((const void*)(wb + b_off[i]), (lds_void*)(sb + (i * NW + wave) * 1024), 16, 0, 0);
+    for (int i = 0; i < IB; ++i) {
+      unsigned o = b_off[i] + kb;
+      asm volatile("" : "+v"(o));
+      __builtin_amdgcn_global_load_lds((const void*)(wb + o), (lds_void*)(sb + (i * NW + wave) * 1024), 16, 0, 0);
+    }
   };
 
   floatx16 acc[TM][TN];
-  auto compute = [&](int buf) {
+  auto compute = [&](int buf, int ks0, int ks1) {
     const char* sa = smem + buf * STAGE;
     const char* sb = sa + A_BYTES;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
+    for (int ks = ks0; ks < ks1; ++ks) {
       bf16x8 fa[TM], fb[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -474,6 +484,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
   };
   const bool has_res = MODE == MODE_PLAIN && p.residual != nullptr;
 
+  // The two waves that share a SIMD (w and w + 4) start their copies of the next slab half a slab
+  // apart: a wave sits in the issue of its direct-to-LDS loads for several hundred cycles, and this
+  // way the other wave of the SIMD is multiplying meanwhile instead of issuing its own.
+  constexpr bool STAG = NW == 8;
+  constexpr int STAG_AT = BK / 32;
+  const bool late = STAG && __builtin_amdgcn_readfirstlane(wave) >= NW / 2;
   int tt = idx, m0, n0, kb0, nk;
   tile_origin(lo + tt, m0, n0);
   k_range(lo + tt, kb0, nk);
@@ -488,22 +504,31 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     // ---- k loop: slab kt multiplied while slab kt+1 loads and parked rows drain -----------------
-    for (int kt = 0; kt < nk; ++kt) {
-      // younger than the loads of slab kt: only the stores issued right after them
-      if (PARK && pending && kt >= 1 && kt <= STORE_ITS) __builtin_amdgcn_s_waitcnt(0x0f70 | STORES_PER_IT);
-      else if (!PARK && kt == 0 && flushed) __builtin_amdgcn_s_waitcnt(0x0f70 | (NIT & 0xf) | ((NIT >> 4) << 14));
-      else __builtin_amdgcn_s_waitcnt(0x0f70);
-      __builtin_amdgcn_s_barrier();   // slab kt is in LDS for everyone; buffer (kt+1)&1 is free
-      if (kt + 1 < nk) issue(kb0 + (kt + 1) * BK, (kt + 1) & 1);
-      __builtin_amdgcn_sched_barrier(0);   // the wait above counts on loads first, stores second
-      if (PARK && pending && kt < STORE_ITS) {
+    auto k_loop = [&](auto late_c) {
+      constexpr bool LATE = decltype(late_c)::value;
+      for (int kt = 0; kt < nk; ++kt) {
+        // younger than the loads of slab kt: only the stores issued right after them
+        if (PARK && pending && kt >= 1 && kt <= STORE_ITS) __builtin_amdgcn_s_waitcnt(0x0f70 | STORES_PER_IT);
+        else if (!PARK && kt == 0 && flushed) __builtin_amdgcn_s_waitcnt(0x0f70 | (NIT & 0xf) | ((NIT >> 4) << 14));
+        else __builtin_amdgcn_s_waitcnt(0x0f70);
+        __builtin_amdgcn_s_barrier();   // slab kt is in LDS for everyone; buffer (kt+1)&1 is free
+        if (LATE) {
+          compute(kt & 1, 0, STAG_AT);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (kt + 1 < nk) issue(kb0 + (kt + 1) * BK, (kt + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);   // the wait above counts on loads first, stores second
+        if (PARK && pending && kt < STORE_ITS) {
 #pragma unroll
-        for (int c = 0; c < STORE_ITS; ++c)
-          if (c == kt) store_parked(c * STORES_PER_IT, STORES_PER_IT);
+          for (int c = 0; c < STORE_ITS; ++c)
+            if (c == kt) store_parked(c * STORES_PER_IT, STORES_PER_IT);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        compute(kt & 1, LATE ? STAG_AT : 0, BK / 16);
       }
-      __builtin_amdgcn_sched_barrier(0);
-      compute(kt & 1);
-    }
+    };
+    if (STAG && late) k_loop(std::true_type{});
+    else k_loop(std::false_type{});
     if (PARK && pending && nk < STORE_ITS) {
 #pragma unroll
       for (int c = 0; c < STORE_ITS; ++c)
