@@ -104,12 +104,19 @@ def test_block_decode_varlen(F, sh, bf16, B):
         assert np.array_equal(gv[b][:, keep], vc[b][:, keep].astype(np.float64))
 
 
+@pytest.mark.parametrize("padded", [False, True], ids=["prompts_one_by_one", "prompts_in_one_launch"])
 @pytest.mark.parametrize("compiled", [False, True], ids=["plain", "compiled"])
-def test_generation_loop_ragged_batch(F, compiled):
+def test_generation_loop_ragged_batch(F, compiled, padded):
     """Three prompts of different lengths, then 6 tokens each (teacher-forced ids): the logits of
     step i of sequence b equal row len_b + i of one causal forward of that sequence, which is
     what the oracle computes.  The compiled variant records the decode step ONCE and replays it
-    for every step while the positions advance in device memory."""
+    for every step while the positions advance in device memory.
+
+    prompts_in_one_launch: the prompts go through ONE prefill launch, padded on the right to the
+    longest with token 0.  Under the causal mask a query at position i < len_b sees keys 0..i only,
+    so the rows of a sequence's own prompt come out as if it had run alone; the rows past len_b
+    (logits and cache) hold the padding's values, which the decode steps never read: step i writes
+    cache row len_b + i before it attends rows 0..len_b + i."""
     sh = GPT
     L, V, cap, steps = 2, 520, 64, 6
     lens = [5, 17, 24]
@@ -125,8 +132,19 @@ def test_generation_loop_ragged_batch(F, compiled):
     tids = torch.from_numpy(ids).cuda()
     kc = torch.zeros(L, B, sh.kv_heads, cap, sh.head_dim, dtype=torch.bfloat16, device="cuda"); vc = torch.zeros_like(kc)
 
+    if padded:
+        n = max(lens)
+        pids = torch.zeros(B, n, dtype=tids.dtype, device="cuda")
+        for b in range(B):
+            pids[b, :lens[b]] = tids[b, :lens[b]]
+        lg = torch.empty(B, n, V, dtype=torch.bfloat16, device="cuda")
+        ws = F.workspace(F.forge_model_workspace_bytes(model, B, n, cap))
+        F.forge_model_forward(model, pids, lg, kc, vc, 0, ws)
+        torch.cuda.synchronize()
+        for b in range(B):
+            check_drift(lg[b:b + 1, :lens[b]], refs[b][:, :lens[b]], "prompt of sequence %d (padded batch)" % b)
     # prompts: one sequence at a time into a cache of its own, copied into the batched cache
-    for b, n in enumerate(lens):
+    for b, n in enumerate([] if padded else lens):
         k1 = torch.zeros(L, 1, sh.kv_heads, cap, sh.head_dim, dtype=torch.bfloat16, device="cuda"); v1 = torch.zeros_like(k1)
         lg = torch.empty(1, n, V, dtype=torch.bfloat16, device="cuda")
         ws = F.workspace(F.forge_model_workspace_bytes(model, 1, n, cap))
