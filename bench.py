@@ -96,6 +96,10 @@ def short_kernel_name(name):
     """'void forge::(anonymous namespace)::gemm_bf16_pers_kernel<256, 256, 2, 4, 4, 0>(...)' ->
     'gemm_bf16_pers<256,256,2,4,4,0>'."""
     import re
+    m = re.match(r"_ZN5forge12_GLOBAL__N_1\d+([a-z_0-9]+?)_kernelI(.*?)E+v", name)   # not demangled by the profiler
+    if m:
+        a = m.group(2).replace("DF16b", "bf16,").replace("Li", "").replace("Lb", "").replace("E", ",").strip(",")
+        return "%s<%s>" % (m.group(1), a)
     m = re.search(r"(\w+?)_kernel<([^>]*)>", name)
     if m:
         return "%s<%s>" % (m.group(1), m.group(2).replace(" ", ""))
@@ -122,10 +126,9 @@ def summarize_traffic(fetch_csv, write_csv):
         return out
 
     fetch, write = per_kernel(fetch_csv, "FETCH_SIZE"), per_kernel(write_csv, "WRITE_SIZE")
-    copy = [k for k in fetch if "copy" in k.lower()]
-    if not copy:
+    ck = "__amd_rocclr_copyBuffer"     # what a device-to-device tensor copy of raw bytes runs
+    if ck not in fetch or ck not in write:
         raise SystemExit("no copy kernel found in %s" % fetch_csv)
-    ck = max(copy, key=lambda k: max(fetch[k]))
     # skip the first launch of every kernel (cold caches, first-touch)
     mean = lambda v: sum(v[1:]) / max(1, len(v) - 1) if len(v) > 1 else v[0]
     # the runtime's copy kernel also serves small transfers: keep the probe's large copies only
