@@ -177,10 +177,7 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   floatx16 s_cur[2], s_nxt[2];
   auto scores = [&](int t, floatx16 (&s_acc)[2]) {
     const char* sk = kbuf + (t & 1) * K_BYTES;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) s_acc[kb][e] = 0.f;
+    // (the first MFMA of each key block takes a zero accumulator as an inline constant)
     // K fragments run LA MFMAs ahead of their use so that no MFMA waits on an LDS read
     constexpr int NF = 2 * NKS, LA = 4;
     bf16x8 kf[LA];
@@ -193,7 +190,8 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
       __builtin_amdgcn_sched_barrier(0);
-      s_acc[i / NKS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % LA], qf[i % NKS], s_acc[i / NKS], 0, 0, 0);
+      const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      s_acc[i / NKS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % LA], qf[i % NKS], i % NKS == 0 ? zero : s_acc[i / NKS], 0, 0, 0);
       if (i + LA < NF) kf[i % LA] = kread(i + LA);
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -308,23 +306,26 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   if (wave_needs(0)) scores(0, s_cur);
   __syncthreads();                     // K(0) is dead from here on: its buffer takes K(2)
 
-  for (int t = 0; t < n_tiles; ++t) {
+  // one tile step; the two score accumulator sets swap roles from step to step (no copies)
+  auto tile_step = [&](int t, floatx16 (&s_c)[2], floatx16 (&s_n)[2]) {
     // LDS now: K(t+1) in K buffer (t+1)&1, V(t) in V buffer t&1; K buffer t&1 and V buffer (t+1)&1 are free
     if (t + 2 < n_tiles) load_rows(kbase, t + 2, rk);
     if (t + 1 < n_tiles) load_rows(vbase, t + 1, rv);
     const bool cur = wave_needs(t), nxt = wave_needs(t + 1);
     if (scores_first) {
-      if (nxt) scores(t + 1, s_nxt);
-      if (cur) softmax_pv(t, s_cur);
+      if (nxt) scores(t + 1, s_n);
+      if (cur) softmax_pv(t, s_c);
     } else {
-      if (cur) softmax_pv(t, s_cur);
-      if (nxt) scores(t + 1, s_nxt);
+      if (cur) softmax_pv(t, s_c);
+      if (nxt) scores(t + 1, s_n);
     }
     if (t + 2 < n_tiles) store_k(t & 1);
     if (t + 1 < n_tiles) store_v((t + 1) & 1);
     __syncthreads();
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) s_cur[kb] = s_nxt[kb];
+  };
+  for (int t = 0; t < n_tiles; t += 2) {
+    tile_step(t, s_cur, s_nxt);
+    if (t + 1 < n_tiles) tile_step(t + 1, s_nxt, s_cur);
   }
 
   // ---- normalise and store: lane owns query my_q; registers 4g..4g+3 are 4 consecutive d -----
