@@ -777,16 +777,31 @@ __device__ inline bf16x8 cvt_i8x8_bf16(u32x2 v) {
   return r;
 }
 
-template <int BN, bool W8>
+// FACT < 0: fp32 partial sums for the split-K reduce (any number of k ranges).
+// FACT >= 0 (an activation code): ONE k range, and the block finishes its outputs itself -- weight
+// scale, bias, activation, residual, one rounding -- with the arithmetic of the reduce kernel, so
+// the result is bit-identical to partials + reduce over one range; no partial planes, no second
+// launch.  For the gated activation a block owns 64 gate rows and the 64 up rows that pair with
+// them (waves 0-1 and 2-3; the up halves cross over through LDS once the ring is dead).
+template <int BN, bool W8, int FACT>
 __global__ __launch_bounds__((WStream<BN, W8>::NWV * 64)) void gemm_bf16_wstream_kernel(GemmParams p) {
   using C = WStream<BN, W8>;
+  constexpr bool FUSE = FACT >= 0;
+  constexpr bool GATED = FACT == FORGE_ACT_SWIGLU;
+  static_assert(!FUSE || (BN == 128 && C::TMW == 2), "the fused finish is written for 4 waves of 32 x 64");
   extern __shared__ __attribute__((aligned(16))) char smem[];   // [W ring | x ring]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wn = wave % C::NG, wm0 = wave / C::NG;   // wm0: the activation half of a TMW == 1 wave
   const int fr = lane & 31, fh = lane >> 5;
-  const int M = p.M, N = p.N, K = p.K;
-  const int n0 = blockIdx.x * BN;
+  const int M = p.M, N = p.N, K = p.K;               // N: weight rows (twice the outputs when GATED)
+  const int NO = GATED ? N / 2 : N;                  // output columns
+  const int n0 = blockIdx.x * (GATED ? BN / 2 : BN); // first output column (FUSE) / weight row of the block
+  // weight row behind row r of the block's slab
+  auto w_row = [&](int r) {
+    if (GATED) return r < BN / 2 ? min(n0 + r, NO - 1) : NO + min(n0 + r - BN / 2, NO - 1);
+    return min(n0 + r, N - 1);
+  };
   const bool w_loader = wave < C::NWL;        // wave-uniform role
   const int lw = w_loader ? wave : wave - C::NWL;   // index among the loaders of a stream
 
@@ -800,7 +815,7 @@ __global__ __launch_bounds__((WStream<BN, W8>::NWV * 64)) void gemm_bf16_wstream
     const int j = i * (w_loader ? C::NWL : C::NXL) + lw;     // which 1 KB piece of the slab
     const int r = (w_loader ? j : j % 8) * 8 + (lane >> 3);
     const int c = (lane & 7) ^ ((r >> 1) & 7);
-    src[i] = w_loader ? (W8 ? (const char*)p.w8 : (const char*)p.w) + ((int64_t)min(n0 + r, N - 1) * K * WESZ + c * 16)
+    src[i] = w_loader ? (W8 ? (const char*)p.w8 : (const char*)p.w) + ((int64_t)w_row(r) * K * WESZ + c * 16)
                       : (const char*)(p.x + (int64_t)min(r, M - 1) * K + (j / 8) * BK + c * 8);
   }
   const int k_begin = blockIdx.y * p.k_per_split;
@@ -870,20 +885,77 @@ __global__ __launch_bounds__((WStream<BN, W8>::NWV * 64)) void gemm_bf16_wstream
   __builtin_amdgcn_s_waitcnt(0x0f70);   // drain the re-loads of the tail before the block ends
   __syncthreads();
 
-  // ---- partial sums: lane = row m, registers = columns (see the fast kernel's epilogue) -----------
-  const bool vec_part = (N & 3) == 0;
-#pragma unroll
-  for (int t = 0; t < C::TMW; ++t) {
-    float run[2][8];
+  // ---- lane = row m, registers = columns (see the fast kernel's epilogue) ---------------------------
+  auto runs_of = [&](const floatx16& a, float (&run)[2][8]) {
 #pragma unroll
     for (int gp = 0; gp < 2; ++gp)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        auto sw2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[t][4 * gp + r]),
-                                                    __float_as_uint(acc[t][4 * (gp + 2) + r]), false, false);
+        auto sw2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(a[4 * gp + r]),
+                                                    __float_as_uint(a[4 * (gp + 2) + r]), false, false);
         run[gp][r] = __uint_as_float(sw2[0]);
         run[gp][4 + r] = __uint_as_float(sw2[1]);
       }
+  };
+  if constexpr (FUSE) {
+    // the same steps, in the same order, as splitk_reduce_kernel takes on the sum of one k range
+    float* const xch = reinterpret_cast<float*>(smem);    // [2 wave pairs][2 halves][2 runs][64 lanes][8]
+    const bool up_wave = GATED && wn >= 2;
+    const int wcol = GATED ? (wn & 1) : wn;                // 32-column group of the block's outputs
+    float run[2][2][8];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      runs_of(acc[t], run[t]);
+#pragma unroll
+      for (int gp = 0; gp < 2; ++gp) {
+        const int n = n0 + wcol * 32 + 16 * fh + 8 * gp;   // output column of element 0
+        const int wr = up_wave ? NO + n : n;               // weight row of element 0
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (n + e >= NO) continue;
+          if (p.wscale != nullptr) run[t][gp][e] *= p.wscale[wr + e];
+          if (p.bias != nullptr) run[t][gp][e] += (float)p.bias[wr + e];
+        }
+        if (up_wave) Vec8<float>::store(xch + ((((wn & 1) * 2 + t) * 2 + gp) * 64 + lane) * 8, run[t][gp]);
+      }
+    }
+    if (GATED) __syncthreads();
+    if (!up_wave) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int m = t * 32 + fr;
+        if (m >= M) continue;
+#pragma unroll
+        for (int gp = 0; gp < 2; ++gp) {
+          const int n = n0 + wcol * 32 + 16 * fh + 8 * gp;
+          if (n >= NO) continue;
+          float uv[8], o[8];
+          if (GATED) Vec8<float>::load(xch + (((wcol * 2 + t) * 2 + gp) * 64 + lane) * 8, uv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = GATED ? silu_f(run[t][gp][e]) * uv[e] : apply_act<FACT>(run[t][gp][e]);
+          bf16* dst = p.y + (int64_t)m * p.ldy + n;
+          const bf16* res = p.residual != nullptr ? p.residual + (int64_t)m * p.ldy + n : nullptr;
+          if (n + 8 <= NO && (p.ldy & 7) == 0) {
+            if (res != nullptr) {
+              float rr[8];
+              Vec8<bf16>::load(res, rr);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) o[e] += rr[e];
+            }
+            Vec8<bf16>::store(dst, o);
+          } else {
+            for (int e = 0; e < 8 && n + e < NO; ++e) dst[e] = (bf16)(o[e] + (res != nullptr ? (float)res[e] : 0.f));
+          }
+        }
+      }
+    }
+    return;
+  }
+  const bool vec_part = (N & 3) == 0;
+#pragma unroll
+  for (int t = 0; t < C::TMW; ++t) {
+    float run[2][8];
+    runs_of(acc[t], run);
     const int m = (C::TMW == 2 ? t : wm0) * 32 + fr;
     if (m >= M) continue;
 #pragma unroll
@@ -1162,12 +1234,26 @@ struct SkinnyPlan {
   int bn;           // weight rows per block of the streaming kernel
   int splits;
   int k_per_split;
+  bool fused;       // one k range of 128-row blocks: a plain output can be finished inside the GEMM
 };
 inline SkinnyPlan plan_skinny(int N, int K, forge_act act, int bk = BK) {
   SkinnyPlan sp;
   sp.ncols = act == FORGE_ACT_SWIGLU ? 2 * N : N;
+  sp.fused = false;
   const int slabs = ceil_div(K, bk);
   const int cus = compute_units();
+  // Enough weight rows for 128-row blocks to cover three quarters of the chip with ONE k range
+  // (8B gate + up: 224 blocks; an LM head): no partial planes and no second launch, and measured
+  // faster than two k ranges of 256-row blocks even before the reduce is counted (51 vs 55 us for
+  // the 8B gate + up at 64 rows).  bf16 weights only: with int8 weights the activation re-reads of
+  // a 128-row block are as large as its weight stream.
+  if (bk == BK && ceil_div(sp.ncols, 128) * 4 >= cus * 3) {
+    sp.bn = 128;
+    sp.splits = 1;
+    sp.k_per_split = slabs * bk;
+    sp.fused = true;
+    return sp;
+  }
   // About one block per CU measured best on the decode shapes: more blocks mean more k ranges,
   // i.e. more partial-sum traffic and a longer reduce.  256-row blocks (fewest activation re-reads
   // per weight byte) when two k ranges of them already cover the chip, 128-row blocks otherwise.
@@ -1181,12 +1267,13 @@ inline SkinnyPlan plan_skinny(int N, int K, forge_act act, int bk = BK) {
   return sp;
 }
 
-template <int BN, bool W8>
+template <int BN, bool W8, int FACT = -1>
 forge_status launch_wstream(const GemmParams& q, int splits, hipStream_t s) {
   using C = WStream<BN, W8>;
-  auto kern = gemm_bf16_wstream_kernel<BN, W8>;
+  auto kern = gemm_bf16_wstream_kernel<BN, W8, FACT>;
   static std::atomic<uint64_t> lds_raised{0};   // per kernel instantiation
   if (raise_lds_limit(reinterpret_cast<const void*>(kern), C::SMEM, lds_raised) != FORGE_OK) return FORGE_ERR_HIP;
+  // (a block of the gated fused finish covers BN / 2 outputs = BN weight rows: the same count)
   kern<<<dim3(ceil_div(q.N, BN), splits), C::NWV * 64, C::SMEM, s>>>(q);
   return launch_status();
 }
@@ -1259,6 +1346,8 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
   q.N = sk.ncols;
   q.k_per_split = sk.k_per_split;
   forge_status st;
+  if (v == V_SKINNY_FAST && sk.fused && q.w8 == nullptr && MODE == MODE_PLAIN && p.nt.y_norm == nullptr)
+    return launch_wstream<128, false, ACT>(q, 1, s);     // finishes its outputs itself
   if (v == V_SKINNY_FAST) {
     if (q.w8 != nullptr) st = sk.bn == 256 ? launch_wstream<256, true>(q, sk.splits, s) : launch_wstream<128, true>(q, sk.splits, s);
     else st = sk.bn == 256 ? launch_wstream<256, false>(q, sk.splits, s) : launch_wstream<128, false>(q, sk.splits, s);
@@ -1343,7 +1432,7 @@ const char* gemm_bf16_variant(int M, int N, int K, int ldy, forge_act act) {
     case V_FAST_128: return act == FORGE_ACT_SWIGLU ? "gemm_bf16_pers<128,128,2,2>" : "gemm_bf16_pers<128,128,2,4>";
     case V_GEN_256: return "gemm_bf16_generic<256,256,2,4>";
     case V_GEN_128: return "gemm_bf16_generic<128,128,2,2>";
-    case V_SKINNY_FAST: return "gemm_bf16_wstream+splitk";
+    case V_SKINNY_FAST: return plan_skinny(N, K, act).fused ? "gemm_bf16_wstream_fused<128>" : "gemm_bf16_wstream+splitk";
     default: return "gemm_bf16_generic<64,64,2,2>+splitk";
   }
 }

@@ -152,6 +152,42 @@ def test_gemm_many_tiles_per_block(F, M, N, K, act, use_b, use_r, ld):
     assert torch.equal(again, ty)
 
 
+@pytest.mark.parametrize("M,N,K,act,use_b,use_r,ld", [
+    (64, 24576, 256, "none", True, True, 0),           # 192 blocks of 128 weight rows: the smallest fused case
+    (64, 24576, 192, "gelu_tanh", True, False, 0),
+    (33, 24578, 128, "silu", False, True, 24584),      # ragged last chunk, padded row stride, fewer than 64 rows
+    (1, 30000, 64, "relu", True, False, 0),            # a single row, a single slab
+    (64, 12288, 256, "swiglu", True, False, 0),        # gated: 64 gate rows + their 64 up rows per block
+    (40, 12296, 128, "swiglu", False, False, 0),       # gated, outputs not a multiple of 64
+    (17, 50257, 128, "none", False, False, 50264),     # an LM head at decode size
+    (64, 24576, 128, "gelu_erf", True, True, 0),
+])
+def test_gemm_decode_sized_finishes_in_the_gemm(F, M, N, K, act, use_b, use_r, ld):
+    """At most 64 rows against enough weight rows for one k range of 128-row blocks to cover the
+    chip: the weight-streaming kernel applies bias, activation and residual itself (no partial
+    planes, no reduce launch).  Poisoned workspace: the fused path must not depend on it."""
+    wn = 2 * N if act == "swiglu" else N
+    ldy = ld or N
+    x = I.normal(69, 0, "x", (M, K), 1.0, bf16=True)
+    w = I.normal(69, 0, "w_up", (wn, K), 1.0 / math.sqrt(K), bf16=True)
+    b = I.normal(69, 0, "b_up", (wn,), 0.5, bf16=True) if use_b else None
+    r = I.normal(69, 0, "residual", (M, ldy), 1.0, bf16=True) if use_r else None
+    ref = O.gemm_bias_act(x, w, b, None if r is None else r[:, :N], act)
+    assert F.forge_gemm_variant(M, N, K, act, torch.bfloat16, ldy=ldy) == "gemm_bf16_wstream_fused<128>"
+    ws = F.workspace(F.forge_gemm_workspace_bytes(M, N, K, act, torch.bfloat16))
+    ws.view(torch.float32).fill_(float("nan"))
+    ty = torch.full((M, ldy), 7.0, dtype=torch.bfloat16, device="cuda")
+    args = (dev(x, True), dev(w, True), None if b is None else dev(b, True), None if r is None else dev(r, True))
+    F.forge_gemm_bias_gelu(*args, ty, act, ws, n=N)
+    torch.cuda.synchronize()
+    check(ty[:, :N], ref, True, "fused decode gemm %s" % act)
+    assert torch.all(ty[:, N:] == 7.0)
+    again = torch.full((M, ldy), 7.0, dtype=torch.bfloat16, device="cuda")
+    F.forge_gemm_bias_gelu(*args, again, act, ws, n=N)
+    torch.cuda.synchronize()
+    assert torch.equal(again, ty)
+
+
 @pytest.mark.parametrize("M,N,K,act", [
     (128, 512, 2048, "none"), (130, 520, 4096, "gelu_tanh"), (257, 256, 14336, "none"),
     (100, 384, 2048, "swiglu"), (512, 128, 8192, "silu"),
