@@ -97,10 +97,12 @@ __device__ inline float wave_max(float v) {
 // tanh-GELU written through the logistic form: 0.5 x (1 + tanh u) = x / (1 + exp(-2u)),
 // u = sqrt(2/pi) (x + 0.044715 x^3).
 __device__ inline float gelu_tanh_f(float x) {
-  const float k0 = 0.7978845608028654f, k1 = 0.044715f;
-  float u = k0 * (x + k1 * x * x * x);
+  // exp(-2u) = exp2(x (a + b x^2)) with a = -2 sqrt(2/pi) log2(e), b = 0.044715 a: three
+  // multiply-adds in front of the two transcendentals (v_exp_f32, v_rcp_f32)
+  const float a = -2.302208198f, b = -0.1029432397f;
+  const float e = __builtin_amdgcn_exp2f(x * __builtin_fmaf(x * x, b, a));
   // x * sigmoid(2u); hardware reciprocal (1 ulp) instead of an IEEE division
-  return x * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
+  return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
 __device__ inline float silu_f(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 __device__ inline float gelu_erf_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.7071067811865476f)); }
