@@ -79,8 +79,10 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   constexpr int KS = DH * 2 + 16;             // K row stride in LDS (bytes)
   constexpr int VS = DH * 2 + 64;             // V row stride in LDS (bytes)
   constexpr int K_BYTES = BKV * KS, V_BYTES = BKV * VS;
-  constexpr int NLOAD = 256;                  // threads that move tiles: waves 0-3 (see below)
-  constexpr int LPT = BKV * CPR / NLOAD;      // chunks per loading thread per tensor per tile
+  // chunks per thread, tensor and tile: the early waves (whose loads issue while no MFMA runs on
+  // their SIMD) move three quarters of a tile at head_dim 128 and all of it at 64
+  constexpr int LPT = BKV * CPR / 256 - (DH == 128 ? 1 : 0);      // early waves
+  constexpr int LPT_LATE = BKV * CPR / 256 - LPT;                  // late waves
   constexpr int NKS = DH / 16;                // MFMA k-steps over dh
   constexpr int NDT = DH / 32;                // 32-row tiles of O^T
   extern __shared__ __attribute__((aligned(16))) char smem[];   // [K0 | K1 | V0 | V1]
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   const int g = h / (p.q_heads / p.kv_heads);
   const int q0 = qb * BQ, q0w = q0 + wave * 32;
   const int off = p.kv_len - p.q_len;
-  const bool scores_first = wave < 4;         // the two waves of a SIMD alternate (see above)
+  const bool late = wave >= 4;                // the second wave of each SIMD runs half a tile behind (see above)
 
   const bf16* kbase = p.k + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
   const bf16* vbase = p.v + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
@@ -123,38 +125,33 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   const int wave_max_limit = p.causal ? min(q0w + 31, p.q_len - 1) + off : p.kv_len - 1;
   const int wave_min_limit = p.causal ? q0w + off : p.kv_len - 1;
 
-  // ---- global -> registers -> LDS copy plan ----------------------------------------------------
-  // Only waves 0-3 move tiles: their phase order leaves them ~2000 cycles of slack at the barrier
-  // of every tile, while waves 4-7 are the critical path (measured), so the copies cost nothing
-  // there and shorten the slow group.
-  const bool loader = scores_first;
+  // ---- global -> registers -> LDS copy plan: every wave moves an eighth of a tile -----------------
+  const int my_lpt = late ? LPT_LATE : LPT;   // wave-uniform
   int ld_row[LPT], ld_c[LPT];
 #pragma unroll
   for (int i = 0; i < LPT; ++i) {
-    const int idx = (tid & (NLOAD - 1)) + i * NLOAD;
+    const int idx = late ? 256 * LPT + (tid - 256) : tid + i * 256;
     ld_row[i] = idx / CPR;
     ld_c[i] = idx % CPR;
   }
   u32x4 rk[LPT], rv[LPT];
   auto load_rows = [&](const bf16* base, int t, u32x4 (&r)[LPT]) {
-    if (!loader) return;
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
+      if (i >= my_lpt) break;
       const int key = min(t * BKV + ld_row[i], p.kv_len - 1);   // rows past the end re-read the last key
       r[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)key * DH + ld_c[i] * 8);
     }
   };
   auto store_k = [&](int buf) {
-    if (!loader) return;
 #pragma unroll
     for (int i = 0; i < LPT; ++i)
-      *reinterpret_cast<u32x4*>(kbuf + buf * K_BYTES + ld_row[i] * KS + ld_c[i] * 16) = rk[i];
+      if (i < my_lpt) *reinterpret_cast<u32x4*>(kbuf + buf * K_BYTES + ld_row[i] * KS + ld_c[i] * 16) = rk[i];
   };
   auto store_v = [&](int buf) {
-    if (!loader) return;
 #pragma unroll
     for (int i = 0; i < LPT; ++i)
-      *reinterpret_cast<u32x4*>(vbuf + buf * V_BYTES + ld_row[i] * VS + ld_c[i] * 16) = rv[i];
+      if (i < my_lpt) *reinterpret_cast<u32x4*>(vbuf + buf * V_BYTES + ld_row[i] * VS + ld_c[i] * 16) = rv[i];
   };
 
   floatx16 o_acc[NDT];
@@ -173,9 +170,10 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   // per-lane byte offset of the transposing V read inside a tile (without key step / d tile)
   const int vt_lane = (((lane & 15) >> 2) + 4 * fh) * VS + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
 
-  // ---- S^T = K . Q^T of one tile ---------------------------------------------------------------
-  floatx16 s_cur[2], s_nxt[2];
-  auto scores = [&](int t, floatx16 (&s_acc)[2]) {
+  // ---- matrix phase, part 2: S^T = K . Q^T of one tile ---------------------------------------------
+  floatx16 sc[2];                  // the scores of the tile in flight, then its probabilities
+  bf16x8 pf[4];                    // P^T of the tile whose vector phase has run: B operand of P.V
+  auto scores = [&](int t) {
     const char* sk = kbuf + (t & 1) * K_BYTES;
     // (the first MFMA of each key block takes a zero accumulator as an inline constant)
     // K fragments run LA MFMAs ahead of their use so that no MFMA waits on an LDS read
@@ -191,16 +189,15 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
     for (int i = 0; i < NF; ++i) {
       __builtin_amdgcn_sched_barrier(0);
       const floatx16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      s_acc[i / NKS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % LA], qf[i % NKS], i % NKS == 0 ? zero : s_acc[i / NKS], 0, 0, 0);
+      sc[i / NKS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % LA], qf[i % NKS], i % NKS == 0 ? zero : sc[i / NKS], 0, 0, 0);
       if (i + LA < NF) kf[i % LA] = kread(i + LA);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
 
-  // ---- mask, online softmax and O^T += V^T . P^T of one tile ---------------------------------------
-  auto softmax_pv = [&](int t, floatx16 (&s_acc)[2]) {
+  // ---- vector phase: mask, online softmax, P rounded to bf16 (no matrix instruction) ----------------
+  auto softmax = [&](int t) {
     const int kv0 = t * BKV;
-    const char* sv = vbuf + (t & 1) * V_BYTES;
     if (MASKED) {
       constexpr float LOG2E = 1.4426950408889634f;
 #pragma unroll
@@ -209,7 +206,7 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
         for (int v = 0; v < 16; ++v) {
           const int key = kv0 + kb * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
           const float mk = key < p.kv_len ? mask_row[key] : 0.f;      // keys past the end are cut below
-          s_acc[kb][v] = s_acc[kb][v] * p.scale_log2e + mk * LOG2E;
+          sc[kb][v] = sc[kb][v] * p.scale_log2e + mk * LOG2E;
         }
     }
     if (kv0 + BKV - 1 > wave_min_limit) {       // diagonal / tail tiles only
@@ -218,14 +215,14 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int key = kv0 + kb * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
-          if (key > my_limit) s_acc[kb][v] = -INFINITY;
+          if (key > my_limit) sc[kb][v] = -INFINITY;
         }
     }
-    float mx = s_acc[0][0];
+    float mx = sc[0][0];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s_acc[kb][v]);
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc[kb][v]);
     mx = xchg32_max(mx);
     const float m_new = fmaxf(m_run, mx);
     if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {   // wave-uniform: some maximum moved
@@ -239,22 +236,27 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
     }
     const float mc = m_run * c;
     float psum = 0.f;
-    // first 32 keys of the tile now; the exponentials of the other 32 fill the shadow of the first
-    // half of the P.V MFMAs (in-order issue: only vector work placed between them can overlap them)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const float pv = __builtin_amdgcn_exp2f(s_acc[0][v] * c - mc);
-      s_acc[0][v] = pv;
-      psum += pv;
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float pv = __builtin_amdgcn_exp2f(sc[kb][v] * c - mc);
+        sc[kb][v] = pv;
+        psum += pv;
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[2 * kb + s2][e] = (bf16)sc[kb][8 * s2 + e];
     }
-    bf16x8 pf[4];
-#pragma unroll
-    for (int s = 0; s < 2; ++s)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) pf[s][e] = (bf16)s_acc[0][8 * s + e];
+    l_run += psum;
+  };
+
+  // ---- matrix phase, part 1: O^T += V^T . P^T --------------------------------------------------------
+  auto pv_mm = [&](int t) {
+    const char* sv = vbuf + (t & 1) * V_BYTES;
     // V^T fragments (two transposing reads each) run LA MFMAs ahead of their use
     constexpr int NF = 4 * NDT, LA = 4;
-    constexpr int EPI = 16 / (NF / 2);          // exponentials per MFMA of the first half
     typedef short v8i16 __attribute__((ext_vector_type(8)));
     v4i16 lo[LA], hi[LA];
     auto vread = [&](int i, v4i16& l, v4i16& hh) {
@@ -272,24 +274,8 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
       v8i16 both = {l[0], l[1], l[2], l[3], hh[0], hh[1], hh[2], hh[3]};
       o_acc[i % NDT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[i / NDT], o_acc[i % NDT], 0, 0, 0);
       if (i + LA < NF) vread(i + LA, lo[i % LA], hi[i % LA]);
-      if (i < NF / 2) {
-#pragma unroll
-        for (int e = 0; e < EPI; ++e) {
-          const int v = i * EPI + e;
-          const float pv = __builtin_amdgcn_exp2f(s_acc[1][v] * c - mc);
-          s_acc[1][v] = pv;
-          psum += pv;
-        }
-      }
-      if (i == NF / 2 - 1) {
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) pf[2 + s2][e] = (bf16)s_acc[1][8 * s2 + e];
-      }
     }
     __builtin_amdgcn_sched_barrier(0);
-    l_run += psum;
   };
   auto wave_needs = [&](int t) { return t < n_tiles && t * BKV <= wave_max_limit; };   // wave-uniform
 
@@ -303,29 +289,48 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
     store_k(1);
   }
   __syncthreads();
-  if (wave_needs(0)) scores(0, s_cur);
+  if (wave_needs(0)) scores(0);
   __syncthreads();                     // K(0) is dead from here on: its buffer takes K(2)
 
-  // one tile step; the two score accumulator sets swap roles from step to step (no copies)
-  auto tile_step = [&](int t, floatx16 (&s_c)[2], floatx16 (&s_n)[2]) {
-    // LDS now: K(t+1) in K buffer (t+1)&1, V(t) in V buffer t&1; K buffer t&1 and V buffer (t+1)&1 are free
+  // Steps of half a tile, a block barrier after each.  Copy job t (K(t+2) into K buffer t&1, V(t+1)
+  // into V buffer (t+1)&1) may run once step 2t has ended (the late waves' matrix phase of tile t-1
+  // was the last reader of both buffers) and must have ended before step 2t+3 (the early waves'
+  // matrix phase of tile t+1): the early waves load their share in step 2t+1 and store it in step
+  // 2t+2, the late waves do both in step 2t+2, around their matrix phase.
+  //   step 2t   : early waves  softmax(t), stores of job t-1      late waves  loads of job t-1, P.V(t-1), S(t), stores of job t-1
+  //   step 2t+1 : early waves  loads of job t, P.V(t), S(t+1)     late waves  softmax(t)
+  auto job_load = [&](int t) {
     if (t + 2 < n_tiles) load_rows(kbase, t + 2, rk);
     if (t + 1 < n_tiles) load_rows(vbase, t + 1, rv);
-    const bool cur = wave_needs(t), nxt = wave_needs(t + 1);
-    if (scores_first) {
-      if (nxt) scores(t + 1, s_n);
-      if (cur) softmax_pv(t, s_c);
-    } else {
-      if (cur) softmax_pv(t, s_c);
-      if (nxt) scores(t + 1, s_n);
-    }
+  };
+  auto job_store = [&](int t) {
     if (t + 2 < n_tiles) store_k(t & 1);
     if (t + 1 < n_tiles) store_v((t + 1) & 1);
-    __syncthreads();
   };
-  for (int t = 0; t < n_tiles; t += 2) {
-    tile_step(t, s_cur, s_nxt);
-    if (t + 1 < n_tiles) tile_step(t + 1, s_nxt, s_cur);
+  auto matrix_phase = [&](int t) {
+    if (wave_needs(t)) pv_mm(t);
+    if (wave_needs(t + 1)) scores(t + 1);
+  };
+  if (!late) {
+    for (int t = 0; t < n_tiles; ++t) {
+      if (wave_needs(t)) softmax(t);
+      if (t >= 1) job_store(t - 1);
+      __syncthreads();
+      job_load(t);
+      matrix_phase(t);
+      __syncthreads();
+    }
+    __syncthreads();                   // the late waves' last step
+  } else {
+    __syncthreads();                   // the early waves' first step
+    for (int t = 0; t < n_tiles; ++t) {
+      if (wave_needs(t)) softmax(t);
+      __syncthreads();
+      job_load(t);                     // both inside step 2t+2: loads issue cheaply only while the
+      matrix_phase(t);                 // SIMD's other wave is not multiplying
+      job_store(t);
+      __syncthreads();
+    }
   }
 
   // ---- normalise and store: lane owns query my_q; registers 4g..4g+3 are 4 consecutive d -----
