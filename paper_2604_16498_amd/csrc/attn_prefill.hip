@@ -23,20 +23,21 @@
 // on both operands, so the sum is unchanged): element e of lane-half h is key
 // 16 s + 8 (e / 4) + 4 h + e % 4, which is what the S^T accumulator registers 8 (s % 2) + e hold.
 //
-// Pipeline: the softmax of a tile is ~1200 cycles of vector ALU work per wave against ~1000
-// cycles of MFMA, and within one wave the two cannot overlap (in-order issue).  So the scores
-// run ONE TILE AHEAD of softmax and P.V: S(t+1) does not depend on tile t, and the two waves
-// that share a SIMD (wave w and w+4) take the three steps in different orders --
-//   waves 0-3:  S(t+1) -> softmax(t) -> P.V(t)        waves 4-7:  softmax(t) -> P.V(t) -> S(t+1)
-// -- so that one is on the matrix core while the other is on the vector ALU, although the block
-// barrier per tile puts them back in step every time.  K is therefore fetched two tiles ahead
-// and V one tile ahead; since K(t) is dead once S(t) exists, two LDS buffers each still suffice.
+// Pipeline: per wave and tile of 64 keys the softmax is ~1000 cycles of vector ALU work and the two
+// contractions ~1100 cycles of MFMA, and a wave issues in order.  The matrix pipe and the vector ALU
+// of a SIMD do overlap when they are fed by two DIFFERENT waves (measured: the MFMA stream keeps its
+// pace, the vector stream loses about a quarter), so the work of a tile is cut into a pure vector
+// phase (mask, maximum, rescale, all exponentials, rounding of P) and a pure matrix phase
+// (P.V of that tile, then S of the next one), and the two waves that share a SIMD (w and w+4) run
+// the same sequence HALF A TILE APART: while one is in its vector phase the other is in its matrix
+// phase.  A block barrier ends every half tile.  Only one set of score registers is alive per wave.
 //
 // LDS: K tile rows padded by 16 B and V tile rows by 64 B so that the row reads (K) and the
-// 4-rows-by-64-B transposing reads (V) of a half wave fall on disjoint banks.  Tiles go
-// HBM -> registers -> LDS: the loads are issued before the tile's arithmetic, the LDS stores
-// after it.  (Direct-to-LDS loads were measured slower here: issuing them costs more than the
-// staging they save, with only 32 MFMAs per wave and tile to hide it.)
+// 4-rows-by-64-B transposing reads (V) of a half wave fall on disjoint banks; two buffers each.
+// Tiles go HBM -> registers -> LDS, moved by the early waves (0-3): the loads of K(t+1) are issued
+// before the softmax of tile t and stored after it, those of V(t+1) before and after the matrix
+// phase of tile t.  (The same loads issue two to four times slower from waves 4-7, and
+// direct-to-LDS loads were measured slower still: +15 %.)
 #include "common.hpp"
 
 namespace forge {
@@ -79,10 +80,9 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   constexpr int KS = DH * 2 + 16;             // K row stride in LDS (bytes)
   constexpr int VS = DH * 2 + 64;             // V row stride in LDS (bytes)
   constexpr int K_BYTES = BKV * KS, V_BYTES = BKV * VS;
-  // chunks per thread, tensor and tile: the early waves (whose loads issue while no MFMA runs on
-  // their SIMD) move three quarters of a tile at head_dim 128 and all of it at 64
-  constexpr int LPT = BKV * CPR / 256 - (DH == 128 ? 1 : 0);      // early waves
-  constexpr int LPT_LATE = BKV * CPR / 256 - LPT;                  // late waves
+  // chunks per thread, tensor and tile: the early waves move the tiles (measured: the same loads
+  // issue two to four times slower from the second wave of a SIMD)
+  constexpr int LPT = BKV * CPR / 256;        // per thread of the early waves; the late waves copy nothing
   constexpr int NKS = DH / 16;                // MFMA k-steps over dh
   constexpr int NDT = DH / 32;                // 32-row tiles of O^T
   extern __shared__ __attribute__((aligned(16))) char smem[];   // [K0 | K1 | V0 | V1]
@@ -125,33 +125,34 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   const int wave_max_limit = p.causal ? min(q0w + 31, p.q_len - 1) + off : p.kv_len - 1;
   const int wave_min_limit = p.causal ? q0w + off : p.kv_len - 1;
 
-  // ---- global -> registers -> LDS copy plan: every wave moves an eighth of a tile -----------------
-  const int my_lpt = late ? LPT_LATE : LPT;   // wave-uniform
+  // ---- global -> registers -> LDS copy plan: each early wave moves a quarter of a tile -------------
   int ld_row[LPT], ld_c[LPT];
 #pragma unroll
   for (int i = 0; i < LPT; ++i) {
-    const int idx = late ? 256 * LPT + (tid - 256) : tid + i * 256;
+    const int idx = (tid & 255) + i * 256;
     ld_row[i] = idx / CPR;
     ld_c[i] = idx % CPR;
   }
   u32x4 rk[LPT], rv[LPT];
   auto load_rows = [&](const bf16* base, int t, u32x4 (&r)[LPT]) {
+    if (late) return;
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
-      if (i >= my_lpt) break;
       const int key = min(t * BKV + ld_row[i], p.kv_len - 1);   // rows past the end re-read the last key
       r[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)key * DH + ld_c[i] * 8);
     }
   };
   auto store_k = [&](int buf) {
+    if (late) return;
 #pragma unroll
     for (int i = 0; i < LPT; ++i)
-      if (i < my_lpt) *reinterpret_cast<u32x4*>(kbuf + buf * K_BYTES + ld_row[i] * KS + ld_c[i] * 16) = rk[i];
+      *reinterpret_cast<u32x4*>(kbuf + buf * K_BYTES + ld_row[i] * KS + ld_c[i] * 16) = rk[i];
   };
   auto store_v = [&](int buf) {
+    if (late) return;
 #pragma unroll
     for (int i = 0; i < LPT; ++i)
-      if (i < my_lpt) *reinterpret_cast<u32x4*>(vbuf + buf * V_BYTES + ld_row[i] * VS + ld_c[i] * 16) = rv[i];
+      *reinterpret_cast<u32x4*>(vbuf + buf * V_BYTES + ld_row[i] * VS + ld_c[i] * 16) = rv[i];
   };
 
   floatx16 o_acc[NDT];
@@ -284,40 +285,30 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   load_rows(vbase, 0, rv);
   store_k(0);
   store_v(0);
-  if (n_tiles > 1) {
-    load_rows(kbase, 1, rk);
-    store_k(1);
-  }
   __syncthreads();
   if (wave_needs(0)) scores(0);
-  __syncthreads();                     // K(0) is dead from here on: its buffer takes K(2)
+  __syncthreads();
 
-  // Steps of half a tile, a block barrier after each.  Copy job t (K(t+2) into K buffer t&1, V(t+1)
-  // into V buffer (t+1)&1) may run once step 2t has ended (the late waves' matrix phase of tile t-1
-  // was the last reader of both buffers) and must have ended before step 2t+3 (the early waves'
-  // matrix phase of tile t+1): the early waves load their share in step 2t+1 and store it in step
-  // 2t+2, the late waves do both in step 2t+2, around their matrix phase.
-  //   step 2t   : early waves  softmax(t), stores of job t-1      late waves  loads of job t-1, P.V(t-1), S(t), stores of job t-1
-  //   step 2t+1 : early waves  loads of job t, P.V(t), S(t+1)     late waves  softmax(t)
-  auto job_load = [&](int t) {
-    if (t + 2 < n_tiles) load_rows(kbase, t + 2, rk);
-    if (t + 1 < n_tiles) load_rows(vbase, t + 1, rv);
-  };
-  auto job_store = [&](int t) {
-    if (t + 2 < n_tiles) store_k(t & 1);
-    if (t + 1 < n_tiles) store_v((t + 1) & 1);
-  };
+  // Steps of half a tile, a block barrier after each; the late waves run one step behind:
+  //   step 2t   : early waves  softmax(t), copy of K(t+1)           late waves  P.V(t-1), S(t)
+  //   step 2t+1 : early waves  P.V(t), S(t+1), copy of V(t+1)      late waves  softmax(t)
+  // K(t+1) goes into K buffer (t+1)&1, whose last reader was the late waves' S(t-1) in step 2t-2, and
+  // is first read by the early waves' S(t+1) in step 2t+1.  V(t+1) goes into V buffer (t+1)&1, last
+  // read by the late waves' P.V(t-1) in step 2t, first read by the early waves' P.V(t+1) in step 2t+3.
   auto matrix_phase = [&](int t) {
     if (wave_needs(t)) pv_mm(t);
     if (wave_needs(t + 1)) scores(t + 1);
   };
   if (!late) {
     for (int t = 0; t < n_tiles; ++t) {
+      // step 2t: K(t+1) travels behind the softmax; step 2t+1: V(t+1) behind the MFMAs
+      if (t + 1 < n_tiles) load_rows(kbase, t + 1, rk);
       if (wave_needs(t)) softmax(t);
-      if (t >= 1) job_store(t - 1);
+      if (t + 1 < n_tiles) store_k((t + 1) & 1);
       __syncthreads();
-      job_load(t);
+      if (t + 1 < n_tiles) load_rows(vbase, t + 1, rv);
       matrix_phase(t);
+      if (t + 1 < n_tiles) store_v((t + 1) & 1);
       __syncthreads();
     }
     __syncthreads();                   // the late waves' last step
@@ -326,9 +317,7 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
     for (int t = 0; t < n_tiles; ++t) {
       if (wave_needs(t)) softmax(t);
       __syncthreads();
-      job_load(t);                     // both inside step 2t+2: loads issue cheaply only while the
-      matrix_phase(t);                 // SIMD's other wave is not multiplying
-      job_store(t);
+      matrix_phase(t);
       __syncthreads();
     }
   }
