@@ -132,7 +132,9 @@ forge_status forge_attn_fused_masked(const void* q, const void* k, const void* v
  * keep fp32 partial sums in forge_gemm_workspace_bytes() bytes of device memory (0 when the
  * problem is not split); the partial sums are added in a fixed order, so results stay bitwise
  * reproducible.  bf16 problems with M <= 64 (a decode step) cannot run without it
- * (FORGE_ERR_WORKSPACE); all others run unsplit, slower, when less is given.
+ * (FORGE_ERR_WORKSPACE) unless the size function returns 0 for them (enough weight rows for one
+ * k range to fill the chip: such a problem is finished inside the streaming kernel); all others
+ * run unsplit, slower, when less is given.
  * ------------------------------------------------------------------------------------ */
 size_t forge_gemm_workspace_bytes(int M, int N, int K, forge_act act, forge_dtype dt);
 

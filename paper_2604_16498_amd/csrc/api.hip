@@ -50,7 +50,7 @@ BlockPlan plan_block(const forge_block_desc* d, int batch, int q_len, int kv_cap
   size_t g = 0;
   for (size_t v : {gemm_qkv_workspace_bytes((int)T, nqkv, d->d_model, d->dt, w8, d->use_rope != 0, q_len, d->head_dim),
                    gemm_ws((int)T, d->d_model, hd, FORGE_ACT_NONE, d->dt, w8),
-                   gemm_ws((int)T, d->d_ff, d->d_model, d->mlp_act, d->dt, w8),
+                   gemm_ws((int)T, d->d_ff, d->d_model, d->mlp_act, d->dt, w8, true),
                    gemm_ws((int)T, d->d_model, d->d_ff, FORGE_ACT_NONE, d->dt, w8)})
     g = v > g ? v : g;
   p.gemm = align_up(g, 256);
@@ -163,7 +163,7 @@ ModelPlan plan_model(const forge_model_desc* m, int batch, int q_len, int kv_cap
     const size_t b = plan_block(&m->layers[l], batch, q_len, kv_cap).total;
     p.block = b > p.block ? b : p.block;
   }
-  const size_t head = m->wte != nullptr ? align_up(gemm_ws((int)T, m->vocab, d0->d_model, FORGE_ACT_NONE, d0->dt, false), 256) : 0;
+  const size_t head = m->wte != nullptr ? align_up(gemm_ws((int)T, m->vocab, d0->d_model, FORGE_ACT_NONE, d0->dt, false, true), 256) : 0;
   p.block = head > p.block ? head : p.block;
   p.total = p.h + p.yf + p.block;
   return p;
@@ -289,7 +289,7 @@ forge_status forge_attn_fused_masked(const void* q, const void* k, const void* v
 
 size_t forge_gemm_workspace_bytes(int M, int N, int K, forge_act act, forge_dtype dt) {
   if (M < 1 || N < 1 || K < 1 || !gemm_size_ok(M, N)) return 0;
-  return gemm_ws(M, N, K, act, dt, false);
+  return gemm_ws(M, N, K, act, dt, false, true);
 }
 
 const char* forge_gemm_variant(int M, int N, int K, int ldy, forge_act act, forge_dtype dt) {
@@ -308,7 +308,7 @@ forge_status forge_gemm_bias_gelu(const void* x, const void* w, const void* bias
   if (K % (dt == FORGE_BF16 ? 8 : 4) != 0 || !gemm_size_ok(M, N)) return FORGE_ERR_UNSUPPORTED;
   if (y == x || y == w) return FORGE_ERR_INVALID_ARG;
   // only the decode-sized bf16 problems cannot run without their partial-sum planes
-  const size_t need = dt == FORGE_BF16 && M <= 64 ? gemm_ws(M, N, K, act, dt, false) : 0;
+  const size_t need = dt == FORGE_BF16 && M <= 64 ? gemm_ws(M, N, K, act, dt, false, true) : 0;
   if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FORGE_ERR_WORKSPACE;
   GemmArgs a = {x, w, bias, residual, y, M, N, K, ldy, act, nullptr, nullptr, workspace, workspace_bytes};
   return gemm_dispatch(a, dt, static_cast<hipStream_t>(stream));

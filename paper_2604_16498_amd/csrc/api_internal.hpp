@@ -56,9 +56,10 @@ inline size_t attn_ws(int batch, int q_heads, int kv_heads, int q_len, int kv_le
   return 0;
 }
 
-inline size_t gemm_ws(int M, int N, int K, forge_act act, forge_dtype dt, bool w8) {
+// plain: see gemm_bf16_workspace_bytes
+inline size_t gemm_ws(int M, int N, int K, forge_act act, forge_dtype dt, bool w8, bool plain = false) {
   if (w8) return gemm_w8_workspace_bytes(M, N, K, act);
-  return dt == FORGE_BF16 ? gemm_bf16_workspace_bytes(M, N, K, act) : gemm_f32_workspace_bytes(M, N, K, act);
+  return dt == FORGE_BF16 ? gemm_bf16_workspace_bytes(M, N, K, act, plain) : gemm_f32_workspace_bytes(M, N, K, act);
 }
 
 // int8 weights: all four scale vectors given (checked by check_block_desc: all or none)

@@ -208,7 +208,9 @@ bool gemm_fuses_tail(int M, int N, forge_dtype dt);
 // then needs gemm_qkv_workspace_bytes() of workspace for its cos / sin table.
 bool gemm_qkv_fuses_rope(int M, int N, int K, int head_dim, int q_len, forge_dtype dt, bool w8);
 size_t gemm_qkv_workspace_bytes(int M, int N, int K, forge_dtype dt, bool w8, bool rope, int q_len, int head_dim);
-size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act);
+// plain: the output is a dense matrix with bias / activation / residual only (no head split, no norm
+// tail); a decode-sized problem that is finished inside the streaming kernel then needs nothing
+size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act, bool plain);
 size_t gemm_w8_workspace_bytes(int M, int N, int K, forge_act act);   // required, any M
 // Symmetric int8 quantisation of a weight, one scale per row.
 forge_status launch_quantize_int8(const void* w, int8_t* q, float* scale, int N, int K, forge_dtype dt,

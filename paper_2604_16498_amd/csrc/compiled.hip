@@ -132,7 +132,7 @@ void lower(forge_compiled* c) {
       lo.emit({FORGE_OP_NORM, l, 1, y2, h_mid, REG_NONE, REG_NONE, REG_NONE}, {h_mid});
     }
     const int u = lo.new_reg(T * d.d_ff * es);
-    ws = lo.new_reg(gemm_ws(Ti, d.d_ff, dm, d.mlp_act, dt, w8));
+    ws = lo.new_reg(gemm_ws(Ti, d.d_ff, dm, d.mlp_act, dt, w8, true));
     lo.emit({FORGE_OP_GEMM_ACT, l, 0, u, y2, REG_NONE, REG_NONE, ws}, {y2, ws});
     if (chain && l + 1 == m.n_layers && !tokens) {
       // the final norm is the caller's output; nobody reads the last residual stream, which is
@@ -156,7 +156,7 @@ void lower(forge_compiled* c) {
       yf = lo.new_reg(h_bytes);
       lo.emit({FORGE_OP_NORM, -1, 2, yf, h, REG_NONE, REG_NONE, REG_NONE}, {h});
     }
-    const int ws = lo.new_reg(gemm_ws(Ti, m.vocab, dm, FORGE_ACT_NONE, dt, false));
+    const int ws = lo.new_reg(gemm_ws(Ti, m.vocab, dm, FORGE_ACT_NONE, dt, false, true));
     lo.emit({FORGE_OP_GEMM, -1, 0, REG_EXT, yf, REG_NONE, REG_NONE, ws}, {yf, ws});
   } else if (!chain) {
     lo.emit({FORGE_OP_NORM, -1, 2, REG_EXT, h, REG_NONE, REG_NONE, REG_NONE}, {h});

@@ -1404,10 +1404,12 @@ size_t gemm_qkv_workspace_bytes(int M, int N, int K, forge_dtype dt, bool w8, bo
   if (rope && M > 64 && gemm_qkv_fuses_rope(M, N, K, head_dim, q_len, dt, w8))
     return (size_t)q_len * head_dim * sizeof(float);            // the cos / sin table
   if (w8) return gemm_w8_workspace_bytes(M, N, K, FORGE_ACT_NONE);
-  return dt == FORGE_BF16 ? gemm_bf16_workspace_bytes(M, N, K, FORGE_ACT_NONE) : gemm_f32_workspace_bytes(M, N, K, FORGE_ACT_NONE);
+  return dt == FORGE_BF16 ? gemm_bf16_workspace_bytes(M, N, K, FORGE_ACT_NONE, false) : gemm_f32_workspace_bytes(M, N, K, FORGE_ACT_NONE);
 }
 
-size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act) {
+size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act, bool plain) {
+  // plain: a dense output with bias / activation / residual only (no head split, no norm tail)
+  if (M <= 64 && plain && K % BK == 0 && plan_skinny(N, K, act).fused) return 0;   // finished inside the GEMM
   if (M > 64) {     // optional: without it the problem runs unsplit
     const int ncols = act == FORGE_ACT_SWIGLU ? 2 * N : N;
     const PersSplit ps = plan_pers_split(M, ncols, K);
@@ -1454,10 +1456,11 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   p.splits = 1;
   const bool w8 = a.w_scale != nullptr;
   // the decode path needs its partial-sum planes; the k split of larger problems is optional
-  const size_t need = w8 ? gemm_w8_workspace_bytes(a.M, a.N, a.K, a.act)
-                         : (a.M <= 64 ? gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act) : 0);
-  if (need > a.workspace_bytes || (need > 0 && a.workspace == nullptr)) return FORGE_ERR_WORKSPACE;
   const bool tails = gemm_fuses_tail(a.M, a.N, FORGE_BF16);
+  const bool plain = a.split == nullptr && !(a.norm != nullptr && tails && a.act == FORGE_ACT_NONE);
+  const size_t need = w8 ? gemm_w8_workspace_bytes(a.M, a.N, a.K, a.act)
+                         : (a.M <= 64 ? gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act, plain) : 0);
+  if (need > a.workspace_bytes || (need > 0 && a.workspace == nullptr)) return FORGE_ERR_WORKSPACE;
   if (a.norm != nullptr && tails && a.split == nullptr && a.act == FORGE_ACT_NONE) {
     if (p.ldy != a.N) return FORGE_ERR_UNSUPPORTED;   // the norm tail writes dense rows
     p.nt = *a.norm;
