@@ -169,9 +169,12 @@ forge_status forge_deinterleave_gated_rows(const void* src, void* dst, int n_pai
  *   residual, y in bf16, fp32 accumulation; the scale multiplies the finished sum (the same
  *   value as multiplying every weight, one rounding fewer).  Arguments as forge_gemm_bias_gelu
  *   (SWIGLU: wq [2N,K], wscale [2N]).  K % 128 != 0 -> FORGE_ERR_UNSUPPORTED.  The workspace of
- *   forge_gemm_w8_workspace_bytes is REQUIRED for every M.  M <= 64 is the tuned case (a decode
- *   step: the int8 weight is streamed once at half the bytes of bf16); larger M runs 64 rows at
- *   a time, re-reading the weight for each group.
+ *   forge_gemm_w8_workspace_bytes is REQUIRED for every M.  M <= 64 (a decode step): the int8
+ *   weight is streamed once at half the bytes of bf16.  Larger M (a prompt): the integers are
+ *   written out once as bf16 (exact) into the workspace, which therefore holds a bf16 copy of
+ *   the weight, and the bf16 kernels run on that copy with the row scale applied to the finished
+ *   sums: the same arithmetic at both sizes, about the speed of the bf16 call plus one pass
+ *   over the weight.
  * ------------------------------------------------------------------------------------ */
 forge_status forge_quantize_int8(const void* w, int8_t* q, float* scale, int N, int K,
                                  forge_dtype dt, void* stream);

@@ -236,8 +236,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_generic_kernel(GemmPara
           p.part[((int64_t)blockIdx.y * M + m) * N + n] = acc[i][j][v];
           continue;
         }
-        float val = acc[i][j][v] + bv;
-        if (SWIGLU) val = silu_f(val) * (acc[i][SWIGLU ? j + TN / 2 : j][v] + bv2);
+        const float ws1 = p.wscale != nullptr ? p.wscale[n] : 1.0f;
+        const float ws2 = SWIGLU && p.wscale != nullptr ? p.wscale[n + N] : 1.0f;
+        float val = acc[i][j][v] * ws1 + bv;
+        if (SWIGLU) val = silu_f(val) * (acc[i][SWIGLU ? j + TN / 2 : j][v] * ws2 + bv2);
         else val = apply_act<ACT>(val);
         if (MODE == MODE_QKV) {
           *split_dst_bf16(p.sp, p.row0 + m, n) = (bf16)val;
@@ -654,6 +656,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
             float o[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = run[gp][e];
+            if (p.wscale != nullptr) {      // dequantised int8 weight: one scale per weight row
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                const int ne = min(n + e, N - 1);
+                o[e] *= p.wscale[ne];
+                if (SWIGLU) run2[gp][e] *= p.wscale[N + ne];
+              }
+            }
             if (p.bias != nullptr && in) {
               float bb[8];
               Vec8<bf16>::load(p.bias + n, bb);
@@ -1301,6 +1311,7 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
         b.part_bytes = 0;
         b.w = p.w + (int64_t)c * p.K;
         if (p.bias != nullptr) b.bias = p.bias + c;
+        if (p.wscale != nullptr) b.wscale = p.wscale + c;
         const forge_status st = launch_act<ACT, MODE>(a, s);
         return st != FORGE_OK ? st : launch_act<ACT, MODE>(b, s);
       }
@@ -1370,6 +1381,17 @@ forge_status launch_act(const GemmParams& p, hipStream_t s) {
   }
 }
 
+// int8 -> bf16, exact (|q| <= 127 has 7 significant bits); one thread per 16 weights (K % 128 == 0)
+__global__ __launch_bounds__(256) void dequant_int8_kernel(const int8_t* __restrict__ q, bf16* __restrict__ w,
+                                                           int64_t n16) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n16) return;
+  const u32x4 v = *reinterpret_cast<const u32x4*>(q + i * 16);
+  const bf16x8 lo = cvt_i8x8_bf16(u32x2{v[0], v[1]}), hi = cvt_i8x8_bf16(u32x2{v[2], v[3]});
+  *reinterpret_cast<bf16x8*>(w + i * 16) = lo;
+  *reinterpret_cast<bf16x8*>(w + i * 16 + 8) = hi;
+}
+
 // cos / sin of the rotary embedding for rows 0 .. q_len-1 of a prompt at positions pos0 + s:
 // tab[s][i] = (cos, sin)(p * theta_i), theta_i = base^(-2i/dh), evaluated in fp64 as rope_kernel
 // does (p * theta reaches thousands of radians) and stored as fp32.
@@ -1391,7 +1413,7 @@ __global__ __launch_bounds__(256) void rope_table_kernel(float* __restrict__ tab
 bool gemm_qkv_fuses_rope(int M, int N, int K, int head_dim, int q_len, forge_dtype dt, bool w8) {
   if (dt != FORGE_BF16) return false;
   if (M <= 64) return gemm_fuses_tail(M, N, dt);     // the reduce step of the weight-streaming path rotates
-  if (w8) return false;                              // int8 prompts run 64 rows at a time, unrotated
+  if (w8) return false;                              // int8 prompts: the workspace holds the bf16 copy of the weight
   if (q_len == 1) return false;                      // a wide decode step may carry per-sequence positions
   if (head_dim != 64 && head_dim != 128) return false;
   const Variant v = choose_variant(M, N, K, N, FORGE_ACT_NONE, true);
@@ -1419,9 +1441,16 @@ size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act, bool plain)
   return (size_t)sk.splits * M * sk.ncols * sizeof(float);
 }
 
+// bytes of the bf16 copy of an int8 weight (prompt-sized problems), 256-byte aligned
+inline size_t w8_dequant_bytes(int N, int K, forge_act act) {
+  const size_t b = (size_t)(act == FORGE_ACT_SWIGLU ? 2 : 1) * N * K * sizeof(bf16);
+  return (b + 255) / 256 * 256;
+}
+
 size_t gemm_w8_workspace_bytes(int M, int N, int K, forge_act act) {
+  if (M > 64) return w8_dequant_bytes(N, K, act) + gemm_bf16_workspace_bytes(M, N, K, act, false);
   const SkinnyPlan sk = plan_skinny(N, K, act, 2 * BK);
-  return (size_t)sk.splits * (M < 64 ? M : 64) * sk.ncols * sizeof(float);
+  return (size_t)sk.splits * M * sk.ncols * sizeof(float);
 }
 
 bool gemm_fuses_tail(int M, int N, forge_dtype dt) {
@@ -1502,25 +1531,27 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   };
   if (!w8) return dispatch(p);
 
-  // Weight-only int8: only the streaming kernel reads such weights.  At most 64 rows go through
-  // it as they are; more rows go 64 at a time (the weight is streamed once per 64 rows: correct,
-  // not tuned - int8 weights are meant for the decode step).
+  // Weight-only int8.  At most 64 rows: the streaming kernel reads the int8 rows as they are.  More
+  // rows (a prompt): the integers are written out once as bf16 (exact) into the workspace and the
+  // bf16 kernels run on them, with the row scale applied to the finished sums in their epilogues,
+  // so both sizes compute scale * sum(x q) and the weight is read once either way.
   if (a.K % (2 * BK) != 0) return FORGE_ERR_UNSUPPORTED;
-  p.w = nullptr;
-  p.w8 = (const int8_t*)a.w;
   p.wscale = a.w_scale;
-  if (a.M <= 64) return dispatch(p);
-  for (int m0 = 0; m0 < a.M; m0 += 64) {
-    GemmParams q = p;
-    q.M = min(64, a.M - m0);
-    q.row0 = m0;
-    q.x = p.x + (int64_t)m0 * p.K;
-    if (p.y != nullptr) q.y = p.y + (int64_t)m0 * p.ldy;
-    if (p.residual != nullptr) q.residual = p.residual + (int64_t)m0 * p.ldy;
-    const forge_status st = dispatch(q);
-    if (st != FORGE_OK) return st;
+  if (a.M <= 64) {
+    p.w = nullptr;
+    p.w8 = (const int8_t*)a.w;
+    return dispatch(p);
   }
-  return FORGE_OK;
+  const int64_t w_elems = (a.act == FORGE_ACT_SWIGLU ? 2 : 1) * (int64_t)a.N * a.K;
+  const size_t w_bytes = w8_dequant_bytes(a.N, a.K, a.act);
+  bf16* wd = (bf16*)a.workspace;
+  dequant_int8_kernel<<<(unsigned)ceil_div64(w_elems / 16, 256), 256, 0, s>>>((const int8_t*)a.w, wd, w_elems / 16);
+  if (hipGetLastError() != hipSuccess) return FORGE_ERR_HIP;
+  p.w = wd;
+  p.w8 = nullptr;
+  p.part = (float*)((char*)a.workspace + w_bytes);
+  p.part_bytes = a.workspace_bytes - w_bytes;
+  return dispatch(p);
 }
 
 }  // namespace forge

@@ -47,7 +47,9 @@ def test_quantize_int8_bit_exact(F, bf16, N, K):
 
 
 W8_SHAPES = [(1, 128, 128), (7, 520, 128), (16, 1000, 512), (33, 136, 1024), (64, 4096, 512),
-             (64, 768, 3072), (48, 257, 384), (2, 1536, 4096), (130, 392, 256), (200, 264, 128)]
+             (64, 768, 3072), (48, 257, 384), (2, 1536, 4096), (130, 392, 256), (200, 264, 128),
+             # prompts: the weight is written out as bf16 once, the bf16 kernels apply the row scale
+             (600, 1032, 256), (300, 1001, 128), (4096, 4096, 128), (1100, 520, 2048)]
 
 
 @pytest.mark.parametrize("act", ["none", "gelu_tanh", "silu", "swiglu"])
