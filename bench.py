@@ -447,8 +447,9 @@ def measure(wl, m, F, torch, steps, warmup, latency_steps=50, traced_steps=3, wi
     return res
 
 
-def int8_decode(wl, m, F, torch, steps, warmup):
-    """The decode step on int8 weights (quantised by the library's own kernel)."""
+def int8_weights(wl, m, F, torch, steps, warmup):
+    """The same step on int8 weights (quantised by the library's own kernel): the decode step streams
+    them as they are, the prompt-sized step writes each weight out as bf16 into the workspace first."""
     layers8 = []
     for w in m["layers"]:
         d = dict(w)
@@ -655,8 +656,8 @@ def main():
 
     head = measure(wl, m, F, torch, args.steps, args.warmup)
     log("measured %s: %.4f ms/step" % (wl.name, head["ms_per_step"]))
-    if head_id == 5:
-        head["int8_weights"] = int8_decode(wl, m, F, torch, args.steps, args.warmup)
+    if head_id in (4, 5):
+        head["int8_weights"] = int8_weights(wl, m, F, torch, args.steps, args.warmup)
 
     # ---- roofline of the dominant kernel of the headline workload, timed inside the step ----------
     dom = head["dominant_operator"]
@@ -691,8 +692,8 @@ def main():
                 log("built %s" % w2.name)
                 st, wu = (200, 20) if cid == 1 else (20, 5)
                 r = measure(w2, m2, F, torch, st, wu, traced_steps=10 if cid == 1 else 3)
-                if cid == 5:
-                    r["int8_weights"] = int8_decode(w2, m2, F, torch, st, wu)
+                if cid in (4, 5):
+                    r["int8_weights"] = int8_weights(w2, m2, F, torch, st, wu)
                 if not args.no_cpu_baseline:
                     r["cpu_baseline"] = cpu_baseline(w2, m2, args.cpu_seconds / 3)
                 log("measured %s: %.4f ms/step" % (w2.name, r["ms_per_step"]))
