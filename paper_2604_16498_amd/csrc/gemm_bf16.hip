@@ -612,6 +612,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
           for (int gp = 0; gp < 2; ++gp) {
             const int cl = blk * 4 + 2 * fh + gp, ch = cl + rope_hb * 4;   // chunks of the pair's two halves
             const int n_lo = n0 + cl * 8, n_hi = n0 + ch * 8;
+            if (p.wscale != nullptr && n_hi + 8 <= N) {   // dequantised int8 weight: one scale per weight row
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                lo[gp][e] *= p.wscale[n_lo + e];
+                hi[gp][e] *= p.wscale[n_hi + e];
+              }
+            }
             if (p.bias != nullptr && n_hi + 8 <= N) {     // N % 8 == 0 (host): a chunk is all in or all out
               float bb[8];
               Vec8<bf16>::load(p.bias + n_lo, bb);
@@ -1410,10 +1417,16 @@ __global__ __launch_bounds__(256) void rope_table_kernel(float* __restrict__ tab
 
 }  // namespace
 
+// bytes of the bf16 copy of an int8 weight (prompt-sized problems), 256-byte aligned
+inline size_t w8_dequant_bytes(int N, int K, forge_act act) {
+  const size_t b = (size_t)(act == FORGE_ACT_SWIGLU ? 2 : 1) * N * K * sizeof(bf16);
+  return (b + 255) / 256 * 256;
+}
+
 bool gemm_qkv_fuses_rope(int M, int N, int K, int head_dim, int q_len, forge_dtype dt, bool w8) {
   if (dt != FORGE_BF16) return false;
   if (M <= 64) return gemm_fuses_tail(M, N, dt);     // the reduce step of the weight-streaming path rotates
-  if (w8) return false;                              // int8 prompts: the workspace holds the bf16 copy of the weight
+  if (w8 && K % (2 * BK) != 0) return false;         // (an int8 prompt runs the bf16 kernels on a bf16 copy of the weight)
   if (q_len == 1) return false;                      // a wide decode step may carry per-sequence positions
   if (head_dim != 64 && head_dim != 128) return false;
   const Variant v = choose_variant(M, N, K, N, FORGE_ACT_NONE, true);
@@ -1423,8 +1436,8 @@ bool gemm_qkv_fuses_rope(int M, int N, int K, int head_dim, int q_len, forge_dty
 }
 
 size_t gemm_qkv_workspace_bytes(int M, int N, int K, forge_dtype dt, bool w8, bool rope, int q_len, int head_dim) {
-  if (rope && M > 64 && gemm_qkv_fuses_rope(M, N, K, head_dim, q_len, dt, w8))
-    return (size_t)q_len * head_dim * sizeof(float);            // the cos / sin table
+  if (rope && M > 64 && gemm_qkv_fuses_rope(M, N, K, head_dim, q_len, dt, w8))   // [bf16 copy of an int8 weight |] cos / sin table
+    return (w8 ? w8_dequant_bytes(N, K, FORGE_ACT_NONE) : 0) + (size_t)q_len * head_dim * sizeof(float);
   if (w8) return gemm_w8_workspace_bytes(M, N, K, FORGE_ACT_NONE);
   return dt == FORGE_BF16 ? gemm_bf16_workspace_bytes(M, N, K, FORGE_ACT_NONE, false) : gemm_f32_workspace_bytes(M, N, K, FORGE_ACT_NONE);
 }
@@ -1439,12 +1452,6 @@ size_t gemm_bf16_workspace_bytes(int M, int N, int K, forge_act act, bool plain)
   }
   const SkinnyPlan sk = plan_skinny(N, K, act);
   return (size_t)sk.splits * M * sk.ncols * sizeof(float);
-}
-
-// bytes of the bf16 copy of an int8 weight (prompt-sized problems), 256-byte aligned
-inline size_t w8_dequant_bytes(int N, int K, forge_act act) {
-  const size_t b = (size_t)(act == FORGE_ACT_SWIGLU ? 2 : 1) * N * K * sizeof(bf16);
-  return (b + 255) / 256 * 256;
 }
 
 size_t gemm_w8_workspace_bytes(int M, int N, int K, forge_act act) {
@@ -1487,7 +1494,7 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   // the decode path needs its partial-sum planes; the k split of larger problems is optional
   const bool tails = gemm_fuses_tail(a.M, a.N, FORGE_BF16);
   const bool plain = a.split == nullptr && !(a.norm != nullptr && tails && a.act == FORGE_ACT_NONE);
-  const size_t need = w8 ? gemm_w8_workspace_bytes(a.M, a.N, a.K, a.act)
+  const size_t need = w8 ? (a.M > 64 ? w8_dequant_bytes(a.N, a.K, a.act) : gemm_w8_workspace_bytes(a.M, a.N, a.K, a.act))
                          : (a.M <= 64 ? gemm_bf16_workspace_bytes(a.M, a.N, a.K, a.act, plain) : 0);
   if (need > a.workspace_bytes || (need > 0 && a.workspace == nullptr)) return FORGE_ERR_WORKSPACE;
   if (a.norm != nullptr && tails && a.split == nullptr && a.act == FORGE_ACT_NONE) {
@@ -1503,12 +1510,13 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
       if (!gemm_qkv_fuses_rope(a.M, a.N, a.K, p.sp.head_dim, p.sp.q_len, FORGE_BF16, w8) || p.sp.pos != nullptr)
         return FORGE_ERR_UNSUPPORTED;
       const size_t tab_bytes = (size_t)p.sp.q_len * p.sp.head_dim * sizeof(float);
-      if (a.workspace == nullptr || a.workspace_bytes < tab_bytes) return FORGE_ERR_WORKSPACE;
+      const size_t tab_at = w8 ? w8_dequant_bytes(a.N, a.K, FORGE_ACT_NONE) : 0;   // behind the bf16 copy of an int8 weight
+      if (a.workspace == nullptr || a.workspace_bytes < tab_at + tab_bytes) return FORGE_ERR_WORKSPACE;
+      float* tab = (float*)((char*)a.workspace + tab_at);
       const int n_tab = p.sp.q_len * (p.sp.head_dim / 2);
-      rope_table_kernel<<<ceil_div(n_tab, 256), 256, 0, s>>>((float*)a.workspace, p.sp.q_len, p.sp.head_dim,
-                                                           p.sp.pos0, p.sp.rope_base);
+      rope_table_kernel<<<ceil_div(n_tab, 256), 256, 0, s>>>(tab, p.sp.q_len, p.sp.head_dim, p.sp.pos0, p.sp.rope_base);
       if (hipGetLastError() != hipSuccess) return FORGE_ERR_HIP;
-      p.sp.rope_tab = (const float*)a.workspace;
+      p.sp.rope_tab = tab;
       p.part = nullptr;
       p.part_bytes = 0;
       rope_epilogue = true;
@@ -1549,8 +1557,10 @@ forge_status launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   if (hipGetLastError() != hipSuccess) return FORGE_ERR_HIP;
   p.w = wd;
   p.w8 = nullptr;
-  p.part = (float*)((char*)a.workspace + w_bytes);
-  p.part_bytes = a.workspace_bytes - w_bytes;
+  if (!rope_epilogue) {            // (with the rotation in the epilogue the table sits there, and K is not split)
+    p.part = (float*)((char*)a.workspace + w_bytes);
+    p.part_bytes = a.workspace_bytes - w_bytes;
+  }
   return dispatch(p);
 }
 

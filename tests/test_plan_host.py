@@ -132,7 +132,8 @@ CASES = [
     ("llama_decode_f32", LLAMA, 2, False, B.FORGE_F32, 8, 1, 40, 64, True, True, True),
     ("gpt_decode_bf16", GPT, 12, True, B.FORGE_BF16, 4, 1, 100, 128, False, False, False),
     ("llama_decode_int8", LLAMA, 3, False, B.FORGE_BF16, 16, 1, 300, 320, False, False, False),
-    ("llama_prefill_int8", LLAMA, 2, False, B.FORGE_BF16, 1, 96, 0, 96, True, True, True),
+    # (an int8 prompt runs the bf16 kernels on a bf16 copy of each weight: the projection rotates)
+    ("llama_prefill_int8", LLAMA, 2, False, B.FORGE_BF16, 1, 96, 0, 96, False, True, True),
 ]
 
 
@@ -170,8 +171,10 @@ def test_compiled_program_and_its_plan(case):
     gws = (lambda M, N, K, a, _dt: l.forge_gemm_w8_workspace_bytes(M, N, K, a)) if w8 else l.forge_gemm_workspace_bytes
     # (a bf16 prompt that rotates in its QKV epilogue keeps a cos / sin table there instead:
     # one fp32 pair per row of the prompt and rotation pair)
-    rope_table = shape.use_rope and dt == B.FORGE_BF16 and q_len > 1 and T > 64 and not w8
-    scratch = {"ws_qkv": q_len * shape.head_dim * 4 if rope_table else gws(T, nqkv, shape.d_model, 0, dt),
+    # (behind the bf16 copy of the weight when the weight is int8)
+    rope_table = shape.use_rope and dt == B.FORGE_BF16 and q_len > 1 and T > 64
+    w_copy = (nqkv * shape.d_model * 2 + 255) // 256 * 256 if w8 else 0
+    scratch = {"ws_qkv": w_copy + q_len * shape.head_dim * 4 if rope_table else gws(T, nqkv, shape.d_model, 0, dt),
                "ws_o": gws(T, shape.d_model, hd, 0, dt),
                "ws_up": gws(T, shape.d_ff, shape.d_model, act, dt),
                "ws_down": gws(T, shape.d_model, shape.d_ff, 0, dt),
