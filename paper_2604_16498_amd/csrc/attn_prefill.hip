@@ -58,6 +58,7 @@ struct AttnParams {
   int n_qblocks;
   const float* mask;        // additive, fp32 [*, *, q_len, kv_len]; only read by the MASKED kernel
   int64_t mask_bs, mask_hs;
+  int mask_vec;             // every group of 4 consecutive keys of a mask row is one aligned 16-byte load
 };
 
 __device__ inline float xchg32_max(float x) {
@@ -71,8 +72,9 @@ __device__ inline float xchg32_sum(float x) {
 }
 
 // MASKED: an additive mask (the optional mask node of the paper's attention chain) is added to
-// the scaled scores before the softmax; its values are fetched when the tile's softmax starts
-// (not hidden behind anything: this variant trades speed for generality).
+// the scaled scores before the softmax.  A lane's 32 mask values of a tile (its query row, the keys
+// its score registers hold: 8 groups of 4 consecutive keys) are requested at the end of the
+// preceding matrix phase, 16 bytes per load, and arrive behind the half-tile barrier.
 template <int DH, bool MASKED>
 __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   constexpr int BQ = 256, BKV = 64;
@@ -167,6 +169,23 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   const float* mask_row = nullptr;
   if (MASKED)
     mask_row = p.mask + b * p.mask_bs + h * p.mask_hs + (int64_t)min(my_q, p.q_len - 1) * p.kv_len;
+  floatx4 mk[MASKED ? 8 : 1];      // mask values of the tile whose vector phase comes next
+  auto mask_prefetch = [&](int t) {
+    if (!MASKED) return;
+#pragma unroll
+    for (int g8 = 0; g8 < 8; ++g8) {
+      const int key0 = t * BKV + (g8 >> 2) * 32 + 8 * (g8 & 3) + 4 * fh;     // registers 4 (g8 & 3) .. + 3 of block g8 >> 2
+      floatx4 m = {0.f, 0.f, 0.f, 0.f};                                     // keys past the end are cut in the softmax
+      if (p.mask_vec) {
+        if (key0 < p.kv_len) m = *reinterpret_cast<const floatx4*>(mask_row + key0);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (key0 + e < p.kv_len) m[e] = mask_row[key0 + e];
+      }
+      mk[g8] = m;
+    }
+  };
 
   // per-lane byte offset of the transposing V read inside a tile (without key step / d tile)
   const int vt_lane = (((lane & 15) >> 2) + 4 * fh) * VS + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
@@ -204,11 +223,7 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = kv0 + kb * 32 + 8 * (v >> 2) + 4 * fh + (v & 3);
-          const float mk = key < p.kv_len ? mask_row[key] : 0.f;      // keys past the end are cut below
-          sc[kb][v] = sc[kb][v] * p.scale_log2e + mk * LOG2E;
-        }
+        for (int v = 0; v < 16; ++v) sc[kb][v] = sc[kb][v] * p.scale_log2e + mk[kb * 4 + (v >> 2)][v & 3] * LOG2E;
     }
     if (kv0 + BKV - 1 > wave_min_limit) {       // diagonal / tail tiles only
 #pragma unroll
@@ -286,7 +301,10 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   store_k(0);
   store_v(0);
   __syncthreads();
-  if (wave_needs(0)) scores(0);
+  if (wave_needs(0)) {
+    scores(0);
+    mask_prefetch(0);
+  }
   __syncthreads();
 
   // Steps of half a tile, a block barrier after each; the late waves run one step behind:
@@ -297,7 +315,10 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(AttnParams p) {
   // read by the late waves' P.V(t-1) in step 2t, first read by the early waves' P.V(t+1) in step 2t+3.
   auto matrix_phase = [&](int t) {
     if (wave_needs(t)) pv_mm(t);
-    if (wave_needs(t + 1)) scores(t + 1);
+    if (wave_needs(t + 1)) {
+      scores(t + 1);
+      mask_prefetch(t + 1);
+    }
   };
   if (!late) {
     for (int t = 0; t < n_tiles; ++t) {
@@ -358,6 +379,8 @@ forge_status launch_dh(const AttnArgs& a, hipStream_t s) {
   p.mask = a.mask;
   p.mask_bs = a.mask_batch_stride;
   p.mask_hs = a.mask_head_stride;
+  p.mask_vec = a.mask != nullptr && a.kv_len % 4 == 0 && (reinterpret_cast<uintptr_t>(a.mask) & 15u) == 0 &&
+               a.mask_batch_stride % 4 == 0 && a.mask_head_stride % 4 == 0;
   constexpr int smem = 2 * 64 * ((DH * 2 + 16) + (DH * 2 + 64));
   auto kern = attn_prefill_kernel<DH, MASKED>;
   static std::atomic<uint64_t> lds_raised{0};   // per kernel instantiation
