@@ -42,7 +42,8 @@ struct DecParams {
   const bf16* v;
   float* part;     // [B, Hkv, splits, G, dh + 2]
   bf16* out;       // [B, Hq * dh]: written directly when splits == 1
-  int q_heads, kv_heads, kv_len, splits;
+  int q_heads, kv_heads, kv_len, splits;   // kv_heads counts blockIdx.y: cache heads x passes
+  int passes;           // blocks (of G query heads each) that share one cache head
   int rows_per_split;   // multiple of GRAIN
   int64_t kv_bs, kv_hs;
   float scale_log2e;
@@ -79,8 +80,10 @@ __global__ __launch_bounds__(NWAVES * 64, G > 4 ? 2 : 3) void attn_decode_kernel
   const int head = lane & 15;                          // ... and the accumulator's column
   const int slot = lane / LPR, c = lane % LPR;         // V layout: row in step / 16-byte chunk
 
-  const bf16* kb = p.k + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
-  const bf16* vb = p.v + (int64_t)b * p.kv_bs + (int64_t)g * p.kv_hs;
+  // query heads g G ... g G + G - 1 attend to cache head g / passes
+  const int64_t cache_head = (int64_t)b * p.kv_bs + (int64_t)(g / p.passes) * p.kv_hs;
+  const bf16* kb = p.k + cache_head;
+  const bf16* vb = p.v + cache_head;
   const int split_begin = split * p.rows_per_split;
   // tiles of this wave that begin before the end of the range, rounded up to a pair (the loop
   // takes two per trip; the loads stay unconditional so that their count per trip is fixed)
@@ -300,9 +303,27 @@ inline int splits_bound(int batch, int kv_heads, int kv_len) {
   return max(1, min(max_splits(batch, kv_heads), ceil_div(kv_len, GRAIN)));
 }
 
+// Query heads per block for `group` heads sharing one cache head: the whole group up to 8, else
+// its largest divisor up to 8 -- several blocks then each stream that cache head for their share of
+// the query heads (16 heads: two passes of 8).  More than four passes (a prime group above 8) are
+// left to the vector-ALU kernel.
+constexpr int MAX_G = 8, MAX_PASSES = 4;
+inline int heads_per_block(int group) {
+  if (group <= MAX_G) return group;
+  for (int d = MAX_G; d >= 1; --d)
+    if (group % d == 0) return group / d <= MAX_PASSES ? d : 0;
+  return 0;
+}
+// blocks along y: cache heads x passes (the split plan counts these)
+inline int block_heads(int q_heads, int kv_heads) {
+  const int gb = heads_per_block(q_heads / kv_heads);
+  return gb > 0 ? q_heads / gb : kv_heads;
+}
+
 template <int DH, int G>
 forge_status launch_dg(const AttnArgs& a, hipStream_t s) {
-  const SplitPlan pl = plan_splits(a.batch, a.kv_heads, a.kv_len);
+  const int yheads = a.q_heads / G;
+  const SplitPlan pl = plan_splits(a.batch, yheads, a.kv_len);
   DecParams p;
   p.q = (const bf16*)a.q;
   p.k = (const bf16*)a.k;
@@ -310,7 +331,8 @@ forge_status launch_dg(const AttnArgs& a, hipStream_t s) {
   p.part = (float*)a.workspace;
   p.out = (bf16*)a.out;
   p.q_heads = a.q_heads;
-  p.kv_heads = a.kv_heads;
+  p.kv_heads = yheads;
+  p.passes = yheads / a.kv_heads;
   p.kv_len = a.kv_len;
   p.splits = pl.splits;
   p.rows_per_split = pl.rows_per_split;
@@ -318,17 +340,17 @@ forge_status launch_dg(const AttnArgs& a, hipStream_t s) {
   p.kv_hs = a.kv_head_stride;
   p.scale_log2e = a.scale * 1.4426950408889634f;
   p.kv_pos = a.kv_pos;
-  attn_decode_kernel<DH, G><<<dim3(p.splits, a.kv_heads, a.batch), NWAVES * 64, 0, s>>>(p);
+  attn_decode_kernel<DH, G><<<dim3(p.splits, yheads, a.batch), NWAVES * 64, 0, s>>>(p);
   if (p.splits == 1) return launch_status();
   if (hipGetLastError() != hipSuccess) return FORGE_ERR_HIP;
   attn_decode_combine<DH><<<dim3(a.q_heads, a.batch), DH, 0, s>>>(p.part, (bf16*)a.out, a.q_heads,
-                                                                  a.kv_heads, p.splits);
+                                                                  yheads, p.splits);
   return launch_status();
 }
 
 template <int DH>
 forge_status launch_d(const AttnArgs& a, hipStream_t s) {
-  switch (a.q_heads / a.kv_heads) {
+  switch (heads_per_block(a.q_heads / a.kv_heads)) {
     case 1: return launch_dg<DH, 1>(a, s);
     case 2: return launch_dg<DH, 2>(a, s);
     case 3: return launch_dg<DH, 3>(a, s);
@@ -337,14 +359,14 @@ forge_status launch_d(const AttnArgs& a, hipStream_t s) {
     case 6: return launch_dg<DH, 6>(a, s);
     case 7: return launch_dg<DH, 7>(a, s);
     case 8: return launch_dg<DH, 8>(a, s);
-    default: return launch_attn_simple_bf16(a, s);   // larger groups: vector-ALU path
+    default: return launch_attn_simple_bf16(a, s);   // groups no pass count covers: vector-ALU path
   }
 }
 
 }  // namespace
 
 size_t attn_decode_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim) {
-  const int splits = splits_bound(batch, kv_heads, kv_len);
+  const int splits = splits_bound(batch, block_heads(q_heads, kv_heads), kv_len);
   if (splits == 1) return 0;       // one block per (kv head, sequence) writes the output itself
   return (size_t)batch * q_heads * splits * (head_dim + 2) * sizeof(float);
 }
@@ -377,7 +399,7 @@ forge_status attn_decode_static_scratch(void** ptr) {
 
 forge_status launch_attn_decode_bf16(const AttnArgs& a, hipStream_t s) {
   // what THIS launch writes (at most the bound the size query reports for any cache >= kv_len)
-  const int splits = plan_splits(a.batch, a.kv_heads, a.kv_len).splits;
+  const int splits = plan_splits(a.batch, block_heads(a.q_heads, a.kv_heads), a.kv_len).splits;
   const size_t need = splits == 1 ? 0 : (size_t)a.batch * a.q_heads * splits * (a.head_dim + 2) * sizeof(float);
   if (need > 0 && (a.workspace == nullptr || a.workspace_bytes < need)) return FORGE_ERR_WORKSPACE;
   if (a.head_dim == 64) return launch_d<64>(a, s);

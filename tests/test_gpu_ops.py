@@ -312,13 +312,21 @@ ATTN_SHAPES = [  # B, Hq, Hkv, Sq, Skv, cap, dh
     (130, 8, 4, 1, 45, 64, 128),
     # ... and with about one pair per CU: two row ranges
     (33, 32, 8, 1, 1000, 1000, 128),
-    # decode with 3, 5, 6, 7, 8 and 16 query heads per KV head (16: the vector-ALU path)
+    # decode with 3, 5, 6, 7, 8 and 16 query heads per KV head (16: two blocks of 8 per KV head)
     (2, 64, 8, 1, 513, 520, 128),
     (70, 16, 2, 1, 300, 300, 64),
     (2, 10, 2, 1, 900, 900, 64),
     (1, 12, 2, 1, 1500, 1504, 128),
     (3, 7, 1, 1, 260, 264, 64),
     (1, 32, 2, 1, 400, 400, 128),
+    # larger groups in several blocks per KV head: 32 = 4 x 8 (one KV head), 12 = 2 x 6, 24 = 3 x 8,
+    # 9 = 3 x 3, with and without row ranges; 11 has no such split (vector-ALU path)
+    (3, 32, 1, 1, 1100, 1104, 128),
+    (40, 32, 1, 1, 300, 320, 64),
+    (2, 24, 2, 1, 700, 704, 64),
+    (70, 24, 1, 1, 200, 200, 128),
+    (2, 9, 1, 1, 530, 536, 128),
+    (2, 11, 1, 1, 140, 144, 64),
 ]
 
 
