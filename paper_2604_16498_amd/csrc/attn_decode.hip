@@ -9,7 +9,7 @@
 // ahead of the one it is working on.  The number of splits is chosen on the host so that about
 // two blocks per compute unit exist: a large batch needs no split at all (one block per
 // (kv head, sequence) walks the whole cache and writes the final output itself: no partials, no
-// second kernel), a small batch is cut into ranges that are multiples of 128 rows.
+// second kernel), a small batch is cut into ranges that are multiples of 128 rows, 256 at least.
 //
 // Per tile of 16 rows:
 //   scores   S[row, head] = K . q^T on the matrix cores (v_mfma_f32_16x16x32_bf16, heads padded
@@ -283,7 +283,11 @@ __global__ __launch_bounds__(DH) void attn_decode_combine(const float* __restric
   out[((int64_t)b * q_heads + h) * DH + d] = (bf16)(o / ltot);
 }
 
-// Number of row ranges: about two blocks per compute unit, at most one range per GRAIN rows.
+// Number of row ranges: about two blocks per compute unit, but no range shorter than
+// MIN_SPLIT_ROWS: a block streams that many rows in less time than the second launch (the merge of
+// the ranges) costs, so a cache shorter than twice that is walked by one block per (head, sequence)
+// however few of those there are.
+constexpr int MIN_SPLIT_ROWS = 2 * GRAIN;
 struct SplitPlan { int splits, rows_per_split; };
 // the most ranges a batch is ever cut into, whatever the cache length
 inline int max_splits(int batch, int kv_heads) {
@@ -292,7 +296,7 @@ inline int max_splits(int batch, int kv_heads) {
   return for_two_per_cu < MAX_SPLITS ? (int)for_two_per_cu : MAX_SPLITS;
 }
 inline SplitPlan plan_splits(int batch, int kv_heads, int kv_len) {
-  const int want = max(1, min(max_splits(batch, kv_heads), ceil_div(kv_len, GRAIN)));
+  const int want = max(1, min(max_splits(batch, kv_heads), kv_len / MIN_SPLIT_ROWS));
   const int rows = ceil_div(ceil_div(kv_len, want), GRAIN) * GRAIN;
   return SplitPlan{ceil_div(kv_len, rows), rows};   // rows >= kv_len / want, so splits <= want
 }
@@ -300,7 +304,7 @@ inline SplitPlan plan_splits(int batch, int kv_heads, int kv_len) {
 // not monotone in the length (the range size is rounded up to GRAIN), the scratch size must be,
 // because a generation loop sizes its scratch once, for the capacity of its cache.
 inline int splits_bound(int batch, int kv_heads, int kv_len) {
-  return max(1, min(max_splits(batch, kv_heads), ceil_div(kv_len, GRAIN)));
+  return max(1, min(max_splits(batch, kv_heads), kv_len / MIN_SPLIT_ROWS));
 }
 
 // Query heads per block for `group` heads sharing one cache head: the whole group up to 8, else

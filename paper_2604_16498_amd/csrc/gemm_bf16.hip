@@ -1281,6 +1281,9 @@ inline SkinnyPlan plan_skinny(int N, int K, forge_act act, int bk = BK) {
   const int per = ceil_div(slabs, want);
   sp.splits = ceil_div(slabs, per);
   sp.k_per_split = per * bk;
+  // a short reduction (K < 1024) comes to one k range as well: the second launch would cost more
+  // than the few blocks lose by streaming alone
+  sp.fused = bk == BK && sp.bn == 128 && sp.splits == 1;
   return sp;
 }
 

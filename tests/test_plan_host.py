@@ -174,10 +174,16 @@ def test_compiled_program_and_its_plan(case):
     # (behind the bf16 copy of the weight when the weight is int8)
     rope_table = shape.use_rope and dt == B.FORGE_BF16 and q_len > 1 and T > 64
     w_copy = (nqkv * shape.d_model * 2 + 255) // 256 * 256 if w8 else 0
-    scratch = {"ws_qkv": w_copy + q_len * shape.head_dim * 4 if rope_table else gws(T, nqkv, shape.d_model, 0, dt),
-               "ws_o": gws(T, shape.d_model, hd, 0, dt),
+    def tail_ws(N, K):
+        """A projection whose output is not a plain matrix (head split, or a row norm behind it):
+        where the plain one of its shape is finished inside the GEMM (public query 0 for a decode
+        step), this one keeps the single fp32 plane that its reduce step reads."""
+        b = gws(T, N, K, 0, dt)
+        return T * N * 4 if b == 0 and T <= 64 and dt == B.FORGE_BF16 and not w8 else b
+    scratch = {"ws_qkv": w_copy + q_len * shape.head_dim * 4 if rope_table else tail_ws(nqkv, shape.d_model),
+               "ws_o": tail_ws(shape.d_model, hd),
                "ws_up": gws(T, shape.d_ff, shape.d_model, act, dt),
-               "ws_down": gws(T, shape.d_model, shape.d_ff, 0, dt),
+               "ws_down": tail_ws(shape.d_model, shape.d_ff),
                "ws_attn": l.forge_attn_fused_workspace_bytes(batch, shape.q_heads, shape.kv_heads, q_len,
                                                              pos0 + q_len, shape.head_dim, dt),
                "ws_head": l.forge_gemm_workspace_bytes(T, 1000, shape.d_model, 0, dt)}

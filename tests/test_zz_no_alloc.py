@@ -40,11 +40,11 @@ def _case(F, seed, B, Hq, Hkv, dh, kv_len, cap):
 
 def test_two_calls_in_a_row_share_the_scratch(F):
     _case(F, 91, 4, 32, 8, 128, 2049, 2100)      # 32 pairs -> 16 ranges of partials
-    _case(F, 92, 2, 8, 2, 64, 300, 320)          # smaller: 4 pairs -> 3 ranges, over the stale partials
+    _case(F, 92, 2, 8, 2, 64, 700, 704)          # smaller: 4 pairs -> 2 ranges, over the stale partials
 
 
 def test_too_large_for_the_fixed_array_is_rejected(F):
-    # 1 sequence x 64 query heads x 64 ranges x 130 floats = 2.1 MB fits; 128 query heads do not
+    # 2 sequences x 128 query heads x 32 ranges x 130 floats = 4.3 MB: more than the 4 MB array
     B, Hq, Hkv, dh, kv_len = 2, 128, 2, 128, 64 * 128
     assert F.forge_attn_fused_workspace_bytes(B, Hq, Hkv, 1, kv_len, dh, torch.bfloat16) > F.forge_attn_decode_static_max_bytes()
     q = torch.zeros(B, Hq, 1, dh, dtype=torch.bfloat16, device="cuda")
