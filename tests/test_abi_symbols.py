@@ -113,7 +113,9 @@ def test_decode_attention_scratch_is_monotone_in_the_cache_length():
     from paper_2604_16498_amd import binding as B
     l = B.lib()
     for batch, hq, hkv, dh in [(8, 32, 8, 128), (4, 12, 12, 64), (2, 12, 12, 64), (1, 32, 8, 128),
-                               (3, 16, 4, 128), (16, 8, 8, 64), (64, 32, 8, 128)]:
+                               (3, 16, 4, 128), (16, 8, 8, 64), (64, 32, 8, 128),
+                               # groups of 16 and 32 query heads (several blocks per KV head), 11 (none)
+                               (2, 32, 2, 128), (3, 32, 1, 64), (2, 11, 1, 64)]:
         prev = 0
         for kv_len in list(range(1, 700)) + list(range(700, 9000, 37)):
             need = l.forge_attn_fused_workspace_bytes(batch, hq, hkv, 1, kv_len, dh, B.FORGE_BF16)
