@@ -326,7 +326,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_pers_kernel(GemmParams 
   extern __shared__ __attribute__((aligned(16))) char smem[];   // [A0 | B0 | A1 | B1]
   char* const stg = smem + STAGE;                     // staging area = ring buffer 1
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // (the wave index is held in a scalar register: everything derived from it alone -- the LDS
+  // destinations of the direct loads above all -- is then computed on the scalar unit)
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
   const int fr = lane & 31, fh = lane >> 5;
   const int M = p.M, N = p.N, K = p.K;
