@@ -347,6 +347,39 @@ def test_attn_fused(F, bf16, causal, B, Hq, Hkv, Sq, Skv, cap, dh):
     check(out, ref, bf16, "attention")
 
 
+def _random_attn_cases():
+    rng = np.random.default_rng(16498)
+    cases = []
+    for _ in range(28):          # prompts: query and key counts around the 32-query / 64-key / 256-query boundaries
+        B = int(rng.integers(1, 4)); Hkv = int(rng.choice([1, 2, 3])); G = int(rng.choice([1, 1, 2, 3, 4, 8]))
+        Sq = int(rng.choice([2, 31, 33, 64, 65, 127, 129, 255, 256, 257, 300, 511, 513, 700, 1025]))
+        Skv = Sq + int(rng.choice([0, 0, 0, 1, 63, 64, 100, 300]))
+        cases.append((B, Hkv * G, Hkv, Sq, Skv, Skv + int(rng.choice([0, 8, 40])), int(rng.choice([64, 128])),
+                      bool(rng.integers(2))))
+    for _ in range(28):          # one query per sequence: every group size, caches around the 128 / 256-row range sizes
+        B = int(rng.choice([1, 2, 3, 8, 33, 70])); Hkv = int(rng.choice([1, 2, 4])); G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 16, 24, 32]))
+        Skv = int(rng.choice([1, 2, 16, 17, 127, 128, 129, 255, 256, 257, 511, 512, 513, 1000, 1500]))
+        cases.append((B, Hkv * G, Hkv, 1, Skv, Skv + int(rng.choice([0, 8, 64])), int(rng.choice([64, 128])), True))
+    return cases
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Skv,cap,dh,causal", _random_attn_cases())
+def test_attn_random_shapes(F, B, Hq, Hkv, Sq, Skv, cap, dh, causal):
+    """Seeded sweep over bf16 attention shapes: prompts with and without a longer key range, and
+    single queries over caches of every group size (grouped, multi-query, several blocks per KV
+    head), each against the oracle on the same inputs."""
+    q = I.normal(67, 0, "q", (B, Hq, Sq, dh), 1.0, bf16=True)
+    k = I.normal(67, 0, "k_cache", (B, Hkv, cap, dh), 1.0, bf16=True)
+    v = I.normal(67, 0, "v_cache", (B, Hkv, cap, dh), 1.0, bf16=True)
+    scale = 1.0 / math.sqrt(dh)
+    ref = O.attention(q, k[:, :, :Skv], v[:, :, :Skv], scale, causal)
+    out = torch.empty(B, Sq, Hq * dh, dtype=torch.bfloat16, device="cuda")
+    ws = F.workspace(F.forge_attn_fused_workspace_bytes(B, Hq, Hkv, Sq, Skv, dh, torch.bfloat16))
+    F.forge_attn_fused(dev(q, True), dev(k, True), dev(v, True), out, kv_len=Skv, scale=scale, causal=causal, workspace=ws)
+    torch.cuda.synchronize()
+    check(out, ref, True, "attention B%d Hq%d Hkv%d Sq%d Skv%d dh%d causal%d" % (B, Hq, Hkv, Sq, Skv, dh, causal))
+
+
 def test_attn_sharp_softmax(F):
     """Large score spread: one key dominates each row, the online rescaling must not lose it."""
     B, H, S, dh = 1, 2, 200, 64
