@@ -161,11 +161,17 @@ def test_gemm_many_tiles_per_block(F, M, N, K, act, use_b, use_r, ld):
     (40, 12296, 128, "swiglu", False, False, 0),       # gated, outputs not a multiple of 64
     (17, 50257, 128, "none", False, False, 50264),     # an LM head at decode size
     (64, 24576, 128, "gelu_erf", True, True, 0),
+    # a short reduction (K < 1024) is one k range whatever the number of weight rows
+    (8, 3072, 768, "gelu_tanh", True, False, 0),       # the GPT-2-small MLP up projection of a decode step
+    (64, 1001, 512, "none", True, True, 1008),
+    (1, 8, 64, "silu", False, False, 0),
+    (5, 704, 960, "swiglu", True, False, 0),
 ])
 def test_gemm_decode_sized_finishes_in_the_gemm(F, M, N, K, act, use_b, use_r, ld):
     """At most 64 rows against enough weight rows for one k range of 128-row blocks to cover the
-    chip: the weight-streaming kernel applies bias, activation and residual itself (no partial
-    planes, no reduce launch) and needs no workspace."""
+    chip, or a reduction short enough to be one k range anyway: the weight-streaming kernel applies
+    bias, activation and residual itself (no partial planes, no reduce launch) and needs no
+    workspace."""
     wn = 2 * N if act == "swiglu" else N
     ldy = ld or N
     x = I.normal(69, 0, "x", (M, K), 1.0, bf16=True)
